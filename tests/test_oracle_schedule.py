@@ -1,0 +1,139 @@
+"""Pins for the oracle's scheduler (Sec. IV-B.1) and depth statistics (Eq. 4): values the paper
+prints, closed forms, and the statements the paper makes in prose."""
+import itertools
+import pathlib
+
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import binding as ob
+
+GOLDEN = pathlib.Path(__file__).parent / "golden" / "table2_exit_layers.txt"
+
+
+def shape_with_layers(L):
+    return wl.TINY.shape.replace(n_layers=L)
+
+
+def run(L, e, K, phase, scope, nt, ns, n, off=0):
+    sched = wl.Schedule(e, K, phase, scope, nt, ns)
+    return ob.schedule_run(shape_with_layers(L), sched, n, off)
+
+
+def golden_rows():
+    rows = []
+    for line in GOLDEN.read_text().splitlines():
+        if not line.strip() or line.startswith("#"):
+            continue
+        f = line.split()
+        rows.append((f[0], *map(int, f[1:7]), float(f[7]), float(f[8]), float(f[9])))
+    return rows
+
+
+@pytest.mark.parametrize("row", golden_rows(), ids=lambda r: r[0])
+def test_table2_exit_layer_column(row):
+    name, L, e, K, phase, nt, ns, mean_depth, saving, tol = row
+    cycles = 50
+    depth, is_text = run(L, e, K, phase, wl.SCOPE_CHUNK, nt, ns, cycles * (nt + ns))
+    speech = depth[is_text == 0]
+    assert len(speech) == cycles * ns
+    assert abs(speech.mean() - mean_depth) <= tol, (name, speech.mean())
+    # text column of the table: full depth at every text position
+    assert np.all(depth[is_text == 1] == L)
+    got_saving = ob.layer_saving(speech, L)
+    assert abs(got_saving - saving) <= 0.5 + 1e-9 + 100 * tol / L, (name, got_saving)
+
+
+def test_named_schedules_patterns():
+    """Even / Odd / Triple as spelled out in Sec. IV-B.1, on Step-Audio-2's 4-slot chunk:
+    each has two full-depth and two early-exit positions (discussion of schedule variants)."""
+    L, e = 28, 22
+    pats = {(2, 0): [L, e, L, e], (2, 1): [e, L, e, L], (3, 0): [L, e, e, L]}
+    for (K, phase), want in pats.items():
+        depth, is_text = run(L, e, K, phase, wl.SCOPE_CHUNK, 1, 4, 15)
+        for c in range(3):
+            assert is_text[5 * c] == 1 and depth[5 * c] == L
+            assert list(depth[5 * c + 1:5 * c + 5]) == want
+            assert list(is_text[5 * c + 1:5 * c + 5]) == [0] * 4
+
+
+def full_count_closed_form(n_slots, K, phase):
+    """number of j in [0, n_slots) with j mod K == phase"""
+    return (n_slots - 1 - phase) // K + 1 if n_slots > phase else 0
+
+
+@pytest.mark.parametrize("scope", [wl.SCOPE_CHUNK, wl.SCOPE_STREAM])
+def test_full_slot_count_closed_form(scope):
+    L, e = 12, 5
+    for K, nt, ns in itertools.product([1, 2, 3, 4, 5, 8], [0, 1, 3], [1, 2, 4, 7, 26]):
+        for phase in range(K):
+            n = 6 * (nt + ns)
+            res = run(L, e, K, phase, scope, nt, ns, n)
+            if res is None:  # refused: a pure-speech cycle that never reaches a full-depth slot
+                assert nt == 0 and scope == wl.SCOPE_CHUNK and K > 1 and phase >= ns
+                continue
+            depth, is_text = res
+            n_speech = int((is_text == 0).sum())
+            assert n_speech == 6 * ns
+            n_full = int(((is_text == 0) & (depth == L)).sum())
+            if K == 1:
+                assert n_full == n_speech
+            elif scope == wl.SCOPE_CHUNK:
+                assert n_full == 6 * full_count_closed_form(ns, K, phase)
+            else:
+                assert n_full == full_count_closed_form(n_speech, K, phase)
+            assert set(np.unique(depth)) <= {e, L}
+            assert np.all(depth[is_text == 1] == L)
+
+
+@pytest.mark.parametrize("L,e,K", [(28, 20, 4), (40, 32, 4), (4, 2, 4), (28, 14, 2), (28, 24, 8)])
+def test_stream_scope_mean_speech_depth(L, e, K):
+    """every K-th speech position is a refresh => mean speech depth ((K-1)e + L)/K over any
+    whole number of periods"""
+    for nt, ns in [(1, 2), (13, 26), (2, 4), (0, 5)]:
+        for phase in (0, K - 1):
+            n_cycles = 3 * K
+            depth, is_text = run(L, e, K, phase, wl.SCOPE_STREAM, nt, ns, n_cycles * (nt + ns))
+            speech = depth[is_text == 0]
+            assert len(speech) % K == 0
+            assert speech.mean() == pytest.approx(((K - 1) * e + L) / K, abs=1e-12)
+            assert ob.layer_saving(speech, L) == pytest.approx(
+                (1 - ((K - 1) * e + L) / K / L) * 100, abs=1e-9)
+
+
+def test_degenerate_configs_are_full_depth():
+    for L, e, K in [(28, 28, 4), (28, 20, 1), (4, 4, 1)]:
+        depth, _ = run(L, e, K, 0, wl.SCOPE_STREAM, 1, 2, 60)
+        assert np.all(depth == L)
+
+
+def test_cycle_offset_shifts_the_pattern():
+    L, e, K, nt, ns = 28, 22, 2, 1, 4
+    base_d, base_t = run(L, e, K, 0, wl.SCOPE_CHUNK, nt, ns, 40)
+    for off in range(1, 5):
+        d, t = run(L, e, K, 0, wl.SCOPE_CHUNK, nt, ns, 30, off)
+        assert list(d) == list(base_d[off:off + 30])
+        assert list(t) == list(base_t[off:off + 30])
+
+
+def test_layer_saving_formula():
+    # Eq. 4 on hand-made logs
+    assert ob.layer_saving(np.array([28, 22, 28, 22]), 28) == pytest.approx((1 - 25 / 28) * 100)
+    assert ob.layer_saving(np.array([40] * 7), 40) == 0.0
+    assert ob.layer_saving(np.array([10]), 40) == pytest.approx(75.0)
+    # benchmark workloads: tiny (whole chunks) 37.5 %, Step shape 21.43 %, GLM shape 15 %
+    for w, want in [(wl.TINY, 37.5), (wl.STEP_AUDIO_2_MINI, (1 - 22 / 28) * 100),
+                    (wl.GLM_4_VOICE, 15.0)]:
+        s = w.schedule
+        n = 4 * s.period_k * (s.n_text + s.n_speech)
+        depth, is_text = ob.schedule_run(w.shape, s, n)
+        assert ob.layer_saving(depth[is_text == 0], w.shape.n_layers) == pytest.approx(want)
+
+
+def test_refused_configs():
+    bad = [dict(exit_layer=0), dict(exit_layer=5), dict(period_k=0), dict(phase=4), dict(phase=-1),
+           dict(scope=2), dict(n_text=0, n_speech=0), dict(n_text=-1)]
+    for kw in bad:
+        s = wl.TINY.schedule.replace(**kw)
+        assert ob.schedule_run(wl.TINY.shape, s, 8) is None, kw
