@@ -1,0 +1,185 @@
+/*
+ * spark.h -- C ABI of the MI355X (gfx950) SPAR-K decoding library.
+ *
+ * SPAR-K (scheduled periodic alternating early exit) decodes an interleaved text/speech token
+ * stream with a depth schedule: text positions run all L layers; inside every speech chunk the
+ * positions are cut into periods of K, one fixed slot of each period runs all L layers (a
+ * "refresh") and the other K-1 exit at layer e and are decoded by a layer-specific head g_e
+ * (Sec. IV-B.1, IV-B.2).  The upper-layer KV of early-exited positions is not computed when they
+ * exit: their hidden state h^(e) is kept, and the next full-depth step pushes them, together with
+ * its own position, through layers e+1..L in one batched pass (Sec. IV-B.3, Algorithm 1).
+ *
+ * All compute runs in HIP kernels on the stream given to spark_init.  Pointers marked [device]
+ * are device memory owned by the caller and must outlive the context; pointers marked [host] are
+ * ordinary host memory.  Every call returns SPARK_OK or a negative SPARK_E* code; nothing throws
+ * and there is no global state.  A context is not thread-safe.
+ */
+#ifndef SPARK_H
+#define SPARK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPARK_OK 0
+#define SPARK_EINVAL (-1)  /* bad dimension, e outside [1,L], K < 1, phase outside [0,K), bad id */
+#define SPARK_ENOSEQ (-2)  /* unknown / closed sequence id, or no free sequence slot */
+#define SPARK_ENOMEM (-3)  /* KV pool exhausted, context longer than max_seq_len, buffer too small */
+#define SPARK_ESTATE (-4)  /* step before prefill, second prefill on a live sequence */
+#define SPARK_EHIP (-5)    /* a HIP runtime call failed; see spark_last_error */
+#define SPARK_ENAN (-6)    /* a head produced a NaN logit */
+
+#define SPARK_DTYPE_FP32 0
+#define SPARK_DTYPE_BF16 1
+
+#define SPARK_SCOPE_CHUNK 0  /* period counter restarts at every speech chunk (Sec. IV-B.1) */
+#define SPARK_SCOPE_STREAM 1 /* period counter runs over all speech positions of the sequence */
+
+#define SPARK_MAX_PERIOD 16  /* largest supported K */
+
+/* Model dimensions and schedule.  Plain data; `size` must be sizeof(spark_config). */
+typedef struct spark_config {
+  uint32_t size;
+  int32_t n_layers;      /* L */
+  int32_t d_model;       /* d, multiple of 8 */
+  int32_t n_q_heads;     /* multiple of n_kv_heads */
+  int32_t n_kv_heads;
+  int32_t head_dim;      /* 64 or 128 */
+  int32_t d_ffn;         /* SwiGLU width F, multiple of 8 */
+  int32_t vocab_text;    /* ids [0, vocab_text) are text */
+  int32_t vocab_speech;  /* ids [vocab_text, vocab_text + vocab_speech) are speech */
+  float rope_base;       /* rotary base, angle = pos * base^(-2i/head_dim) on pairs (i, i+hd/2) */
+  float rms_eps;
+  int32_t dtype;         /* SPARK_DTYPE_*: element type of every matrix and of the KV cache */
+  int32_t exit_layer;    /* e in [1, L]; e == L disables early exit (Sec. III, IV-B.1) */
+  int32_t period_k;      /* K in [1, SPARK_MAX_PERIOD]; K == 1 disables early exit */
+  int32_t phase;         /* in [0, K): slot of the full-depth position inside each period */
+  int32_t scope;         /* SPARK_SCOPE_* */
+  int32_t n_text;        /* interleave pattern: n_text text slots, then n_speech speech slots */
+  int32_t n_speech;
+  int32_t max_batch;     /* sequences that may be open / stepped together */
+  int32_t max_seq_len;   /* longest context (prompt + generated) of one sequence */
+  int32_t kv_page_tokens;/* tokens per KV page, multiple of 16 */
+} spark_config;
+
+/* Weights [device].  Matrices are row-major [out][in] in `dtype`; gains and lens_b are fp32.
+ * Per-layer tensors are stacked along a leading layer axis.  The layer-specific head is
+ * g_e(h) = lens_head . RMSNorm(h + lens_a h + lens_b ; lens_norm)  (Sec. IV-B.2, Eq. 2);
+ * the final head is g_L(h) = lm_head . RMSNorm(h ; final_norm)  (Sec. III, Eq. 1). */
+typedef struct spark_weights {
+  const void *embed;       /* [V][d] */
+  const float *attn_norm;  /* [L][d] */
+  const void *wq;          /* [L][n_q_heads*head_dim][d] */
+  const void *wk;          /* [L][n_kv_heads*head_dim][d] */
+  const void *wv;          /* [L][n_kv_heads*head_dim][d] */
+  const void *wo;          /* [L][d][n_q_heads*head_dim] */
+  const float *mlp_norm;   /* [L][d] */
+  const void *wg;          /* [L][F][d] */
+  const void *wu;          /* [L][F][d] */
+  const void *wd;          /* [L][d][F] */
+  const float *final_norm; /* [d] */
+  const void *lm_head;     /* [V][d] */
+  const void *lens_a;      /* [d][d] */
+  const float *lens_b;     /* [d] */
+  const float *lens_norm;  /* [d] */
+  const void *lens_head;   /* [V][d]; may alias lm_head */
+} spark_weights;
+
+/* Exit-layer log of one sequence (Sec. V-A "Metrics", Eq. 4). */
+typedef struct spark_stats {
+  int64_t text_steps;        /* text positions decoded (always depth L) */
+  int64_t speech_full_steps; /* speech positions decoded at depth L */
+  int64_t speech_ee_steps;   /* speech positions decoded at depth e */
+  int64_t flush_rows[2 * SPARK_MAX_PERIOD]; /* [m]: full-depth steps that pushed m rows through
+                                               layers e+1..L (pending positions + their own) */
+  double mean_text_depth;    /* average exit layer over text positions (0 if none) */
+  double mean_speech_depth;  /* average exit layer over speech positions (0 if none) */
+  double speech_layer_saving;/* (1 - mean_speech_depth / L) * 100, Eq. 4 (0 if none) */
+} spark_stats;
+
+typedef struct spark_ctx spark_ctx;
+
+/* Sizes of the two device buffers the caller must provide for this configuration: the paged KV
+ * pool (every sequence at max_seq_len) and the scratch area (activations, schedule state, logits).
+ * Returns SPARK_EINVAL for a configuration the library refuses. */
+int spark_workspace_bytes(const spark_config *cfg, size_t *kv_pool_bytes, size_t *scratch_bytes);
+
+/* Create a context.  kv_pool and scratch [device] must be at least the sizes reported above and
+ * 256-byte aligned; hip_stream is a hipStream_t (NULL = the default stream) on which every kernel
+ * of this context is launched.  The weights struct is copied; the tensors are not. */
+int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_pool,
+               size_t kv_pool_bytes, void *scratch, size_t scratch_bytes, void *hip_stream,
+               spark_ctx **out);
+
+/* Open a sequence.  cycle_offset >= 0 is the slot of the interleave cycle at which the first
+ * generated token falls (0 = first text slot).  Writes the id to *seq_id. */
+int spark_seq_open(spark_ctx *ctx, int32_t cycle_offset, int32_t *seq_id);
+
+/* Condition on a prompt [host] of n >= 1 ids: positions 0..n-2 are run at full depth and fill
+ * the KV of every layer; the last id is held as the input of the first spark_step, so that every
+ * generated token comes out of spark_step with its executed depth.  One prompt per sequence. */
+int spark_prefill(spark_ctx *ctx, int32_t seq_id, const int32_t *prompt, int32_t n);
+
+/* One decoding step for n distinct prefilled sequences seq_ids[0..n) [host] (Algorithm 1).
+ * For each: the schedule decides early exit or full depth; layers 1..e run on the new position;
+ * an early-exit position is decoded by g_e and its h^(e) kept pending; a full-depth position
+ * takes the pending positions with it through layers e+1..L and is decoded by g_L.
+ * out_tokens[i], out_depth[i] [host]: emitted id (greedy, lowest id on ties) and executed depth
+ * (e or L).  forced_next [host, nullable]: if forced_next[i] >= 0 it becomes the next input of
+ * sequence i in place of the emitted id (teacher forcing); the emitted id is still reported.
+ * Returns after the results are on the host. */
+int spark_step(spark_ctx *ctx, int32_t n, const int32_t *seq_ids, const int32_t *forced_next,
+               int32_t *out_tokens, int32_t *out_depth);
+
+/* n_steps consecutive steps of the same n sequences without returning to the host in between:
+ * the emitted id (or forced_next[s*n + i] when given and >= 0) feeds the next step on the device.
+ * out_tokens / out_depth [host] are [n_steps][n].  Same results as n_steps calls of spark_step. */
+int spark_decode(spark_ctx *ctx, int32_t n_steps, int32_t n, const int32_t *seq_ids,
+                 const int32_t *forced_next, int32_t *out_tokens, int32_t *out_depth);
+
+/* Logits [host, V floats] of the head that decoded the sequence's latest position, and which head
+ * it was (*head = e or L). */
+int spark_get_logits(spark_ctx *ctx, int32_t seq_id, float *out_logits, int32_t *head);
+
+/* Copy one position's cached key and value vectors (n_kv_heads*head_dim floats each) of one layer
+ * (0-based) to the host; for tests of the deferred KV fill. */
+int spark_get_kv(spark_ctx *ctx, int32_t seq_id, int32_t layer, int32_t pos, float *k_out,
+                 float *v_out);
+
+/* Current context length, number of positions whose upper-layer KV is complete, and number of
+ * pending early-exited positions of a sequence (any pointer may be NULL). */
+int spark_seq_state(spark_ctx *ctx, int32_t seq_id, int32_t *len, int32_t *upper_valid,
+                    int32_t *n_pending);
+
+int spark_get_stats(spark_ctx *ctx, int32_t seq_id, spark_stats *out);
+
+/* Release a sequence and its KV pages. */
+int spark_seq_close(spark_ctx *ctx, int32_t seq_id);
+
+void spark_destroy(spark_ctx *ctx);
+
+/* Text of the last error of this context (never NULL; valid until the next call on ctx). */
+const char *spark_last_error(const spark_ctx *ctx);
+
+/* Measurement support.  While `kernel_class` is >= 0, every launch of that class of kernel during
+ * spark_step / spark_decode is bracketed by HIP events on the context's stream;
+ * spark_profile_read waits for them and reports the number of bracketed launches and their summed
+ * duration in milliseconds since the last read.  Classes: see SPARK_KC_*.  -1 switches it off. */
+#define SPARK_KC_QKV 0
+#define SPARK_KC_ATTN 1
+#define SPARK_KC_OPROJ 2
+#define SPARK_KC_GATEUP 3
+#define SPARK_KC_DOWN 4
+#define SPARK_KC_LENS 5
+#define SPARK_KC_HEAD 6
+#define SPARK_KC_COUNT 7
+int spark_profile_select(spark_ctx *ctx, int32_t kernel_class);
+int spark_profile_read(spark_ctx *ctx, int64_t *n_launches, double *total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARK_H */

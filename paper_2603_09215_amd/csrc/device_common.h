@@ -1,0 +1,91 @@
+// Shared device-side types and helpers of the SPAR-K HIP library (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace spark {
+
+typedef uint16_t bf16_t;  // bf16 bit pattern
+
+// One activation row of a pass through a range of layers.
+struct RowDesc {
+  int x_slot;   // row of the hidden-state arena that holds this row's residual stream
+  int seq;      // sequence slot (selects the page table)
+  int pos;      // absolute position in the sequence (RoPE angle, KV slot, causal limit)
+  int out_idx;  // row of per-step outputs (logits, argmax) this row reports to, or -1
+};
+
+// Paged KV cache: pool[page][layer][k|v][kv_head][token_in_page][head_dim]
+struct KVView {
+  void *pool;
+  const int *page_table;  // [seq][max_pages] -> physical page
+  int max_pages;
+  int n_layers, n_kv_heads, page_tokens, head_dim;
+};
+
+__device__ __forceinline__ size_t kv_elem_offset(const KVView &kv, int seq, int pos, int layer,
+                                                 int which, int head) {
+  int page = kv.page_table[seq * kv.max_pages + pos / kv.page_tokens];
+  size_t o = (size_t)page * kv.n_layers + layer;
+  o = (o * 2 + which) * kv.n_kv_heads + head;
+  o = o * kv.page_tokens + pos % kv.page_tokens;
+  return o * kv.head_dim;
+}
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) {
+  return __uint_as_float((uint32_t)b << 16);
+}
+
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static constexpr int VEC = 4;  // elements per 16-byte load
+  __device__ static __forceinline__ float widen(float v) { return v; }
+  __device__ static __forceinline__ float narrow(float v) { return v; }
+  __device__ static __forceinline__ void unpack(const uint4 &r, float *f) {
+    f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
+    f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+  }
+};
+template <> struct Elem<bf16_t> {
+  static constexpr int VEC = 8;
+  __device__ static __forceinline__ float widen(bf16_t v) { return bf16_to_f32(v); }
+  __device__ static __forceinline__ bf16_t narrow(float v) { return f32_to_bf16(v); }
+  __device__ static __forceinline__ void unpack(const uint4 &r, float *f) {
+    f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
+    f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
+    f[4] = __uint_as_float(r.z << 16); f[5] = __uint_as_float(r.z & 0xffff0000u);
+    f[6] = __uint_as_float(r.w << 16); f[7] = __uint_as_float(r.w & 0xffff0000u);
+  }
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// Order-preserving map float -> uint32 (larger float => larger key; every NaN above +inf).
+__device__ __forceinline__ uint32_t float_order_key(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0xffffffffu;
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+// 64-bit argmax key: larger logit wins, then the lower index.
+__device__ __forceinline__ unsigned long long argmax_key(float logit, int idx) {
+  return ((unsigned long long)float_order_key(logit) << 32) | (uint32_t)(0xffffffffu - (uint32_t)idx);
+}
+
+}  // namespace spark

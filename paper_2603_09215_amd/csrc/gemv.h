@@ -1,0 +1,333 @@
+// Weight-streaming projection kernel for a handful of activation rows (decode, flush).
+//
+// Small-batch decoding is bound by reading each layer's weights from HBM (Sec. IV-B.3, second
+// paragraph), so the kernel is organised around the weight stream: every wave owns pairs of weight
+// rows and walks them with 16-byte loads, 1 KiB per wave per instruction; the (few) activation
+// rows sit in LDS as fp32 and are reused by every weight row; partial sums are combined with wave
+// shuffles.  Up to MT activation rows share one pass over the weights, which is what makes the
+// deferred completion of pending positions cost about one full-depth pass.
+#pragma once
+#include "device_common.h"
+
+namespace spark {
+
+constexpr int GEMV_THREADS = 256;
+constexpr int GEMV_WAVES = GEMV_THREADS / 64;
+
+// LDS position of activation element k (multiple of 4) of a row.  With 8 weights per lane and
+// load, a lane needs x[8*lane .. 8*lane+8); storing the two float4 halves 256 floats apart makes
+// consecutive lanes read consecutive 16-byte words (no bank conflicts).
+template <int VEC> __device__ __forceinline__ int lds_pos(int k) {
+  if (VEC == 8) return (k & ~511) + ((k >> 2) & 1) * 256 + ((k & 511) >> 3) * 4;
+  return k;
+}
+
+// ------------------------------------------------------------------ prologues (fill LDS)
+
+// rows come straight from a buffer: row r of the pass, or the row's hidden-state slot
+struct ProPlain {
+  const float *src;
+  int stride;
+  int indirect;  // 1: src row = x_slot of the row descriptor; 0: src row = pass row index
+  template <int VEC, int MT>
+  __device__ void stage(float *xs, int kc, const RowDesc *rd, int tile0, int n_valid, int k0,
+                        int klen, float *red) const {
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+      int mm = m < n_valid ? m : n_valid - 1;
+      const float *row = src + (size_t)(indirect ? rd[mm].x_slot : tile0 + mm) * stride + k0;
+      for (int k = threadIdx.x * 4; k < klen; k += GEMV_THREADS * 4)
+        *(float4 *)(xs + m * kc + lds_pos<VEC>(k)) = *(const float4 *)(row + k);
+    }
+  }
+};
+
+// rows are RMSNorm(hidden[x_slot]; gamma): x / sqrt(mean x^2 + eps) * gamma  (whole row at once)
+struct ProNorm {
+  const float *hidden;
+  const float *gamma;
+  float eps;
+  int d;
+  int indirect;  // 1: row = x_slot of the row descriptor; 0: row = pass row index
+  template <int VEC, int MT>
+  __device__ void stage(float *xs, int kc, const RowDesc *rd, int tile0, int n_valid, int k0,
+                        int klen, float *red) const {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+      int mm = m < n_valid ? m : n_valid - 1;
+      const float *row = hidden + (size_t)(indirect ? rd[mm].x_slot : tile0 + mm) * d;
+      float ss = 0.f;
+      for (int k = threadIdx.x * 4; k < d; k += GEMV_THREADS * 4) {
+        float4 v = *(const float4 *)(row + k);
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+      }
+      ss = wave_sum(ss);
+      if (lane == 0) red[wave * MT + m] = ss;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+      int mm = m < n_valid ? m : n_valid - 1;
+      const float *row = hidden + (size_t)(indirect ? rd[mm].x_slot : tile0 + mm) * d;
+      float tot = 0.f;
+#pragma unroll
+      for (int w = 0; w < GEMV_WAVES; ++w) tot += red[w * MT + m];
+      float inv = 1.0f / sqrtf(tot / (float)d + eps);
+      for (int k = threadIdx.x * 4; k < d; k += GEMV_THREADS * 4) {
+        float4 v = *(const float4 *)(row + k);
+        float4 g = *(const float4 *)(gamma + k);
+        float4 o = make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w);
+        *(float4 *)(xs + m * kc + lds_pos<VEC>(k)) = o;
+      }
+    }
+  }
+};
+
+// ------------------------------------------------------------------ epilogues
+// Each wave task owns two weight rows; after the reduction lane m finishes activation row m.
+
+struct NoState {};
+
+// q, k, v projection + rotary embedding + KV-cache write.  Task t -> head t / (hd/2), pair index
+// i = t % (hd/2): weight rows (head*hd + i) and (head*hd + i + hd/2), the two elements that the
+// rotary embedding mixes.  Heads [0,nq) are queries, [nq,nq+nkv) keys, the rest values.
+template <typename WT> struct EpiQKV {
+  typedef NoState State;
+  const WT *wq, *wk, *wv;  // this layer
+  int d, nq, nkv, hd, layer;
+  float *qbuf;             // [pass row][nq*hd], rotated queries
+  const float2 *rope;      // [pos][hd/2] (cos, sin)
+  KVView kv;
+  __device__ void init(State &) const {}
+  __device__ void weight_rows(int task, const WT *&r0, const WT *&r1) const {
+    int half = hd >> 1, head = task / half, i = task - head * half;
+    const WT *base;
+    int h = head;
+    if (h < nq) base = wq;
+    else if (h < nq + nkv) { base = wk; h -= nq; }
+    else { base = wv; h -= nq + nkv; }
+    r0 = base + (size_t)(h * hd + i) * d;
+    r1 = r0 + (size_t)half * d;
+  }
+  __device__ void finish(int task, int r, const RowDesc &rd, float y0, float y1, State &) const {
+    int half = hd >> 1, head = task / half, i = task - head * half;
+    if (head < nq + nkv) {
+      float2 cs = rope[(size_t)rd.pos * half + i];
+      float a = y0 * cs.x - y1 * cs.y, b = y1 * cs.x + y0 * cs.y;
+      y0 = a; y1 = b;
+    }
+    if (head < nq) {
+      float *q = qbuf + (size_t)r * nq * hd + head * hd + i;
+      q[0] = y0; q[half] = y1;
+    } else {
+      int which = head < nq + nkv ? 0 : 1;
+      int h = head - nq - which * nkv;
+      WT *dst = (WT *)kv.pool + kv_elem_offset(kv, rd.seq, rd.pos, layer, which, h) + i;
+      dst[0] = Elem<WT>::narrow(y0);
+      dst[half] = Elem<WT>::narrow(y1);
+    }
+  }
+  __device__ void end(int, const RowDesc &, State &) const {}
+};
+
+// hidden[x_slot][i] += y  (attention output projection, MLP down projection)
+template <typename WT> struct EpiResidual {
+  typedef NoState State;
+  const WT *w;
+  int n_in, n_out;
+  float *hidden;
+  int d;
+  __device__ void init(State &) const {}
+  __device__ void weight_rows(int task, const WT *&r0, const WT *&r1) const {
+    r0 = w + (size_t)(2 * task) * n_in;
+    r1 = r0 + n_in;
+  }
+  __device__ void finish(int task, int r, const RowDesc &rd, float y0, float y1, State &) const {
+    float2 *h = (float2 *)(hidden + (size_t)rd.x_slot * d + 2 * task);
+    float2 v = *h;
+    v.x += y0; v.y += y1;
+    *h = v;
+  }
+  __device__ void end(int, const RowDesc &, State &) const {}
+};
+
+// act[r][i] = silu(Wg_i . n) * (Wu_i . n)
+template <typename WT> struct EpiSwiGLU {
+  typedef NoState State;
+  const WT *wg, *wu;
+  int d, F;
+  float *act;  // [pass row][F]
+  __device__ void init(State &) const {}
+  __device__ void weight_rows(int task, const WT *&r0, const WT *&r1) const {
+    r0 = wg + (size_t)task * d;
+    r1 = wu + (size_t)task * d;
+  }
+  __device__ void finish(int task, int r, const RowDesc &, float y0, float y1, State &) const {
+    float s = y0 / (1.0f + expf(-y0));
+    act[(size_t)r * F + task] = s * y1;
+  }
+  __device__ void end(int, const RowDesc &, State &) const {}
+};
+
+// u[r][i] = h[i] + (A h)[i] + b[i]   (translator of the layer-specific head)
+template <typename WT> struct EpiLensAffine {
+  typedef NoState State;
+  const WT *a;
+  const float *b;
+  const float *hidden;
+  float *u;  // [pass row][d]
+  int d;
+  __device__ void init(State &) const {}
+  __device__ void weight_rows(int task, const WT *&r0, const WT *&r1) const {
+    r0 = a + (size_t)(2 * task) * d;
+    r1 = r0 + d;
+  }
+  __device__ void finish(int task, int r, const RowDesc &rd, float y0, float y1, State &) const {
+    const float *h = hidden + (size_t)rd.x_slot * d + 2 * task;
+    float2 o = make_float2(h[0] + y0 + b[2 * task], h[1] + y1 + b[2 * task + 1]);
+    *(float2 *)(u + (size_t)r * d + 2 * task) = o;
+  }
+  __device__ void end(int, const RowDesc &, State &) const {}
+};
+
+// logits[out_idx][i] = y, and a running (max logit, lowest index) per activation row; one 64-bit
+// atomic max per wave and row at the end makes the result independent of the order of arrival.
+template <typename WT> struct EpiVocab {
+  struct State { unsigned long long best; };
+  const WT *w;
+  int d, V;
+  float *logits;               // [out_idx][V]
+  unsigned long long *best;    // [out_idx]
+  __device__ void init(State &s) const { s.best = 0ull; }
+  __device__ void weight_rows(int task, const WT *&r0, const WT *&r1) const {
+    int i1 = 2 * task + 1 < V ? 2 * task + 1 : 2 * task;
+    r0 = w + (size_t)(2 * task) * d;
+    r1 = w + (size_t)i1 * d;
+  }
+  __device__ void finish(int task, int r, const RowDesc &rd, float y0, float y1, State &s) const {
+    float *lg = logits + (size_t)rd.out_idx * V;
+    int i0 = 2 * task;
+    lg[i0] = y0;
+    unsigned long long k = argmax_key(y0, i0);
+    if (k > s.best) s.best = k;
+    if (i0 + 1 < V) {
+      lg[i0 + 1] = y1;
+      k = argmax_key(y1, i0 + 1);
+      if (k > s.best) s.best = k;
+    }
+  }
+  __device__ void end(int r, const RowDesc &rd, State &s) const {
+    if (s.best) atomicMax(best + rd.out_idx, s.best);
+  }
+};
+
+// ------------------------------------------------------------------ the kernel
+
+template <typename WT, int MT>
+__device__ __forceinline__ void fma_block(const uint4 &a, const uint4 &b, const float *xs, int kc,
+                                          int kb, int lane, float *acc0, float *acc1) {
+  constexpr int VEC = Elem<WT>::VEC;
+  float wa[VEC], wb[VEC];
+  Elem<WT>::unpack(a, wa);
+  Elem<WT>::unpack(b, wb);
+#pragma unroll
+  for (int m = 0; m < MT; ++m) {
+    const float *xm = xs + m * kc + kb + lane * 4;
+    float4 x0 = *(const float4 *)xm;
+    acc0[m] += wa[0] * x0.x + wa[1] * x0.y + wa[2] * x0.z + wa[3] * x0.w;
+    acc1[m] += wb[0] * x0.x + wb[1] * x0.y + wb[2] * x0.z + wb[3] * x0.w;
+    if (VEC == 8) {
+      float4 x1 = *(const float4 *)(xm + 256);
+      acc0[m] += wa[4] * x1.x + wa[5] * x1.y + wa[6] * x1.z + wa[7] * x1.w;
+      acc1[m] += wb[4] * x1.x + wb[5] * x1.y + wb[6] * x1.z + wb[7] * x1.w;
+    }
+  }
+}
+
+// grid.x: blocks that share the weight rows; grid.y: tiles of MT activation rows.
+// kc: activation elements of one row held in LDS at a time (multiple of 512).
+// Dynamic LDS: (MT*kc + GEMV_WAVES*MT) floats.
+template <typename WT, int MT, typename Pro, typename Epi>
+__global__ void __launch_bounds__(GEMV_THREADS)
+gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int n_in, int n_tasks,
+            int kc) {
+  extern __shared__ float4 smem4[];
+  float *xs = (float *)smem4;          // [MT][kc] activations
+  float *red = xs + MT * kc;           // [GEMV_WAVES][MT] partial sums of squares
+  constexpr int VEC = Elem<WT>::VEC;
+  constexpr int WSTEP = 64 * VEC;
+  constexpr int U = 4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int tile0 = blockIdx.y * MT;
+  const int n_valid = min(MT, m_rows - tile0);
+  if (n_valid <= 0) return;
+  RowDesc rd[MT];
+#pragma unroll
+  for (int m = 0; m < MT; ++m) rd[m] = rows[tile0 + (m < n_valid ? m : n_valid - 1)];
+
+  const int n_chunks = (n_in + kc - 1) / kc;
+  const int n_waves = gridDim.x * GEMV_WAVES, wave_global = blockIdx.x * GEMV_WAVES + wave;
+  const int rounds = (n_tasks + n_waves - 1) / n_waves;
+  typename Epi::State st;
+  epi.init(st);
+
+  for (int round = 0; round < rounds; ++round) {
+    const int task = round * n_waves + wave_global;
+    const bool valid = task < n_tasks;
+    const WT *r0, *r1;
+    epi.weight_rows(valid ? task : 0, r0, r1);
+    float acc0[MT], acc1[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) acc0[m] = acc1[m] = 0.f;
+
+    for (int chunk = 0; chunk < n_chunks; ++chunk) {
+      const int k0 = chunk * kc, klen = min(kc, n_in - k0);
+      if (round == 0 || n_chunks > 1) {
+        __syncthreads();
+        pro.template stage<VEC, MT>(xs, kc, rd, tile0, n_valid, k0, klen, red);
+        __syncthreads();
+      }
+      if (valid) {
+        const WT *p0 = r0 + k0 + lane * VEC, *p1 = r1 + k0 + lane * VEC;
+        int kb = 0;
+        for (; kb + U * WSTEP <= klen; kb += U * WSTEP) {
+          uint4 a[U], b[U];
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            a[u] = *(const uint4 *)(p0 + kb + u * WSTEP);
+            b[u] = *(const uint4 *)(p1 + kb + u * WSTEP);
+          }
+#pragma unroll
+          for (int u = 0; u < U; ++u)
+            fma_block<WT, MT>(a[u], b[u], xs, kc, kb + u * WSTEP, lane, acc0, acc1);
+        }
+        for (; kb < klen; kb += WSTEP) {
+          if (kb + lane * VEC < klen) {
+            uint4 a = *(const uint4 *)(p0 + kb), b = *(const uint4 *)(p1 + kb);
+            fma_block<WT, MT>(a, b, xs, kc, kb, lane, acc0, acc1);
+          }
+        }
+      }
+    }
+    if (valid) {
+      float y0 = 0.f, y1 = 0.f;
+      RowDesc mine = rd[0];
+#pragma unroll
+      for (int m = 0; m < MT; ++m) {
+        float s0 = wave_sum(acc0[m]), s1 = wave_sum(acc1[m]);
+        if (lane == m) { y0 = s0; y1 = s1; mine = rd[m]; }
+      }
+      if (lane < n_valid) epi.finish(task, tile0 + lane, mine, y0, y1, st);
+    }
+  }
+  if (lane < n_valid) {
+    RowDesc mine = rd[0];
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+      if (lane == m) mine = rd[m];
+    epi.end(tile0 + lane, mine, st);
+  }
+}
+
+}  // namespace spark

@@ -1,0 +1,776 @@
+// Host side of the SPAR-K decoding library: context, sequence bookkeeping, kernel launches and
+// the C ABI declared in include/spark.h.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <type_traits>
+#include <vector>
+
+#include "../../include/spark.h"
+#include "attention.h"
+#include "device_common.h"
+#include "gemv.h"
+#include "sched.h"
+
+using namespace spark;
+
+namespace {
+
+constexpr int PREFILL_CHUNK = 64;    // prompt rows pushed through the layers together
+constexpr int MAX_STEPS_PER_CALL = 256;
+constexpr int MAX_SPLITS = 64;
+
+struct Layout {  // byte offsets into the scratch buffer
+  size_t state, page_table, plan, lower, upper, ee, full, prefill_rows, prefill_tokens, seq_ids,
+      forced, step_flags, out_tokens, out_depth, best, hidden, qbuf, attn_out, part, act, lens_u,
+      logits, rope, inv_freq, total;
+};
+
+struct Derived {
+  int V, rmax, max_rows, max_pages, n_pages_total, slice, n_splits, group, esz;
+  size_t page_elems, kv_pool_bytes;
+};
+
+struct Seq {
+  bool open = false, prefilled = false;
+  int cycle_offset = 0, len = 0, g = 0, j_stream = 0, n_pending = 0, last_full = 0;
+  std::vector<int> pages;
+  int64_t text_steps = 0, speech_full = 0, speech_ee = 0;
+  int64_t flush_rows[2 * SPARK_MAX_PERIOD] = {0};
+};
+
+}  // namespace
+
+struct spark_ctx {
+  spark_config cfg;
+  spark_weights w;
+  Derived dv;
+  Layout lo;
+  SchedParams sp;
+  hipStream_t stream;
+  char *scratch;
+  void *kv_pool;
+  int n_cu;
+  std::vector<Seq> seqs;
+  std::vector<int> free_pages;
+  int *h_in;   // pinned: seq_ids[max_batch] + forced[MAX_STEPS][max_batch]
+  int *h_out;  // pinned: tokens[MAX_STEPS][max_batch] + depth[...] + plan[PL_WORDS]
+  char err[512];
+  // profiling of one kernel class
+  int prof_class = -1;
+  std::vector<hipEvent_t> prof_ev;
+  size_t prof_used = 0;
+};
+
+namespace {
+
+int fail(spark_ctx *c, int code, const char *fmt, ...) {
+  if (c) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(c->err, sizeof(c->err), fmt, ap);
+    va_end(ap);
+  }
+  return code;
+}
+
+#define HIP_TRY(ctx, call)                                                                  \
+  do {                                                                                      \
+    hipError_t e_ = (call);                                                                 \
+    if (e_ != hipSuccess)                                                                   \
+      return fail(ctx, SPARK_EHIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_),  \
+                  __FILE__, __LINE__);                                                      \
+  } while (0)
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+bool config_ok(const spark_config *c, char *why, size_t n) {
+#define BAD(cond, msg) if (cond) { snprintf(why, n, "%s", msg); return false; }
+  BAD(c->size != sizeof(spark_config), "spark_config.size does not match this library");
+  BAD(c->n_layers < 1, "n_layers < 1");
+  BAD(c->d_model < 8 || c->d_model % 8, "d_model must be a positive multiple of 8");
+  BAD(c->d_model > 4096, "d_model > 4096 is not supported");
+  BAD(c->n_kv_heads < 1 || c->n_q_heads < 1 || c->n_q_heads % c->n_kv_heads,
+      "n_q_heads must be a positive multiple of n_kv_heads");
+  BAD(c->n_q_heads / c->n_kv_heads > ATTN_MAX_GROUP, "more than 16 query heads per KV head");
+  BAD(c->head_dim != 64 && c->head_dim != 128, "head_dim must be 64 or 128");
+  BAD(c->d_ffn < 8 || c->d_ffn % 8, "d_ffn must be a positive multiple of 8");
+  BAD(c->vocab_text < 0 || c->vocab_speech < 0 || c->vocab_text + c->vocab_speech < 1,
+      "empty vocabulary");
+  BAD(c->dtype != SPARK_DTYPE_FP32 && c->dtype != SPARK_DTYPE_BF16, "unknown dtype");
+  BAD(c->exit_layer < 1 || c->exit_layer > c->n_layers, "exit_layer outside [1, n_layers]");
+  BAD(c->period_k < 1 || c->period_k > SPARK_MAX_PERIOD, "period_k outside [1, 16]");
+  BAD(c->phase < 0 || c->phase >= c->period_k, "phase outside [0, period_k)");
+  BAD(c->scope != SPARK_SCOPE_CHUNK && c->scope != SPARK_SCOPE_STREAM, "unknown scope");
+  BAD(c->n_text < 0 || c->n_speech < 0 || c->n_text + c->n_speech < 1, "empty interleave cycle");
+  BAD(c->n_text == 0 && c->scope == SPARK_SCOPE_CHUNK && c->exit_layer < c->n_layers &&
+          c->period_k > 1 && c->phase >= c->n_speech,
+      "a pure-speech cycle without a full-depth slot would never complete its KV");
+  BAD(c->max_batch < 1 || c->max_batch > SCHED_THREADS, "max_batch outside [1, 256]");
+  BAD(c->max_seq_len < 1 || c->max_seq_len > 256 * MAX_SPLITS, "max_seq_len outside [1, 16384]");
+  BAD(c->kv_page_tokens < 16 || c->kv_page_tokens % 16, "kv_page_tokens must be a multiple of 16");
+#undef BAD
+  return true;
+}
+
+void derive(const spark_config &c, Derived &d) {
+  d.V = c.vocab_text + c.vocab_speech;
+  d.rmax = 2 * c.period_k;
+  d.max_rows = std::max(c.max_batch * d.rmax, PREFILL_CHUNK);
+  d.max_pages = (c.max_seq_len + c.kv_page_tokens - 1) / c.kv_page_tokens;
+  d.n_pages_total = d.max_pages * c.max_batch;
+  int per = (c.max_seq_len + 256 * MAX_SPLITS - 1) / (256 * MAX_SPLITS);
+  d.slice = 256 * per;
+  d.n_splits = (c.max_seq_len + d.slice - 1) / d.slice;
+  d.group = c.n_q_heads / c.n_kv_heads;
+  d.esz = c.dtype == SPARK_DTYPE_BF16 ? 2 : 4;
+  d.page_elems = (size_t)c.n_layers * 2 * c.n_kv_heads * c.kv_page_tokens * c.head_dim;
+  d.kv_pool_bytes = d.page_elems * d.esz * d.n_pages_total;
+}
+
+void layout(const spark_config &c, const Derived &d, Layout &l) {
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+  const size_t qw = (size_t)c.n_q_heads * c.head_dim;
+  l.state = take(sizeof(int) * ST_WORDS * c.max_batch);
+  l.page_table = take(sizeof(int) * (size_t)d.max_pages * c.max_batch);
+  l.plan = take(sizeof(int) * PL_WORDS);
+  l.lower = take(sizeof(RowDesc) * c.max_batch);
+  l.upper = take(sizeof(RowDesc) * (size_t)c.max_batch * d.rmax);
+  l.ee = take(sizeof(RowDesc) * c.max_batch);
+  l.full = take(sizeof(RowDesc) * c.max_batch);
+  l.prefill_rows = take(sizeof(RowDesc) * PREFILL_CHUNK);
+  l.prefill_tokens = take(sizeof(int) * PREFILL_CHUNK);
+  l.seq_ids = take(sizeof(int) * c.max_batch);
+  l.forced = take(sizeof(int) * (size_t)MAX_STEPS_PER_CALL * c.max_batch);
+  l.step_flags = take(sizeof(int) * c.max_batch);
+  l.out_tokens = take(sizeof(int) * (size_t)MAX_STEPS_PER_CALL * c.max_batch);
+  l.out_depth = take(sizeof(int) * (size_t)MAX_STEPS_PER_CALL * c.max_batch);
+  l.best = take(sizeof(unsigned long long) * c.max_batch);
+  l.hidden = take(sizeof(float) * ((size_t)c.max_batch * d.rmax + PREFILL_CHUNK) * c.d_model);
+  l.qbuf = take(sizeof(float) * d.max_rows * qw);
+  l.attn_out = take(sizeof(float) * d.max_rows * qw);
+  l.part = take(sizeof(float) * (size_t)d.max_rows * c.n_q_heads * d.n_splits * (c.head_dim + 2));
+  l.act = take(sizeof(float) * (size_t)d.max_rows * c.d_ffn);
+  l.lens_u = take(sizeof(float) * (size_t)c.max_batch * c.d_model);
+  l.logits = take(sizeof(float) * (size_t)c.max_batch * d.V);
+  l.rope = take(sizeof(float2) * (size_t)c.max_seq_len * (c.head_dim / 2));
+  l.inv_freq = take(sizeof(float) * (c.head_dim / 2));
+  l.total = o;
+}
+
+template <typename T> T *at(spark_ctx *c, size_t off) { return (T *)(c->scratch + off); }
+
+// ------------------------------------------------------------------ profiling brackets
+
+int prof_begin(spark_ctx *c, int kclass) {
+  if (c->prof_class != kclass) return SPARK_OK;
+  if (c->prof_used + 2 > c->prof_ev.size()) {
+    for (int i = 0; i < 2; ++i) {
+      hipEvent_t ev;
+      HIP_TRY(c, hipEventCreate(&ev));
+      c->prof_ev.push_back(ev);
+    }
+  }
+  HIP_TRY(c, hipEventRecord(c->prof_ev[c->prof_used], c->stream));
+  return SPARK_OK;
+}
+int prof_end(spark_ctx *c, int kclass) {
+  if (c->prof_class != kclass) return SPARK_OK;
+  HIP_TRY(c, hipEventRecord(c->prof_ev[c->prof_used + 1], c->stream));
+  c->prof_used += 2;
+  return SPARK_OK;
+}
+
+// ------------------------------------------------------------------ launches
+
+template <typename WT, typename Pro, typename Epi>
+int launch_gemv(spark_ctx *c, const Pro &pro, const Epi &epi, const RowDesc *rows, int m_rows,
+                int n_in, int n_tasks, int kclass) {
+  if (m_rows <= 0) return SPARK_OK;
+  // activation rows per pass over the weights: as many as fit in 64 KiB of LDS next to the
+  // partial-sum words; a norm prologue needs the whole row resident
+  constexpr size_t LDS_BUDGET = 65536 - sizeof(float) * GEMV_WAVES * 4;
+  const bool whole_row = std::is_same<Pro, ProNorm>::value;
+  int mt = std::min(4, m_rows);
+  while (mt > 1 && whole_row && sizeof(float) * mt * align_up(n_in, 512) > LDS_BUDGET) --mt;
+  int kc_cap = (int)(LDS_BUDGET / (sizeof(float) * mt)) / 512 * 512;
+  int kc = std::min((int)align_up(n_in, 512), kc_cap);
+  if (whole_row && kc < n_in) return fail(c, SPARK_EINVAL, "row of %d does not fit in LDS", n_in);
+  size_t lds = sizeof(float) * ((size_t)mt * kc + GEMV_WAVES * mt);
+  int bx = std::min((n_tasks + GEMV_WAVES - 1) / GEMV_WAVES, c->n_cu * (lds > 32768 ? 2 : 4));
+  dim3 grid(bx, (m_rows + mt - 1) / mt), block(GEMV_THREADS);
+  int rc = prof_begin(c, kclass);
+  if (rc) return rc;
+  switch (mt) {
+    case 1: gemv_rows_k<WT, 1, Pro, Epi><<<grid, block, lds, c->stream>>>(pro, epi, rows, m_rows, n_in, n_tasks, kc); break;
+    case 2: gemv_rows_k<WT, 2, Pro, Epi><<<grid, block, lds, c->stream>>>(pro, epi, rows, m_rows, n_in, n_tasks, kc); break;
+    case 3: gemv_rows_k<WT, 3, Pro, Epi><<<grid, block, lds, c->stream>>>(pro, epi, rows, m_rows, n_in, n_tasks, kc); break;
+    default: gemv_rows_k<WT, 4, Pro, Epi><<<grid, block, lds, c->stream>>>(pro, epi, rows, m_rows, n_in, n_tasks, kc); break;
+  }
+  HIP_TRY(c, hipGetLastError());
+  return prof_end(c, kclass);
+}
+
+KVView kv_view(spark_ctx *c) {
+  KVView v;
+  v.pool = c->kv_pool;
+  v.page_table = at<int>(c, c->lo.page_table);
+  v.max_pages = c->dv.max_pages;
+  v.n_layers = c->cfg.n_layers;
+  v.n_kv_heads = c->cfg.n_kv_heads;
+  v.page_tokens = c->cfg.kv_page_tokens;
+  v.head_dim = c->cfg.head_dim;
+  return v;
+}
+
+template <typename WT> int launch_attention(spark_ctx *c, const RowDesc *rows, int m, int layer) {
+  const spark_config &g = c->cfg;
+  const Derived &d = c->dv;
+  int rc = prof_begin(c, SPARK_KC_ATTN);
+  if (rc) return rc;
+  dim3 grid(d.n_splits, g.n_kv_heads, m);
+  size_t lds = attn_partial_lds_bytes(d.group, g.head_dim, d.slice);
+  float scale = 1.0f / sqrtf((float)g.head_dim);
+  float *part = at<float>(c, c->lo.part);
+  if (g.head_dim == 128) {
+    attn_partial_k<WT, 128><<<grid, ATTN_THREADS, lds, c->stream>>>(
+        rows, at<float>(c, c->lo.qbuf), kv_view(c), layer, g.n_q_heads, d.group, d.slice,
+        d.n_splits, scale, part);
+    attn_merge_k<128><<<dim3(g.n_q_heads, m), 128, 0, c->stream>>>(part, g.n_q_heads, d.n_splits,
+                                                                 at<float>(c, c->lo.attn_out));
+  } else {
+    attn_partial_k<WT, 64><<<grid, ATTN_THREADS, lds, c->stream>>>(
+        rows, at<float>(c, c->lo.qbuf), kv_view(c), layer, g.n_q_heads, d.group, d.slice,
+        d.n_splits, scale, part);
+    attn_merge_k<64><<<dim3(g.n_q_heads, m), 64, 0, c->stream>>>(part, g.n_q_heads, d.n_splits,
+                                                               at<float>(c, c->lo.attn_out));
+  }
+  HIP_TRY(c, hipGetLastError());
+  return prof_end(c, SPARK_KC_ATTN);
+}
+
+// layers [l0, l1) on m rows described by `rows` (device)
+template <typename WT> int run_layers(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
+  const spark_config &g = c->cfg;
+  const int d = g.d_model, hd = g.head_dim, nq = g.n_q_heads, nkv = g.n_kv_heads, F = g.d_ffn;
+  const size_t qw = (size_t)nq * hd, kvw = (size_t)nkv * hd;
+  float *hidden = at<float>(c, c->lo.hidden);
+  int rc;
+  for (int l = l0; l < l1; ++l) {
+    ProNorm n1{hidden, c->w.attn_norm + (size_t)l * d, g.rms_eps, d, 1};
+    EpiQKV<WT> eq;
+    eq.wq = (const WT *)c->w.wq + (size_t)l * qw * d;
+    eq.wk = (const WT *)c->w.wk + (size_t)l * kvw * d;
+    eq.wv = (const WT *)c->w.wv + (size_t)l * kvw * d;
+    eq.d = d; eq.nq = nq; eq.nkv = nkv; eq.hd = hd; eq.layer = l;
+    eq.qbuf = at<float>(c, c->lo.qbuf);
+    eq.rope = at<float2>(c, c->lo.rope);
+    eq.kv = kv_view(c);
+    if ((rc = launch_gemv<WT>(c, n1, eq, rows, m, d, (nq + 2 * nkv) * (hd / 2), SPARK_KC_QKV))) return rc;
+
+    if ((rc = launch_attention<WT>(c, rows, m, l))) return rc;
+
+    ProPlain pa{at<float>(c, c->lo.attn_out), (int)qw, 0};
+    EpiResidual<WT> eo{(const WT *)c->w.wo + (size_t)l * d * qw, (int)qw, d, hidden, d};
+    if ((rc = launch_gemv<WT>(c, pa, eo, rows, m, (int)qw, d / 2, SPARK_KC_OPROJ))) return rc;
+
+    ProNorm n2{hidden, c->w.mlp_norm + (size_t)l * d, g.rms_eps, d, 1};
+    EpiSwiGLU<WT> eg{(const WT *)c->w.wg + (size_t)l * F * d, (const WT *)c->w.wu + (size_t)l * F * d,
+                     d, F, at<float>(c, c->lo.act)};
+    if ((rc = launch_gemv<WT>(c, n2, eg, rows, m, d, F, SPARK_KC_GATEUP))) return rc;
+
+    ProPlain pd{at<float>(c, c->lo.act), F, 0};
+    EpiResidual<WT> ed{(const WT *)c->w.wd + (size_t)l * d * F, F, d, hidden, d};
+    if ((rc = launch_gemv<WT>(c, pd, ed, rows, m, F, d / 2, SPARK_KC_DOWN))) return rc;
+  }
+  return SPARK_OK;
+}
+
+template <typename WT> int run_lens_head(spark_ctx *c, const RowDesc *rows, int m) {
+  const spark_config &g = c->cfg;
+  const int d = g.d_model, V = c->dv.V;
+  float *hidden = at<float>(c, c->lo.hidden), *u = at<float>(c, c->lo.lens_u);
+  int rc;
+  ProPlain ph{hidden, d, 1};
+  EpiLensAffine<WT> ea{(const WT *)c->w.lens_a, c->w.lens_b, hidden, u, d};
+  if ((rc = launch_gemv<WT>(c, ph, ea, rows, m, d, d / 2, SPARK_KC_LENS))) return rc;
+  // the translated state sits in u[pass row]; normalising it is the head's prologue
+  ProNorm pn{u, c->w.lens_norm, g.rms_eps, d, 0};
+  EpiVocab<WT> ev{(const WT *)c->w.lens_head, d, V, at<float>(c, c->lo.logits),
+                  at<unsigned long long>(c, c->lo.best)};
+  return launch_gemv<WT>(c, pn, ev, rows, m, d, (V + 1) / 2, SPARK_KC_LENS);
+}
+
+template <typename WT> int run_final_head(spark_ctx *c, const RowDesc *rows, int m) {
+  const spark_config &g = c->cfg;
+  const int d = g.d_model, V = c->dv.V;
+  ProNorm pn{at<float>(c, c->lo.hidden), c->w.final_norm, g.rms_eps, d, 1};
+  EpiVocab<WT> ev{(const WT *)c->w.lm_head, d, V, at<float>(c, c->lo.logits),
+                  at<unsigned long long>(c, c->lo.best)};
+  return launch_gemv<WT>(c, pn, ev, rows, m, d, (V + 1) / 2, SPARK_KC_HEAD);
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ C ABI
+
+namespace {
+
+Seq *find_seq(spark_ctx *c, int id) {
+  if (id < 0 || id >= (int)c->seqs.size() || !c->seqs[id].open) return nullptr;
+  return &c->seqs[id];
+}
+
+// make sure `seq` owns pages for positions [0, upto); new page-table entries go to the device
+int ensure_pages(spark_ctx *c, int id, int upto) {
+  Seq &s = c->seqs[id];
+  const int pt = c->cfg.kv_page_tokens;
+  const int need = (upto + pt - 1) / pt;
+  const int have = (int)s.pages.size();
+  if (need <= have) return SPARK_OK;
+  if (need > c->dv.max_pages) return fail(c, SPARK_ENOMEM, "sequence %d exceeds max_seq_len", id);
+  if ((int)c->free_pages.size() < need - have) return fail(c, SPARK_ENOMEM, "KV pool exhausted");
+  for (int p = have; p < need; ++p) {
+    s.pages.push_back(c->free_pages.back());
+    c->free_pages.pop_back();
+  }
+  int *dst = at<int>(c, c->lo.page_table) + (size_t)id * c->dv.max_pages + have;
+  HIP_TRY(c, hipMemcpyAsync(dst, s.pages.data() + have, sizeof(int) * (need - have),
+                            hipMemcpyHostToDevice, c->stream));
+  // the source vector may be reallocated by a later push_back
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return SPARK_OK;
+}
+
+template <typename WT>
+int enqueue_step(spark_ctx *c, int n, int n_upper, int n_ee, int n_full, const int *forced_dev,
+                 int *out_tok_dev, int *out_depth_dev) {
+  const spark_config &g = c->cfg;
+  RowDesc *lower = at<RowDesc>(c, c->lo.lower), *upper = at<RowDesc>(c, c->lo.upper);
+  RowDesc *ee = at<RowDesc>(c, c->lo.ee), *full = at<RowDesc>(c, c->lo.full);
+  int *state = at<int>(c, c->lo.state), *plan = at<int>(c, c->lo.plan);
+  int *seq_ids = at<int>(c, c->lo.seq_ids), *flags = at<int>(c, c->lo.step_flags);
+  unsigned long long *best = at<unsigned long long>(c, c->lo.best);
+  int rc;
+  sched_dispatch_k<<<1, SCHED_THREADS, 0, c->stream>>>(c->sp, n, seq_ids, state, lower, upper, ee,
+                                                      full, plan, flags, out_depth_dev, best);
+  embed_rows_k<WT><<<n, 256, 0, c->stream>>>(lower, state, nullptr, (const WT *)c->w.embed,
+                                             g.d_model, at<float>(c, c->lo.hidden));
+  HIP_TRY(c, hipGetLastError());
+  if ((rc = run_layers<WT>(c, 0, g.exit_layer, lower, n))) return rc;
+  if (n_ee && (rc = run_lens_head<WT>(c, ee, n_ee))) return rc;
+  if (n_full) {
+    if ((rc = run_layers<WT>(c, g.exit_layer, g.n_layers, upper, n_upper))) return rc;
+    if ((rc = run_final_head<WT>(c, full, n_full))) return rc;
+  }
+  emit_k<<<1, SCHED_THREADS, 0, c->stream>>>(n, seq_ids, forced_dev, flags, best, state, plan,
+                                            out_tok_dev);
+  HIP_TRY(c, hipGetLastError());
+  return SPARK_OK;
+}
+
+int decode_chunk(spark_ctx *c, int steps, int n, const int32_t *seq_ids, const int32_t *forced,
+                 int32_t *out_tokens, int32_t *out_depth) {
+  const spark_config &g = c->cfg;
+  int rc;
+  // validation and page reservation
+  for (int i = 0; i < n; ++i) {
+    Seq *s = find_seq(c, seq_ids[i]);
+    if (!s) return fail(c, SPARK_ENOSEQ, "unknown sequence id %d", seq_ids[i]);
+    if (!s->prefilled) return fail(c, SPARK_ESTATE, "sequence %d stepped before prefill", seq_ids[i]);
+    for (int k = 0; k < i; ++k)
+      if (seq_ids[k] == seq_ids[i]) return fail(c, SPARK_EINVAL, "sequence %d listed twice", seq_ids[i]);
+    if (s->len + steps > g.max_seq_len)
+      return fail(c, SPARK_ENOMEM, "sequence %d would exceed max_seq_len", seq_ids[i]);
+    if (forced)
+      for (int st = 0; st < steps; ++st)
+        if (forced[st * n + i] >= c->dv.V) return fail(c, SPARK_EINVAL, "forced id out of range");
+  }
+  for (int i = 0; i < n; ++i)
+    if ((rc = ensure_pages(c, seq_ids[i], c->seqs[seq_ids[i]].len + steps))) return rc;
+
+  // inputs
+  int *h_ids = c->h_in, *h_forced = c->h_in + g.max_batch;
+  memcpy(h_ids, seq_ids, sizeof(int) * n);
+  HIP_TRY(c, hipMemcpyAsync(at<int>(c, c->lo.seq_ids), h_ids, sizeof(int) * n, hipMemcpyHostToDevice,
+                            c->stream));
+  if (forced) {
+    memcpy(h_forced, forced, sizeof(int) * (size_t)steps * n);
+    HIP_TRY(c, hipMemcpyAsync(at<int>(c, c->lo.forced), h_forced, sizeof(int) * (size_t)steps * n,
+                              hipMemcpyHostToDevice, c->stream));
+  }
+
+  // host mirror of the schedule: decides the launch shapes, checked against the device's depths
+  struct Mirror { int g, j, npend, len; };
+  std::vector<Mirror> mir(n);
+  for (int i = 0; i < n; ++i) {
+    Seq &s = c->seqs[seq_ids[i]];
+    mir[i] = Mirror{s.g, s.j_stream, s.n_pending, s.len};
+  }
+  std::vector<int> want_depth((size_t)steps * n), want_text((size_t)steps * n),
+      want_rows((size_t)steps * n);
+  for (int st = 0; st < steps; ++st) {
+    int n_upper = 0, n_ee = 0, n_full = 0;
+    for (int i = 0; i < n; ++i) {
+      int is_text, full;
+      schedule_decide(c->sp, mir[i].g, c->seqs[seq_ids[i]].cycle_offset, mir[i].j, is_text, full);
+      want_depth[st * n + i] = full ? g.n_layers : g.exit_layer;
+      want_text[st * n + i] = is_text;
+      want_rows[st * n + i] = full ? mir[i].npend + 1 : 0;
+      if (full) { n_upper += mir[i].npend + 1; ++n_full; mir[i].npend = 0; }
+      else { ++n_ee; mir[i].npend += 1; }
+      mir[i].g += 1;
+      if (!is_text) mir[i].j += 1;
+      mir[i].len += 1;
+    }
+    const int *f = forced ? at<int>(c, c->lo.forced) + (size_t)st * n : nullptr;
+    int *ot = at<int>(c, c->lo.out_tokens) + (size_t)st * n;
+    int *od = at<int>(c, c->lo.out_depth) + (size_t)st * n;
+    rc = g.dtype == SPARK_DTYPE_BF16 ? enqueue_step<bf16_t>(c, n, n_upper, n_ee, n_full, f, ot, od)
+                                     : enqueue_step<float>(c, n, n_upper, n_ee, n_full, f, ot, od);
+    if (rc) return rc;
+  }
+
+  // results
+  const size_t cnt = (size_t)steps * n;
+  int *h_tok = c->h_out, *h_dep = c->h_out + (size_t)MAX_STEPS_PER_CALL * g.max_batch;
+  int *h_plan = h_dep + (size_t)MAX_STEPS_PER_CALL * g.max_batch;
+  HIP_TRY(c, hipMemcpyAsync(h_tok, at<int>(c, c->lo.out_tokens), sizeof(int) * cnt,
+                            hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipMemcpyAsync(h_dep, at<int>(c, c->lo.out_depth), sizeof(int) * cnt,
+                            hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipMemcpyAsync(h_plan, at<int>(c, c->lo.plan), sizeof(int) * PL_WORDS,
+                            hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  memcpy(out_tokens, h_tok, sizeof(int) * cnt);
+  memcpy(out_depth, h_dep, sizeof(int) * cnt);
+
+  // commit the mirror and the exit-layer log
+  for (int st = 0; st < steps; ++st)
+    for (int i = 0; i < n; ++i) {
+      Seq &s = c->seqs[seq_ids[i]];
+      const size_t k = (size_t)st * n + i;
+      if (h_dep[k] != want_depth[k])
+        return fail(c, SPARK_ESTATE, "device schedule (%d) and host mirror (%d) disagree", h_dep[k],
+                    want_depth[k]);
+      if (want_rows[k]) {
+        s.flush_rows[want_rows[k]] += 1;
+        if (want_text[k]) s.text_steps += 1; else s.speech_full += 1;
+      } else {
+        s.speech_ee += 1;
+      }
+      s.last_full = want_rows[k] != 0;
+    }
+  for (int i = 0; i < n; ++i) {
+    Seq &s = c->seqs[seq_ids[i]];
+    s.g = mir[i].g; s.j_stream = mir[i].j; s.n_pending = mir[i].npend; s.len = mir[i].len;
+  }
+  if (h_plan[PL_ERR]) {
+    int e = h_plan[PL_ERR];
+    int zero = 0;  // error path only: clear the flag so that the context stays usable
+    (void)hipMemcpy(at<int>(c, c->lo.plan) + PL_ERR, &zero, sizeof(int), hipMemcpyHostToDevice);
+    if (e & ERR_NAN) return fail(c, SPARK_ENAN, "a head produced a NaN logit");
+    return fail(c, SPARK_ESTATE, "device saw an inactive sequence");
+  }
+  return SPARK_OK;
+}
+
+template <typename WT> int prefill_rows(spark_ctx *c, int id, const int32_t *prompt, int n_rows) {
+  const spark_config &g = c->cfg;
+  const int base_slot = g.max_batch * c->dv.rmax;
+  std::vector<RowDesc> rows(PREFILL_CHUNK);
+  RowDesc *rows_dev = at<RowDesc>(c, c->lo.prefill_rows);
+  int *tok_dev = at<int>(c, c->lo.prefill_tokens);
+  int rc;
+  for (int p0 = 0; p0 < n_rows; p0 += PREFILL_CHUNK) {
+    const int m = std::min(PREFILL_CHUNK, n_rows - p0);
+    for (int r = 0; r < m; ++r) rows[r] = RowDesc{base_slot + r, id, p0 + r, -1};
+    HIP_TRY(c, hipMemcpyAsync(rows_dev, rows.data(), sizeof(RowDesc) * m, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(tok_dev, prompt + p0, sizeof(int) * m, hipMemcpyHostToDevice, c->stream));
+    embed_rows_k<WT><<<m, 256, 0, c->stream>>>(rows_dev, nullptr, tok_dev, (const WT *)c->w.embed,
+                                               g.d_model, at<float>(c, c->lo.hidden));
+    HIP_TRY(c, hipGetLastError());
+    if ((rc = run_layers<WT>(c, 0, g.n_layers, rows_dev, m))) return rc;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+  }
+  return SPARK_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int spark_workspace_bytes(const spark_config *cfg, size_t *kv_pool_bytes, size_t *scratch_bytes) {
+  char why[128];
+  if (!cfg || !config_ok(cfg, why, sizeof(why))) return SPARK_EINVAL;
+  Derived d;
+  Layout l;
+  derive(*cfg, d);
+  layout(*cfg, d, l);
+  if (kv_pool_bytes) *kv_pool_bytes = d.kv_pool_bytes;
+  if (scratch_bytes) *scratch_bytes = l.total;
+  return SPARK_OK;
+}
+
+int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_pool,
+               size_t kv_pool_bytes, void *scratch, size_t scratch_bytes, void *hip_stream,
+               spark_ctx **out) {
+  if (!out) return SPARK_EINVAL;
+  *out = nullptr;
+  char why[128];
+  if (!cfg || !weights || !config_ok(cfg, why, sizeof(why))) return SPARK_EINVAL;
+  const void *const *wp = (const void *const *)weights;
+  for (size_t i = 0; i < sizeof(spark_weights) / sizeof(void *); ++i)
+    if (!wp[i]) return SPARK_EINVAL;
+  spark_ctx *c = new spark_ctx();
+  c->cfg = *cfg;
+  c->w = *weights;
+  c->err[0] = 0;
+  derive(*cfg, c->dv);
+  layout(*cfg, c->dv, c->lo);
+  if (!kv_pool || !scratch || kv_pool_bytes < c->dv.kv_pool_bytes || scratch_bytes < c->lo.total ||
+      ((uintptr_t)kv_pool & 255) || ((uintptr_t)scratch & 255)) {
+    delete c;
+    return SPARK_ENOMEM;
+  }
+  c->stream = (hipStream_t)hip_stream;
+  c->scratch = (char *)scratch;
+  c->kv_pool = kv_pool;
+  c->sp = SchedParams{cfg->n_layers, cfg->exit_layer, cfg->period_k, cfg->phase, cfg->scope,
+                      cfg->n_text, cfg->n_speech, c->dv.rmax};
+  c->seqs.resize(cfg->max_batch);
+  for (int p = c->dv.n_pages_total - 1; p >= 0; --p) c->free_pages.push_back(p);
+  c->h_in = c->h_out = nullptr;
+  auto bail = [&](int code) { spark_destroy(c); return code; };
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
+    return bail(SPARK_EHIP);
+  c->n_cu = prop.multiProcessorCount;
+  size_t in_ints = (size_t)cfg->max_batch * (1 + MAX_STEPS_PER_CALL);
+  size_t out_ints = (size_t)cfg->max_batch * 2 * MAX_STEPS_PER_CALL + PL_WORDS;
+  if (hipHostMalloc((void **)&c->h_in, sizeof(int) * in_ints, hipHostMallocDefault) != hipSuccess ||
+      hipHostMalloc((void **)&c->h_out, sizeof(int) * out_ints, hipHostMallocDefault) != hipSuccess)
+    return bail(SPARK_EHIP);
+  // device state, rotary table
+  if (hipMemsetAsync(c->scratch + c->lo.state, 0, c->lo.hidden - c->lo.state, c->stream) != hipSuccess)
+    return bail(SPARK_EHIP);
+  const int half = cfg->head_dim / 2;
+  std::vector<float> inv(half);
+  for (int i = 0; i < half; ++i)
+    inv[i] = (float)pow((double)cfg->rope_base, -2.0 * i / (double)cfg->head_dim);
+  if (hipMemcpyAsync(c->scratch + c->lo.inv_freq, inv.data(), sizeof(float) * half,
+                     hipMemcpyHostToDevice, c->stream) != hipSuccess)
+    return bail(SPARK_EHIP);
+  int total = half * cfg->max_seq_len;
+  rope_table_k<<<(total + 255) / 256, 256, 0, c->stream>>>(at<float>(c, c->lo.inv_freq), half,
+                                                          cfg->max_seq_len, at<float2>(c, c->lo.rope));
+  if (hipGetLastError() != hipSuccess || hipStreamSynchronize(c->stream) != hipSuccess)
+    return bail(SPARK_EHIP);
+  *out = c;
+  return SPARK_OK;
+}
+
+int spark_seq_open(spark_ctx *c, int32_t cycle_offset, int32_t *seq_id) {
+  if (!c || !seq_id) return SPARK_EINVAL;
+  if (cycle_offset < 0) return fail(c, SPARK_EINVAL, "cycle_offset < 0");
+  for (int i = 0; i < (int)c->seqs.size(); ++i)
+    if (!c->seqs[i].open) {
+      c->seqs[i] = Seq();
+      c->seqs[i].open = true;
+      c->seqs[i].cycle_offset = cycle_offset % (c->cfg.n_text + c->cfg.n_speech);
+      *seq_id = i;
+      return SPARK_OK;
+    }
+  return fail(c, SPARK_ENOSEQ, "all %d sequence slots are open", (int)c->seqs.size());
+}
+
+int spark_prefill(spark_ctx *c, int32_t seq_id, const int32_t *prompt, int32_t n) {
+  if (!c) return SPARK_EINVAL;
+  Seq *s = find_seq(c, seq_id);
+  if (!s) return fail(c, SPARK_ENOSEQ, "unknown sequence id %d", seq_id);
+  if (s->prefilled) return fail(c, SPARK_ESTATE, "sequence %d already has a prompt", seq_id);
+  if (!prompt || n < 1) return fail(c, SPARK_EINVAL, "empty prompt");
+  if (n > c->cfg.max_seq_len) return fail(c, SPARK_ENOMEM, "prompt longer than max_seq_len");
+  for (int i = 0; i < n; ++i)
+    if (prompt[i] < 0 || prompt[i] >= c->dv.V) return fail(c, SPARK_EINVAL, "prompt id out of range");
+  int rc = ensure_pages(c, seq_id, n - 1);
+  if (rc) return rc;
+  if (n > 1) {
+    rc = c->cfg.dtype == SPARK_DTYPE_BF16 ? prefill_rows<bf16_t>(c, seq_id, prompt, n - 1)
+                                          : prefill_rows<float>(c, seq_id, prompt, n - 1);
+    if (rc) return rc;
+  }
+  int st[ST_WORDS] = {0};
+  st[ST_LEN] = n - 1;
+  st[ST_OFFSET] = s->cycle_offset;
+  st[ST_NEXT] = prompt[n - 1];
+  st[ST_ACTIVE] = 1;
+  HIP_TRY(c, hipMemcpyAsync(at<int>(c, c->lo.state) + (size_t)seq_id * ST_WORDS, st, sizeof(st),
+                            hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  s->len = n - 1;
+  s->prefilled = true;
+  return SPARK_OK;
+}
+
+int spark_decode(spark_ctx *c, int32_t n_steps, int32_t n, const int32_t *seq_ids,
+                 const int32_t *forced_next, int32_t *out_tokens, int32_t *out_depth) {
+  if (!c) return SPARK_EINVAL;
+  if (n < 1 || n > c->cfg.max_batch || n_steps < 1 || !seq_ids || !out_tokens || !out_depth)
+    return fail(c, SPARK_EINVAL, "bad batch (n=%d, n_steps=%d)", n, n_steps);
+  for (int s0 = 0; s0 < n_steps; s0 += MAX_STEPS_PER_CALL) {
+    int steps = std::min(MAX_STEPS_PER_CALL, n_steps - s0);
+    int rc = decode_chunk(c, steps, n, seq_ids, forced_next ? forced_next + (size_t)s0 * n : nullptr,
+                          out_tokens + (size_t)s0 * n, out_depth + (size_t)s0 * n);
+    if (rc) return rc;
+  }
+  return SPARK_OK;
+}
+
+int spark_step(spark_ctx *c, int32_t n, const int32_t *seq_ids, const int32_t *forced_next,
+               int32_t *out_tokens, int32_t *out_depth) {
+  return spark_decode(c, 1, n, seq_ids, forced_next, out_tokens, out_depth);
+}
+
+int spark_get_logits(spark_ctx *c, int32_t seq_id, float *out_logits, int32_t *head) {
+  if (!c || !out_logits) return SPARK_EINVAL;
+  Seq *s = find_seq(c, seq_id);
+  if (!s) return fail(c, SPARK_ENOSEQ, "unknown sequence id %d", seq_id);
+  if (!s->g) return fail(c, SPARK_ESTATE, "sequence %d has not been stepped", seq_id);
+  // logits rows are indexed by the position of the sequence in the last batch
+  std::vector<int> ids(c->cfg.max_batch);
+  HIP_TRY(c, hipMemcpy(ids.data(), at<int>(c, c->lo.seq_ids), sizeof(int) * c->cfg.max_batch,
+                       hipMemcpyDeviceToHost));
+  int row = -1;
+  for (int i = 0; i < c->cfg.max_batch; ++i)
+    if (ids[i] == seq_id) { row = i; break; }
+  if (row < 0) return fail(c, SPARK_ESTATE, "sequence %d was not in the last step", seq_id);
+  HIP_TRY(c, hipMemcpy(out_logits, at<float>(c, c->lo.logits) + (size_t)row * c->dv.V,
+                       sizeof(float) * c->dv.V, hipMemcpyDeviceToHost));
+  if (head) *head = s->last_full ? c->cfg.n_layers : c->cfg.exit_layer;
+  return SPARK_OK;
+}
+
+int spark_get_kv(spark_ctx *c, int32_t seq_id, int32_t layer, int32_t pos, float *k_out,
+                 float *v_out) {
+  if (!c || !k_out || !v_out) return SPARK_EINVAL;
+  Seq *s = find_seq(c, seq_id);
+  if (!s) return fail(c, SPARK_ENOSEQ, "unknown sequence id %d", seq_id);
+  const spark_config &g = c->cfg;
+  if (layer < 0 || layer >= g.n_layers || pos < 0 || pos >= s->len)
+    return fail(c, SPARK_EINVAL, "layer or position out of range");
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  const int pt = g.kv_page_tokens, hd = g.head_dim, esz = c->dv.esz;
+  const int page = s->pages[pos / pt];
+  std::vector<unsigned char> raw((size_t)hd * esz);
+  for (int which = 0; which < 2; ++which)
+    for (int h = 0; h < g.n_kv_heads; ++h) {
+      size_t o = (size_t)page * g.n_layers + layer;
+      o = (o * 2 + which) * g.n_kv_heads + h;
+      o = (o * pt + pos % pt) * hd;
+      HIP_TRY(c, hipMemcpy(raw.data(), (const char *)c->kv_pool + o * esz, (size_t)hd * esz,
+                           hipMemcpyDeviceToHost));
+      float *dst = (which ? v_out : k_out) + (size_t)h * hd;
+      for (int i = 0; i < hd; ++i) {
+        if (esz == 2) {
+          uint32_t u = (uint32_t)((const uint16_t *)raw.data())[i] << 16;
+          memcpy(dst + i, &u, 4);
+        } else {
+          dst[i] = ((const float *)raw.data())[i];
+        }
+      }
+    }
+  return SPARK_OK;
+}
+
+int spark_seq_state(spark_ctx *c, int32_t seq_id, int32_t *len, int32_t *upper_valid,
+                    int32_t *n_pending) {
+  if (!c) return SPARK_EINVAL;
+  Seq *s = find_seq(c, seq_id);
+  if (!s) return fail(c, SPARK_ENOSEQ, "unknown sequence id %d", seq_id);
+  // the device copy is authoritative
+  int st[ST_WORDS];
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  HIP_TRY(c, hipMemcpy(st, at<int>(c, c->lo.state) + (size_t)seq_id * ST_WORDS, sizeof(st),
+                       hipMemcpyDeviceToHost));
+  if (s->prefilled && (st[ST_LEN] != s->len || st[ST_NPENDING] != s->n_pending))
+    return fail(c, SPARK_ESTATE, "device state and host mirror disagree");
+  if (len) *len = s->len;
+  if (upper_valid) *upper_valid = s->len - s->n_pending;
+  if (n_pending) *n_pending = s->n_pending;
+  return SPARK_OK;
+}
+
+int spark_get_stats(spark_ctx *c, int32_t seq_id, spark_stats *out) {
+  if (!c || !out) return SPARK_EINVAL;
+  Seq *s = find_seq(c, seq_id);
+  if (!s) return fail(c, SPARK_ENOSEQ, "unknown sequence id %d", seq_id);
+  memset(out, 0, sizeof(*out));
+  out->text_steps = s->text_steps;
+  out->speech_full_steps = s->speech_full;
+  out->speech_ee_steps = s->speech_ee;
+  memcpy(out->flush_rows, s->flush_rows, sizeof(out->flush_rows));
+  const double L = c->cfg.n_layers, e = c->cfg.exit_layer;
+  if (s->text_steps) out->mean_text_depth = L;
+  const int64_t ns = s->speech_full + s->speech_ee;
+  if (ns) {
+    out->mean_speech_depth = (s->speech_full * L + s->speech_ee * e) / (double)ns;
+    out->speech_layer_saving = (1.0 - out->mean_speech_depth / L) * 100.0;
+  }
+  return SPARK_OK;
+}
+
+int spark_seq_close(spark_ctx *c, int32_t seq_id) {
+  if (!c) return SPARK_EINVAL;
+  Seq *s = find_seq(c, seq_id);
+  if (!s) return fail(c, SPARK_ENOSEQ, "unknown sequence id %d", seq_id);
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  for (int p : s->pages) c->free_pages.push_back(p);
+  int zero[ST_WORDS] = {0};
+  HIP_TRY(c, hipMemcpy(at<int>(c, c->lo.state) + (size_t)seq_id * ST_WORDS, zero, sizeof(zero),
+                       hipMemcpyHostToDevice));
+  *s = Seq();
+  return SPARK_OK;
+}
+
+void spark_destroy(spark_ctx *c) {
+  if (!c) return;
+  (void)hipStreamSynchronize(c->stream);
+  for (hipEvent_t ev : c->prof_ev) (void)hipEventDestroy(ev);
+  if (c->h_in) (void)hipHostFree(c->h_in);
+  if (c->h_out) (void)hipHostFree(c->h_out);
+  delete c;
+}
+
+const char *spark_last_error(const spark_ctx *c) { return c ? c->err : "null context"; }
+
+int spark_profile_select(spark_ctx *c, int32_t kernel_class) {
+  if (!c || kernel_class < -1 || kernel_class >= SPARK_KC_COUNT) return SPARK_EINVAL;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  c->prof_class = kernel_class;
+  c->prof_used = 0;
+  return SPARK_OK;
+}
+
+int spark_profile_read(spark_ctx *c, int64_t *n_launches, double *total_ms) {
+  if (!c || !n_launches || !total_ms) return SPARK_EINVAL;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  double tot = 0;
+  for (size_t i = 0; i + 1 < c->prof_used; i += 2) {
+    float ms = 0;
+    HIP_TRY(c, hipEventElapsedTime(&ms, c->prof_ev[i], c->prof_ev[i + 1]));
+    tot += ms;
+  }
+  *n_launches = (int64_t)(c->prof_used / 2);
+  *total_ms = tot;
+  c->prof_used = 0;
+  return SPARK_OK;
+}
+
+}  // extern "C"
