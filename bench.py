@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the SPAR-K decode hot path on one MI355X.
+
+A "step" is one decoding step (one generated token) of the whole path: schedule/dispatch, layers
+1..e on the new position, then either the layer-specific head (early exit) or the batched pass of
+pending rows through layers e+1..L and the final head.  Default workload: the Step-Audio-2-mini
+shape of the paper's Sec. V-A (28 layers), bf16, random-init weights, batch 1, 512-token prompt,
+interleave 1 text : 2 speech, exit layer 20, refresh period 4.
+
+Prints ONE JSON line: decode tokens/s with the weights, KV cache and prompt resident in HBM, the
+HBM roofline of the dominant kernel (the gate/up projection) from HIP events recorded on the
+library's stream, and the CPU oracle timed on the host cores as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+import workloads as wl
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+
+
+def synth_weights_on_device(shape, seed: int, device):
+    """N(0, 0.02) bf16 matrices drawn on the device (unit gains); same shapes as workloads.make_weights"""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    out = {}
+    for name, shp in wl.tensor_shapes(shape).items():
+        if name in wl.GAIN_TENSORS:
+            out[name] = torch.ones(shp, dtype=torch.float32, device=device)
+        elif name in wl.FP32_TENSORS:
+            out[name] = torch.randn(shp, generator=g, dtype=torch.float32, device=device) * 0.02
+        else:
+            dt = torch.bfloat16 if shape.dtype == wl.DTYPE_BF16 else torch.float32
+            t = torch.empty(shp, dtype=dt, device=device)
+            flat = t.view(-1)
+            step = 1 << 28
+            for lo in range(0, flat.numel(), step):   # bounded temporaries
+                hi = min(flat.numel(), lo + step)
+                flat[lo:hi] = (torch.randn(hi - lo, generator=g, dtype=torch.float32, device=device)
+                               * 0.02).to(dt)
+            out[name] = t
+    return out
+
+
+def weights_to_host(dev_weights: dict) -> dict:
+    """device tensors -> numpy arrays in the oracle's conventions (bf16 as uint16 bit patterns)"""
+    import torch
+    out = {}
+    for k, t in dev_weights.items():
+        c = t.cpu()
+        if c.dtype == torch.bfloat16:
+            out[k] = c.view(torch.int16).numpy().view(np.uint16)
+        else:
+            out[k] = c.numpy()
+    return out
+
+
+def step_bytes(shape, sched, ctx_len: float):
+    """algorithmic HBM bytes of one early-exit step and one full-depth step at context length T:
+    each needed weight matrix once, plus the KV of the layers that run"""
+    esz = 2 if shape.dtype == wl.DTYPE_BF16 else 4
+    d, F, V = shape.d_model, shape.d_ffn, shape.vocab
+    q, kv = shape.n_q_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim
+    w_layer = ((q + 2 * kv) * d + d * q + 2 * F * d + d * F) * esz
+    w_head = V * d * esz
+    kv_tok = 2 * kv * esz
+    ee = sched.exit_layer * w_layer + d * d * esz + w_head + sched.exit_layer * ctx_len * kv_tok
+    full = shape.n_layers * w_layer + w_head + shape.n_layers * ctx_len * kv_tok
+    return ee, full, w_layer
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1024)
+    ap.add_argument("--warmup", type=int, default=36)
+    ap.add_argument("--workload", default="step_audio_2_mini", choices=sorted(wl.WORKLOADS))
+    ap.add_argument("--prompt-len", type=int, default=None)
+    ap.add_argument("--cpu-steps", type=int, default=12, help="oracle steps timed for cpu_baseline (0 = skip)")
+    ap.add_argument("--profile-steps", type=int, default=48)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 (no collectives, no "
+              "sharding across devices are part of it)", file=sys.stderr)
+        return 2
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    from paper_2603_09215_amd import Spark
+
+    w = wl.WORKLOADS[args.workload]
+    shape, sched = w.shape, w.schedule
+    prompt_len = args.prompt_len or w.prompt_len
+    K, W = args.steps, args.warmup
+    device = torch.device("cuda:0")
+    max_seq = prompt_len + W + K + args.profile_steps + 64
+    max_seq = min(16384, (max_seq + 63) // 64 * 64)
+
+    t0 = time.time()
+    if shape.dtype == wl.DTYPE_BF16:
+        dev_w = synth_weights_on_device(shape, 0, device)
+    else:
+        dev_w = wl.make_weights(shape, seed=0)
+    sp = Spark(shape, sched, dev_w, max_batch=1, max_seq_len=max_seq, kv_page_tokens=64, device="cuda:0")
+    prompt = wl.make_prompt(shape, prompt_len, seed=1, ids=w.prompt_ids)
+    sid = sp.seq_open(0)
+    torch.cuda.synchronize()
+    tp0 = time.perf_counter()
+    sp.prefill(sid, prompt)
+    torch.cuda.synchronize()
+    prefill_s = time.perf_counter() - tp0
+    print(f"[bench] weights + prefill({prompt_len}) ready in {time.time() - t0:.1f}s "
+          f"(prefill {prefill_s * 1e3:.1f} ms)", file=sys.stderr, flush=True)
+
+    # ---- warm-up, then the timed region: exactly K steps, tokens fed back on the device
+    sp.decode(W, [sid])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    tok, dep = sp.decode(K, [sid])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t1
+    ms_per_step = elapsed * 1e3 / K
+    value = K / elapsed
+
+    # ---- per-class step times (one synchronous spark_step per token), same sequence continues
+    n_cls = min(args.profile_steps, 48)
+    cls = {}
+    ctx_now = prompt_len - 1 + W + K
+    for i in range(n_cls):
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        t_, d_ = sp.step([sid])
+        b = time.perf_counter()
+        st = sp.seq_state(sid)
+        key = "ee" if d_[0] != shape.n_layers else "full"
+        cls.setdefault(key, []).append((b - a) * 1e3)
+    ee_b, full_b, w_layer = step_bytes(shape, sched, ctx_now + n_cls / 2)
+    classes = {}
+    for key, ts in cls.items():
+        med = float(np.median(ts))
+        by = ee_b if key == "ee" else full_b
+        classes[key] = {"ms": round(med, 4), "algorithmic_GB": round(by / 1e9, 3),
+                        "GBps": round(by / med / 1e6, 1), "frac_of_hbm_peak": round(by / med / 1e6 / HBM_PEAK_GBS, 4)}
+
+    # ---- roofline of the dominant kernel: gate/up projection, HIP events on the library's stream
+    esz = 2 if shape.dtype == wl.DTYPE_BF16 else 4
+    gateup_bytes = 2 * shape.d_ffn * shape.d_model * esz
+    sp.profile_select("gateup")
+    sp.decode(args.profile_steps, [sid])
+    n_launch, tot_ms = sp.profile_read()
+    sp.profile_select(-1)
+    avg_ms = tot_ms / max(1, n_launch)
+    achieved = gateup_bytes / (avg_ms * 1e-3) / 1e9 if n_launch else 0.0
+    roofline = {"bound": "hbm", "kernel": "gemv_rows_k<gate/up + SwiGLU>", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": None, "bytes_per_launch": gateup_bytes, "avg_launch_ms": round(avg_ms, 5),
+                "launches_timed": int(n_launch)}
+
+    depth_all = dep[:, 0]
+    mix = {"full_steps": int((depth_all == shape.n_layers).sum()), "ee_steps": int((depth_all != shape.n_layers).sum())}
+    stats = sp.get_stats(sid)
+    avg_bytes = (mix["full_steps"] * full_b + mix["ee_steps"] * ee_b) / K
+    whole = {"algorithmic_GB_per_step": round(avg_bytes / 1e9, 3),
+             "GBps": round(avg_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+             "frac_of_hbm_peak": round(avg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload
+    cpu = None
+    if args.cpu_steps > 0:
+        from oracle import binding as ob
+        host_w = weights_to_host(sp.dev_weights)
+        om = ob.Model(shape, sched, host_w, max_seq_len=64)
+        osq = om.open(0)
+        osq.prefill(prompt[:4])
+        c0 = time.perf_counter()
+        for _ in range(args.cpu_steps):
+            rc, *_ = osq.step(want_logits=False)
+            assert rc == 0
+        cpu_s = time.perf_counter() - c0
+        cpu = {"value": round(args.cpu_steps / cpu_s, 4), "unit": "tokens/s", "cores": ob.num_threads(),
+               "kind": "oracle",
+               "sample": f"{args.cpu_steps} decode steps after a 4-token prompt, same shape, weights and schedule"}
+        osq.close(); om.close()
+
+    line = {
+        "metric": "decode tokens/s per GPU (batch 1)", "value": round(value, 2), "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if shape.dtype == wl.DTYPE_BF16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{shape.name}: L={shape.n_layers} d={shape.d_model} "
+                               f"{shape.n_q_heads}q/{shape.n_kv_heads}kv hd={shape.head_dim} F={shape.d_ffn} "
+                               f"V={shape.vocab}; prompt {prompt_len}, decode {K}, batch 1, "
+                               f"{sched.n_text}:{sched.n_speech} text:speech, e={sched.exit_layer}, "
+                               f"K={sched.period_k}, phase={sched.phase}, "
+                               f"scope={'chunk' if sched.scope == 0 else 'stream'}",
+                   "weights": "random N(0,0.02), fp32 accumulation", "kv_cache": "paged, 64 tokens/page",
+                   "step_mix": mix, "mean_speech_depth": stats["mean_speech_depth"],
+                   "speech_layer_saving_pct": round(stats["speech_layer_saving"], 2),
+                   "prefill_ms": round(prefill_s * 1e3, 1)},
+        "roofline": roofline, "whole_step": whole, "step_classes": classes, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+    sp.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -70,8 +70,13 @@ def load(kind: str = "f32") -> C.CDLL:
     lib.ora_prim_argmax.argtypes = [P, I]
     lib.ora_prim_bf16_round.restype = C.c_double
     lib.ora_prim_bf16_round.argtypes = [C.c_double]
+    lib.ora_num_threads.argtypes = []
     _libs[kind] = lib
     return lib
+
+
+def num_threads(kind: str = "f32") -> int:
+    return int(load(kind).ora_num_threads())
 
 
 def _ptr(a: np.ndarray) -> C.c_void_p:

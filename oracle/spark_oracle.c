@@ -29,6 +29,7 @@
  * that choice of form; its arithmetic is pinned to the numpy definition.
  */
 #include <math.h>
+#include <omp.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -579,6 +580,17 @@ int ora_lens_logits(ora_model *m, const double *h_in, double *logits_out) {
 }
 
 int ora_real_bytes(void) { return (int)sizeof(real); }
+
+/* threads the row loops of matvec run on */
+int ora_num_threads(void) {
+  int n = 1;
+#pragma omp parallel
+  {
+#pragma omp master
+    n = omp_get_num_threads();
+  }
+  return n;
+}
 
 /* ------------------------------------------------------------------ primitive probes (for pins) */
 

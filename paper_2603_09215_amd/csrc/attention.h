@@ -3,156 +3,157 @@
 // has already written K/V of every row of the pass, this is causal inside a batch of pending
 // positions as well (the "length-K causal mask" of Sec. IV-B.3).
 //
-// Few KV heads cannot fill 256 CUs, so the context is cut into slices: one block per
+// Few KV heads cannot fill 256 CUs, so the context is cut into slices of 64 tokens: one block per
 // (slice, kv head, row) produces an unnormalised partial (max, sum, weighted values) for all the
-// query heads of the group, and a second kernel merges the slices.
+// query heads of the group, and a second kernel merges the slices.  Inside a block a token's key
+// (and value) vector is spread over LPT consecutive lanes, 16 bytes each, so a wave reads
+// 64/LPT whole rows per instruction; all K and V loads of the slice are issued before any use.
 #pragma once
 #include "device_common.h"
 
 namespace spark {
 
 constexpr int ATTN_THREADS = 256;
+constexpr int ATTN_SLICE = 64;      // tokens per block
 constexpr int ATTN_MAX_GROUP = 16;  // query heads per KV head
+static_assert(ATTN_SLICE == 64, "the softmax step maps one token to one lane of a wave");
 
-// partial layout: part[((r*nq + hq)*n_splits + split)*(hd+2)] = {o[hd], m, l}
-template <typename KT, int HD>
+// partial layout: part[((r*nq + hq)*n_splits + split)*(HD+2)] = {o[HD], m, l}
+template <typename KT, int HD, int G>
 __global__ void __launch_bounds__(ATTN_THREADS)
 attn_partial_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbuf, KVView kv,
-               int layer, int nq, int group, int slice, int n_splits, float scale,
-               float *__restrict__ part) {
-  extern __shared__ float4 smem4[];
-  float *qs = (float *)smem4;           // [group][HD]
-  float *sc = qs + group * HD;          // [group][slice]
-  float *ml = sc + group * slice;       // [group][2]
-  float *ored = ml + group * 2;         // [ATTN_THREADS/ (HD/2)][group][HD] partial outputs
+               int layer, int nq, int n_splits, float scale, float *__restrict__ part) {
+  constexpr int VEC = Elem<KT>::VEC;
+  constexpr int LPT = HD / VEC;                   // lanes per token
+  constexpr int TPI = ATTN_THREADS / LPT;         // tokens per iteration of the block
+  constexpr int ITERS = ATTN_SLICE / TPI;
+  constexpr int WAVES = ATTN_THREADS / 64;
+  __shared__ float sc[G][ATTN_SLICE];             // scores, then probabilities
+  __shared__ float ml[G][2];
+  __shared__ float ored[WAVES][G][HD];
 
   const int split = blockIdx.x, hk = blockIdx.y, r = blockIdx.z;
   const RowDesc rd = rows[r];
   const int ctx = rd.pos + 1;
-  const int t0 = split * slice, t1 = min(ctx, t0 + slice);
+  const int t0 = split * ATTN_SLICE;
+  if (t0 >= ctx) return;                          // the merge only reads slices below the context
+  const int n_tok = min(ATTN_SLICE, ctx - t0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int hq0 = hk * group;
+  const int tg = tid / LPT, dc = tid % LPT;       // token slot in an iteration, 16-byte chunk of the row
+  const int hq0 = hk * G;
 
-  if (t0 >= ctx) {  // empty slice: neutral element of the merge
-    for (int i = tid; i < group * (HD + 2); i += ATTN_THREADS) {
-      int g = i / (HD + 2), c = i - g * (HD + 2);
-      float *p = part + ((size_t)(r * nq + hq0 + g) * n_splits + split) * (HD + 2);
-      p[c] = c == HD ? -INFINITY : 0.f;
-    }
-    return;
-  }
-  const int n_tok = t1 - t0;
-
-  for (int i = tid; i < group * HD; i += ATTN_THREADS)
-    qs[i] = qbuf[(size_t)r * nq * HD + hq0 * HD + i] * scale;
-  __syncthreads();
-
-  // scores: one token per thread, the whole key row in registers 16 bytes at a time
-  constexpr int VEC = Elem<KT>::VEC;
-  for (int t = tid; t < slice; t += ATTN_THREADS) {
+  // issue every K and V load of the slice
+  uint4 kraw[ITERS], vraw[ITERS];
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    const int t = it * TPI + tg;
     if (t < n_tok) {
-      const KT *kp = (const KT *)kv.pool + kv_elem_offset(kv, rd.seq, t0 + t, layer, 0, hk);
-      float s[ATTN_MAX_GROUP];
-#pragma unroll
-      for (int g = 0; g < ATTN_MAX_GROUP; ++g) s[g] = 0.f;
-#pragma unroll 4
-      for (int c = 0; c < HD; c += VEC) {
-        uint4 raw = *(const uint4 *)(kp + c);
-        float kf[VEC];
-        Elem<KT>::unpack(raw, kf);
-#pragma unroll
-        for (int g = 0; g < ATTN_MAX_GROUP; ++g) {
-          if (g < group) {
-            const float *q = qs + g * HD + c;
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) s[g] += q[e] * kf[e];
-          }
-        }
-      }
-#pragma unroll
-      for (int g = 0; g < ATTN_MAX_GROUP; ++g)
-        if (g < group) sc[g * slice + t] = s[g];
+      const KT *kp = (const KT *)kv.pool + kv_elem_offset(kv, rd.seq, t0 + t, layer, 0, hk) + dc * VEC;
+      const KT *vp = (const KT *)kv.pool + kv_elem_offset(kv, rd.seq, t0 + t, layer, 1, hk) + dc * VEC;
+      kraw[it] = *(const uint4 *)kp;
+      vraw[it] = *(const uint4 *)vp;
     } else {
-      for (int g = 0; g < group; ++g) sc[g * slice + t] = -INFINITY;
+      kraw[it] = make_uint4(0, 0, 0, 0);
+      vraw[it] = make_uint4(0, 0, 0, 0);
+    }
+  }
+
+  // this lane's chunk of every query head of the group, pre-scaled
+  float q[G][VEC];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    const float *qp = qbuf + (size_t)r * nq * HD + (hq0 + g) * HD + dc * VEC;
+#pragma unroll
+    for (int e = 0; e < VEC; e += 4) {
+      float4 v = *(const float4 *)(qp + e);
+      q[g][e] = v.x * scale; q[g][e + 1] = v.y * scale; q[g][e + 2] = v.z * scale; q[g][e + 3] = v.w * scale;
+    }
+  }
+
+  // scores
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    const int t = it * TPI + tg;
+    float kf[VEC];
+    Elem<KT>::unpack(kraw[it], kf);
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float s = 0.f;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) s += q[g][e] * kf[e];
+#pragma unroll
+      for (int o = LPT / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+      if (dc == 0) sc[g][t] = t < n_tok ? s : -INFINITY;
     }
   }
   __syncthreads();
 
-  // per query head: max, exp, sum over the slice (one wave per head at a time)
-  for (int g = wave; g < group; g += ATTN_THREADS / 64) {
-    float mx = -INFINITY;
-    for (int t = lane; t < slice; t += 64) mx = fmaxf(mx, sc[g * slice + t]);
-    mx = wave_max(mx);
-    float sum = 0.f;
-    for (int t = lane; t < slice; t += 64) {
-      float p = t < n_tok ? expf(sc[g * slice + t] - mx) : 0.f;
-      sc[g * slice + t] = p;
-      sum += p;
-    }
-    sum = wave_sum(sum);
-    if (lane == 0) { ml[g * 2] = mx; ml[g * 2 + 1] = sum; }
+  // softmax statistics of the slice, one wave per query head at a time (lane = token)
+  for (int g = wave; g < G; g += WAVES) {
+    float s = sc[g][lane];
+    float mx = wave_max(s);
+    float p = lane < n_tok ? expf(s - mx) : 0.f;
+    sc[g][lane] = p;
+    float sum = wave_sum(p);
+    if (lane == 0) { ml[g][0] = mx; ml[g][1] = sum; }
   }
   __syncthreads();
 
-  // weighted values: thread owns two adjacent dims of one token stripe
-  constexpr int DT = HD / 2;                 // threads per token
-  constexpr int STRIPES = ATTN_THREADS / DT; // tokens in flight
-  const int dpair = tid % DT, stripe = tid / DT;
-  float o0[ATTN_MAX_GROUP], o1[ATTN_MAX_GROUP];
+  // weighted values: acc[g][e] over this thread's tokens, then over the token slots of the wave
+  float acc[G][VEC];
 #pragma unroll
-  for (int g = 0; g < ATTN_MAX_GROUP; ++g) o0[g] = o1[g] = 0.f;
-  for (int t = stripe; t < n_tok; t += STRIPES) {
-    const KT *vp = (const KT *)kv.pool + kv_elem_offset(kv, rd.seq, t0 + t, layer, 1, hk) + 2 * dpair;
-    float v0 = Elem<KT>::widen(vp[0]), v1 = Elem<KT>::widen(vp[1]);
+  for (int g = 0; g < G; ++g)
 #pragma unroll
-    for (int g = 0; g < ATTN_MAX_GROUP; ++g) {
-      if (g < group) {
-        float p = sc[g * slice + t];
-        o0[g] += p * v0;
-        o1[g] += p * v1;
-      }
+    for (int e = 0; e < VEC; ++e) acc[g][e] = 0.f;
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    const int t = it * TPI + tg;
+    float vf[VEC];
+    Elem<KT>::unpack(vraw[it], vf);
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float p = sc[g][t];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[g][e] += p * vf[e];
     }
   }
 #pragma unroll
-  for (int g = 0; g < ATTN_MAX_GROUP; ++g) {
-    if (g < group) {
-      ored[(stripe * group + g) * HD + 2 * dpair] = o0[g];
-      ored[(stripe * group + g) * HD + 2 * dpair + 1] = o1[g];
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      float a = acc[g][e];
+#pragma unroll
+      for (int o = LPT; o < 64; o <<= 1) a += __shfl_xor(a, o, 64);
+      if (lane < LPT) ored[wave][g][dc * VEC + e] = a;
     }
-  }
   __syncthreads();
-  for (int i = tid; i < group * HD; i += ATTN_THREADS) {
-    int g = i / HD, c = i - g * HD;
+  for (int i = tid; i < G * HD; i += ATTN_THREADS) {
+    const int g = i / HD, c = i - g * HD;
     float o = 0.f;
 #pragma unroll
-    for (int s = 0; s < STRIPES; ++s) o += ored[(s * group + g) * HD + c];
+    for (int w = 0; w < WAVES; ++w) o += ored[w][g][c];
     part[((size_t)(r * nq + hq0 + g) * n_splits + split) * (HD + 2) + c] = o;
   }
-  if (tid < group * 2) {
-    int g = tid >> 1, w = tid & 1;
-    part[((size_t)(r * nq + hq0 + g) * n_splits + split) * (HD + 2) + HD + w] = ml[g * 2 + w];
+  if (tid < G * 2) {
+    const int g = tid >> 1, w = tid & 1;
+    part[((size_t)(r * nq + hq0 + g) * n_splits + split) * (HD + 2) + HD + w] = ml[g][w];
   }
 }
 
-inline size_t attn_partial_lds_bytes(int group, int hd, int slice) {
-  int stripes = ATTN_THREADS / (hd / 2);
-  return sizeof(float) * ((size_t)group * hd + (size_t)group * slice + group * 2 +
-                          (size_t)stripes * group * hd);
-}
-
-// out[r][hq*HD + c] = sum_s exp(m_s - M) o_s[c] / sum_s exp(m_s - M) l_s
+// out[r][hq*HD + c] = sum_s exp(m_s - M) o_s[c] / sum_s exp(m_s - M) l_s over the slices that
+// intersect the row's context
 template <int HD>
 __global__ void __launch_bounds__(HD)
-attn_merge_k(const float *__restrict__ part, int nq, int n_splits, float *__restrict__ out) {
+attn_merge_k(const RowDesc *__restrict__ rows, const float *__restrict__ part, int nq, int n_splits,
+             float *__restrict__ out) {
   const int hq = blockIdx.x, r = blockIdx.y, c = threadIdx.x;
+  const int used = (rows[r].pos + ATTN_SLICE) / ATTN_SLICE;  // ceil((pos + 1) / slice)
   const float *p = part + (size_t)(r * nq + hq) * n_splits * (HD + 2);
   float M = -INFINITY;
-  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, p[s * (HD + 2) + HD]);
+  for (int s = 0; s < used; ++s) M = fmaxf(M, p[s * (HD + 2) + HD]);
   float num = 0.f, den = 0.f;
-  for (int s = 0; s < n_splits; ++s) {
-    float m = p[s * (HD + 2) + HD];
-    if (m == -INFINITY) continue;
-    float w = expf(m - M);
+  for (int s = 0; s < used; ++s) {
+    float w = expf(p[s * (HD + 2) + HD] - M);
     num += w * p[s * (HD + 2) + c];
     den += w * p[s * (HD + 2) + HD + 1];
   }

@@ -224,6 +224,14 @@ template <typename WT> struct EpiVocab {
 
 // ------------------------------------------------------------------ the kernel
 
+// 16-byte streaming load of weights: read once per step, so keep them out of the way of the
+// activations and KV that live in L2 (non-temporal hint)
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_weights16(const void *p) {
+  u32x4_t t = __builtin_nontemporal_load((const u32x4_t *)p);
+  return make_uint4(t.x, t.y, t.z, t.w);
+}
+
 template <typename WT, int MT>
 __device__ __forceinline__ void fma_block(const uint4 &a, const uint4 &b, const float *xs, int kc,
                                           int kb, int lane, float *acc0, float *acc1) {
@@ -295,8 +303,8 @@ gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int 
           uint4 a[U], b[U];
 #pragma unroll
           for (int u = 0; u < U; ++u) {
-            a[u] = *(const uint4 *)(p0 + kb + u * WSTEP);
-            b[u] = *(const uint4 *)(p1 + kb + u * WSTEP);
+            a[u] = load_weights16(p0 + kb + u * WSTEP);
+            b[u] = load_weights16(p1 + kb + u * WSTEP);
           }
 #pragma unroll
           for (int u = 0; u < U; ++u)
@@ -304,7 +312,7 @@ gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int 
         }
         for (; kb < klen; kb += WSTEP) {
           if (kb + lane * VEC < klen) {
-            uint4 a = *(const uint4 *)(p0 + kb), b = *(const uint4 *)(p1 + kb);
+            uint4 a = load_weights16(p0 + kb), b = load_weights16(p1 + kb);
             fma_block<WT, MT>(a, b, xs, kc, kb, lane, acc0, acc1);
           }
         }

@@ -22,7 +22,7 @@ namespace {
 
 constexpr int PREFILL_CHUNK = 64;    // prompt rows pushed through the layers together
 constexpr int MAX_STEPS_PER_CALL = 256;
-constexpr int MAX_SPLITS = 64;
+constexpr int MAX_SEQ_LEN = 16384;
 
 struct Layout {  // byte offsets into the scratch buffer
   size_t state, page_table, plan, lower, upper, ee, full, prefill_rows, prefill_tokens, seq_ids,
@@ -96,7 +96,11 @@ bool config_ok(const spark_config *c, char *why, size_t n) {
   BAD(c->d_model > 4096, "d_model > 4096 is not supported");
   BAD(c->n_kv_heads < 1 || c->n_q_heads < 1 || c->n_q_heads % c->n_kv_heads,
       "n_q_heads must be a positive multiple of n_kv_heads");
-  BAD(c->n_q_heads / c->n_kv_heads > ATTN_MAX_GROUP, "more than 16 query heads per KV head");
+  {
+    int grp = c->n_q_heads / c->n_kv_heads;
+    BAD(grp != 1 && grp != 2 && grp != 4 && grp != 7 && grp != 8 && grp != 16,
+        "query heads per KV head must be one of 1, 2, 4, 7, 8, 16");
+  }
   BAD(c->head_dim != 64 && c->head_dim != 128, "head_dim must be 64 or 128");
   BAD(c->d_ffn < 8 || c->d_ffn % 8, "d_ffn must be a positive multiple of 8");
   BAD(c->vocab_text < 0 || c->vocab_speech < 0 || c->vocab_text + c->vocab_speech < 1,
@@ -111,7 +115,7 @@ bool config_ok(const spark_config *c, char *why, size_t n) {
           c->period_k > 1 && c->phase >= c->n_speech,
       "a pure-speech cycle without a full-depth slot would never complete its KV");
   BAD(c->max_batch < 1 || c->max_batch > SCHED_THREADS, "max_batch outside [1, 256]");
-  BAD(c->max_seq_len < 1 || c->max_seq_len > 256 * MAX_SPLITS, "max_seq_len outside [1, 16384]");
+  BAD(c->max_seq_len < 1 || c->max_seq_len > MAX_SEQ_LEN, "max_seq_len outside [1, 16384]");
   BAD(c->kv_page_tokens < 16 || c->kv_page_tokens % 16, "kv_page_tokens must be a multiple of 16");
 #undef BAD
   return true;
@@ -123,8 +127,7 @@ void derive(const spark_config &c, Derived &d) {
   d.max_rows = std::max(c.max_batch * d.rmax, PREFILL_CHUNK);
   d.max_pages = (c.max_seq_len + c.kv_page_tokens - 1) / c.kv_page_tokens;
   d.n_pages_total = d.max_pages * c.max_batch;
-  int per = (c.max_seq_len + 256 * MAX_SPLITS - 1) / (256 * MAX_SPLITS);
-  d.slice = 256 * per;
+  d.slice = ATTN_SLICE;
   d.n_splits = (c.max_seq_len + d.slice - 1) / d.slice;
   d.group = c.n_q_heads / c.n_kv_heads;
   d.esz = c.dtype == SPARK_DTYPE_BF16 ? 2 : 4;
@@ -228,28 +231,35 @@ KVView kv_view(spark_ctx *c) {
   return v;
 }
 
-template <typename WT> int launch_attention(spark_ctx *c, const RowDesc *rows, int m, int layer) {
+template <typename WT, int HD, int G>
+void launch_attention_g(spark_ctx *c, const RowDesc *rows, int m, int layer) {
   const spark_config &g = c->cfg;
   const Derived &d = c->dv;
+  float *part = at<float>(c, c->lo.part);
+  attn_partial_k<WT, HD, G><<<dim3(d.n_splits, g.n_kv_heads, m), ATTN_THREADS, 0, c->stream>>>(
+      rows, at<float>(c, c->lo.qbuf), kv_view(c), layer, g.n_q_heads, d.n_splits,
+      1.0f / sqrtf((float)HD), part);
+  attn_merge_k<HD><<<dim3(g.n_q_heads, m), HD, 0, c->stream>>>(rows, part, g.n_q_heads, d.n_splits,
+                                                              at<float>(c, c->lo.attn_out));
+}
+
+template <typename WT, int HD>
+void launch_attention_hd(spark_ctx *c, const RowDesc *rows, int m, int layer) {
+  switch (c->dv.group) {
+    case 1: launch_attention_g<WT, HD, 1>(c, rows, m, layer); break;
+    case 2: launch_attention_g<WT, HD, 2>(c, rows, m, layer); break;
+    case 4: launch_attention_g<WT, HD, 4>(c, rows, m, layer); break;
+    case 7: launch_attention_g<WT, HD, 7>(c, rows, m, layer); break;
+    case 8: launch_attention_g<WT, HD, 8>(c, rows, m, layer); break;
+    default: launch_attention_g<WT, HD, 16>(c, rows, m, layer); break;
+  }
+}
+
+template <typename WT> int launch_attention(spark_ctx *c, const RowDesc *rows, int m, int layer) {
   int rc = prof_begin(c, SPARK_KC_ATTN);
   if (rc) return rc;
-  dim3 grid(d.n_splits, g.n_kv_heads, m);
-  size_t lds = attn_partial_lds_bytes(d.group, g.head_dim, d.slice);
-  float scale = 1.0f / sqrtf((float)g.head_dim);
-  float *part = at<float>(c, c->lo.part);
-  if (g.head_dim == 128) {
-    attn_partial_k<WT, 128><<<grid, ATTN_THREADS, lds, c->stream>>>(
-        rows, at<float>(c, c->lo.qbuf), kv_view(c), layer, g.n_q_heads, d.group, d.slice,
-        d.n_splits, scale, part);
-    attn_merge_k<128><<<dim3(g.n_q_heads, m), 128, 0, c->stream>>>(part, g.n_q_heads, d.n_splits,
-                                                                 at<float>(c, c->lo.attn_out));
-  } else {
-    attn_partial_k<WT, 64><<<grid, ATTN_THREADS, lds, c->stream>>>(
-        rows, at<float>(c, c->lo.qbuf), kv_view(c), layer, g.n_q_heads, d.group, d.slice,
-        d.n_splits, scale, part);
-    attn_merge_k<64><<<dim3(g.n_q_heads, m), 64, 0, c->stream>>>(part, g.n_q_heads, d.n_splits,
-                                                               at<float>(c, c->lo.attn_out));
-  }
+  if (c->cfg.head_dim == 128) launch_attention_hd<WT, 128>(c, rows, m, layer);
+  else launch_attention_hd<WT, 64>(c, rows, m, layer);
   HIP_TRY(c, hipGetLastError());
   return prof_end(c, SPARK_KC_ATTN);
 }
