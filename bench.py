@@ -26,43 +26,6 @@ import workloads as wl
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 
 
-def synth_weights_on_device(shape, seed: int, device):
-    """N(0, 0.02) bf16 matrices drawn on the device (unit gains); same shapes as workloads.make_weights"""
-    import torch
-    g = torch.Generator(device=device)
-    g.manual_seed(seed)
-    out = {}
-    for name, shp in wl.tensor_shapes(shape).items():
-        if name in wl.GAIN_TENSORS:
-            out[name] = torch.ones(shp, dtype=torch.float32, device=device)
-        elif name in wl.FP32_TENSORS:
-            out[name] = torch.randn(shp, generator=g, dtype=torch.float32, device=device) * 0.02
-        else:
-            dt = torch.bfloat16 if shape.dtype == wl.DTYPE_BF16 else torch.float32
-            t = torch.empty(shp, dtype=dt, device=device)
-            flat = t.view(-1)
-            step = 1 << 28
-            for lo in range(0, flat.numel(), step):   # bounded temporaries
-                hi = min(flat.numel(), lo + step)
-                flat[lo:hi] = (torch.randn(hi - lo, generator=g, dtype=torch.float32, device=device)
-                               * 0.02).to(dt)
-            out[name] = t
-    return out
-
-
-def weights_to_host(dev_weights: dict) -> dict:
-    """device tensors -> numpy arrays in the oracle's conventions (bf16 as uint16 bit patterns)"""
-    import torch
-    out = {}
-    for k, t in dev_weights.items():
-        c = t.cpu()
-        if c.dtype == torch.bfloat16:
-            out[k] = c.view(torch.int16).numpy().view(np.uint16)
-        else:
-            out[k] = c.numpy()
-    return out
-
-
 def step_bytes(shape, sched, ctx_len: float):
     """algorithmic HBM bytes of one early-exit step and one full-depth step at context length T:
     each needed weight matrix once, plus the KV of the layers that run"""
@@ -108,7 +71,7 @@ def main() -> int:
 
     t0 = time.time()
     if shape.dtype == wl.DTYPE_BF16:
-        dev_w = synth_weights_on_device(shape, 0, device)
+        dev_w = wl.make_weights_on_device(shape, seed=0, device="cuda:0")
     else:
         dev_w = wl.make_weights(shape, seed=0)
     sp = Spark(shape, sched, dev_w, max_batch=1, max_seq_len=max_seq, kv_page_tokens=64, device="cuda:0")
@@ -178,7 +141,7 @@ def main() -> int:
     cpu = None
     if args.cpu_steps > 0:
         from oracle import binding as ob
-        host_w = weights_to_host(sp.dev_weights)
+        host_w = wl.device_weights_to_host(sp.dev_weights)
         om = ob.Model(shape, sched, host_w, max_seq_len=64)
         osq = om.open(0)
         osq.prefill(prompt[:4])

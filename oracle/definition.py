@@ -4,7 +4,7 @@ No KV cache and no early exit: the whole token sequence is pushed through every 
 with an explicit T x T causal mask, which is the textbook definition of what a decoder-only
 model computes (Sec. III: hidden states h_t^(l), l = 1..L, final head g_L, Eq. 1).  The C oracle's
 incremental decoding is pinned to this file; this file's own pieces are pinned to library routines
-in tests/test_oracle_definition.py.
+in tests/test_oracle_primitives.py.
 
 Conventions (the paper treats the backbone as a black box; these follow the stated workload
 shapes): pre-norm residual blocks, RMSNorm with gain, rotary embedding on pairs (i, i + hd/2) with
@@ -59,9 +59,17 @@ def silu(x: np.ndarray) -> np.ndarray:
     return x / (1.0 + np.exp(-x))
 
 
-def hidden_states(shape, weights: dict, tokens: np.ndarray) -> np.ndarray:
+def bf16_storage(x: np.ndarray) -> np.ndarray:
+    """values as they read back from a bf16 store (library cast: fp32 -> bf16, nearest even)"""
+    import torch
+    return torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+
+
+def hidden_states(shape, weights: dict, tokens: np.ndarray, kv_bf16: bool = False) -> np.ndarray:
     """h[l, t, :] for l = 0..L (l = 0 is the embedding, l >= 1 is the residual stream after
-    block l) of every position of `tokens`, all computed in one full-sequence pass."""
+    block l) of every position of `tokens`, all computed in one full-sequence pass.
+    kv_bf16: keys (after the rotary embedding) and values pass through a bf16 store, as they do
+    in a bf16 KV cache."""
     T = len(tokens)
     L, d, hd = shape.n_layers, shape.d_model, shape.head_dim
     nq, nkv = shape.n_q_heads, shape.n_kv_heads
@@ -75,6 +83,8 @@ def hidden_states(shape, weights: dict, tokens: np.ndarray) -> np.ndarray:
         k = (n @ widen(weights["wk"][l]).T).reshape(T, nkv, hd)
         v = (n @ widen(weights["wv"][l]).T).reshape(T, nkv, hd)
         q, k = rope(q, pos, shape.rope_base), rope(k, pos, shape.rope_base)
+        if kv_bf16:
+            k, v = bf16_storage(k), bf16_storage(v)
         a = causal_attention(q, k, v).reshape(T, nq * hd)
         h = h + a @ widen(weights["wo"][l]).T
         n = rmsnorm(h, weights["mlp_norm"][l], shape.rms_eps)

@@ -18,7 +18,7 @@ def say(msg: str) -> None:
 
 
 def compare_run(spark, shape, sched, weights, prompts, offsets, n_steps, forced_seed=2,
-                check_kv_every=0, chunk=1, oracle_kind="f32", label=""):
+                check_kv_every=0, chunk=1, oracle_kind="f32", label="", kv_round_bf16=None):
     """Run len(prompts) sequences for n_steps teacher-forced steps on both sides.
 
     chunk > 1 uses spark_decode with that many steps per call.  Returns a dict of what was seen.
@@ -27,7 +27,10 @@ def compare_run(spark, shape, sched, weights, prompts, offsets, n_steps, forced_
     tol = TOL[shape.dtype]
     B = len(prompts)
     max_len = max(len(p) for p in prompts) + n_steps + 1
-    om = ob.Model(shape, sched, weights, max_seq_len=max_len, kind=oracle_kind)
+    if kv_round_bf16 is None:     # the KV cache of a bf16 model stores bf16 on both sides
+        kv_round_bf16 = shape.dtype == wl.DTYPE_BF16
+    om = ob.Model(shape, sched, weights, max_seq_len=max_len, kind=oracle_kind,
+                  kv_round_bf16=kv_round_bf16)
     oseqs = [om.open(off) for off in offsets]
     sids = [spark.seq_open(off) for off in offsets]
     forced = np.stack([wl.make_forced_stream(shape, n_steps, sched.n_text, sched.n_speech, off,

@@ -191,3 +191,43 @@ def test_state_errors(tiny):
     assert s.step()[0] == 0 and s.step()[0] == 0 and s.step()[0] == 0
     assert s.step()[0] == -3                     # context full (16 prompt + 3 = 18 + held input)
     s.close(); m.close()
+
+
+def test_bf16_model_with_bf16_kv_storage():
+    """bf16 weights and a KV cache that stores bf16 (rounded once, when written): standard
+    decoding equals the numpy definition with the same storage rounding, and teacher-forced
+    SPAR-K equals standard decoding, cache entry for cache entry"""
+    w = wl.TINY
+    shape = w.shape.replace(dtype=wl.DTYPE_BF16)
+    sched = w.schedule
+    weights = wl.make_weights(shape, seed=4, gain_std=0.1)
+    prompt = wl.make_prompt(shape, 12, seed=1)
+    n = 26
+    forced = wl.make_forced_stream(shape, n, sched.n_text, sched.n_speech, 0, seed=2)
+    tokens = stream_positions(prompt, forced)
+    hs = od.hidden_states(shape, weights, tokens, kv_bf16=True)
+    hs_plain = od.hidden_states(shape, weights, tokens, kv_bf16=False)
+    assert np.max(np.abs(hs[-1] - hs_plain[-1])) > 1e-4          # the storage format matters
+    p0 = len(prompt) - 1
+    L, e = shape.n_layers, sched.exit_layer
+    for kind, tol in (("f64", 1e-9), ("f32", 5e-4)):
+        m = ob.Model(shape, sched, weights, max_seq_len=len(tokens) + 1, kind=kind, kv_round_bf16=True)
+        s, ref = m.open(), m.open()
+        s.prefill(prompt); ref.prefill(prompt)
+        for i in range(n):
+            rc, tok, depth, logits = s.step(forced_next=int(forced[i]))
+            rc2, rtok, rlogits, h_e = ref.step_standard(forced_next=int(forced[i]), capture_layer=e)
+            assert rc == 0 and rc2 == 0
+            pos = p0 + i
+            if depth == L:
+                assert np.max(np.abs(logits - od.final_logits(shape, weights, hs[L, pos]))) < tol
+                assert np.max(np.abs(logits - rlogits)) < tol
+                for l in range(L):
+                    for p in range(max(0, pos - 4), pos + 1):
+                        k1, v1 = s.kv(l, p); k2, v2 = ref.kv(l, p)
+                        assert np.array_equal(k1, k2) and np.array_equal(v1, v2)
+                        # what is stored is representable in bf16
+                        assert np.array_equal(k1, od.bf16_storage(k1))
+            else:
+                assert np.max(np.abs(logits - od.lens_logits(shape, weights, hs[e, pos]))) < tol
+        s.close(); ref.close(); m.close()

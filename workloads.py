@@ -201,3 +201,40 @@ def make_forced_stream(shape: ModelShape, n: int, n_text: int, n_speech: int, sl
 def make_prompt_lengths(n_seq: int, lo: int, hi: int, seed: int = 3) -> np.ndarray:
     rng = np.random.Generator(np.random.Philox(np.random.SeedSequence((seed, 303))))
     return rng.integers(lo, hi + 1, size=n_seq, dtype=np.int32)
+
+
+# --------------------------------------------------------------------------- large models
+
+def make_weights_on_device(shape: ModelShape, seed: int = 0, std: float = 0.02, device="cuda:0") -> dict:
+    """The same tensors as make_weights (unit gains), drawn with torch's generator on the GPU:
+    billions of parameters in about a second.  Returns torch device tensors."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    dt = torch.bfloat16 if shape.dtype == DTYPE_BF16 else torch.float32
+    out = {}
+    for name, shp in tensor_shapes(shape).items():
+        if name in GAIN_TENSORS:
+            out[name] = torch.ones(shp, dtype=torch.float32, device=device)
+        elif name in FP32_TENSORS:
+            out[name] = torch.randn(shp, generator=g, dtype=torch.float32, device=device) * std
+        else:
+            t = torch.empty(shp, dtype=dt, device=device)
+            flat = t.view(-1)
+            step = 1 << 28          # bounded fp32 temporaries
+            for lo in range(0, flat.numel(), step):
+                hi = min(flat.numel(), lo + step)
+                flat[lo:hi] = (torch.randn(hi - lo, generator=g, dtype=torch.float32, device=device)
+                               * std).to(dt)     # rounded to bf16 exactly once, here
+            out[name] = t
+    return out
+
+
+def device_weights_to_host(dev_weights: dict) -> dict:
+    """torch device tensors -> numpy arrays in make_weights' conventions (bf16 as uint16 bits)"""
+    import torch
+    out = {}
+    for k, t in dev_weights.items():
+        c = t.cpu()
+        out[k] = c.view(torch.int16).numpy().view(np.uint16) if c.dtype == torch.bfloat16 else c.numpy()
+    return out
