@@ -5,7 +5,8 @@
 //
 // Few KV heads cannot fill 256 CUs, so the context is cut into slices of 64 tokens: one block per
 // (slice, kv head, row) produces an unnormalised partial (max, sum, weighted values) for all the
-// query heads of the group, and a second kernel merges the slices.  Inside a block a token's key
+// query heads of the group, and the block that finishes last for a (row, kv head) merges the
+// slices (arrival counter, device-scope accesses), so no second launch is needed.  Inside a block a token's key
 // (and value) vector is spread over LPT consecutive lanes, 16 bytes each, so a wave reads
 // 64/LPT whole rows per instruction; all K and V loads of the slice are issued before any use.
 #pragma once
@@ -18,11 +19,12 @@ constexpr int ATTN_SLICE = 64;      // tokens per block
 constexpr int ATTN_MAX_GROUP = 16;  // query heads per KV head
 static_assert(ATTN_SLICE == 64, "the softmax step maps one token to one lane of a wave");
 
-// partial layout: part[((r*nq + hq)*n_splits + split)*(HD+2)] = {o[HD], m, l}
+// partial layout: part[((r*nq + hq)*n_splits + split)*(HD+4)] = {o[HD], m, l, pad, pad}
 template <typename KT, int HD, int G>
 __global__ void __launch_bounds__(ATTN_THREADS)
-attn_partial_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbuf, KVView kv,
-               int layer, int nq, int n_splits, float scale, float *__restrict__ part) {
+attn_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbuf, KVView kv,
+            int layer, int nq, int n_splits, float scale, float *__restrict__ part,
+            int *__restrict__ arrivals, float *__restrict__ out) {
   constexpr int VEC = Elem<KT>::VEC;
   constexpr int LPT = HD / VEC;                   // lanes per token
   constexpr int TPI = ATTN_THREADS / LPT;         // tokens per iteration of the block
@@ -31,6 +33,7 @@ attn_partial_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbuf,
   __shared__ float sc[G][ATTN_SLICE];             // scores, then probabilities
   __shared__ float ml[G][2];
   __shared__ float ored[WAVES][G][HD];
+  __shared__ int s_last;
 
   const int split = blockIdx.x, hk = blockIdx.y, r = blockIdx.z;
   const RowDesc rd = rows[r];
@@ -127,37 +130,75 @@ attn_partial_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbuf,
       if (lane < LPT) ored[wave][g][dc * VEC + e] = a;
     }
   __syncthreads();
+  constexpr int PS = HD + 4;   // floats per partial: o[HD], m, l, 2 pad (keeps rows 16-byte aligned)
   for (int i = tid; i < G * HD; i += ATTN_THREADS) {
     const int g = i / HD, c = i - g * HD;
     float o = 0.f;
 #pragma unroll
     for (int w = 0; w < WAVES; ++w) o += ored[w][g][c];
-    part[((size_t)(r * nq + hq0 + g) * n_splits + split) * (HD + 2) + c] = o;
+    store_device_scope(part + ((size_t)(r * nq + hq0 + g) * n_splits + split) * PS + c, o);
   }
   if (tid < G * 2) {
     const int g = tid >> 1, w = tid & 1;
-    part[((size_t)(r * nq + hq0 + g) * n_splits + split) * (HD + 2) + HD + w] = ml[g][w];
+    store_device_scope(part + ((size_t)(r * nq + hq0 + g) * n_splits + split) * PS + HD + w, ml[g][w]);
   }
-}
 
-// out[r][hq*HD + c] = sum_s exp(m_s - M) o_s[c] / sum_s exp(m_s - M) l_s over the slices that
-// intersect the row's context
-template <int HD>
-__global__ void __launch_bounds__(HD)
-attn_merge_k(const RowDesc *__restrict__ rows, const float *__restrict__ part, int nq, int n_splits,
-             float *__restrict__ out) {
-  const int hq = blockIdx.x, r = blockIdx.y, c = threadIdx.x;
-  const int used = (rows[r].pos + ATTN_SLICE) / ATTN_SLICE;  // ceil((pos + 1) / slice)
-  const float *p = part + (size_t)(r * nq + hq) * n_splits * (HD + 2);
-  float M = -INFINITY;
-  for (int s = 0; s < used; ++s) M = fmaxf(M, p[s * (HD + 2) + HD]);
-  float num = 0.f, den = 0.f;
-  for (int s = 0; s < used; ++s) {
-    float w = expf(p[s * (HD + 2) + HD] - M);
-    num += w * p[s * (HD + 2) + c];
-    den += w * p[s * (HD + 2) + HD + 1];
+  // The block that arrives last for this (row, kv head) merges the slices:
+  // out = sum_s exp(m_s - M) o_s / sum_s exp(m_s - M) l_s.
+  // Partials are written through to memory (device-scope stores) and counted with a device-scope
+  // atomic; the merging block drops its stale cache lines once and then reads them normally.
+  const int used = (rd.pos + ATTN_SLICE) / ATTN_SLICE;   // slices that intersect the context
+  wait_memory_ops();                                      // partials written before the count
+  __syncthreads();
+  if (tid == 0) {
+    int *cnt = arrivals + r * (nq / G) + hk;
+    const int prev = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_last = prev == used - 1;
+    if (s_last) {
+      __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next layer
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // one cache invalidate for the block
+    }
   }
-  out[(size_t)r * nq * HD + hq * HD + c] = num / den;
+  __syncthreads();
+  if (!s_last) return;
+
+  // normalised slice weights wn[g][s] = exp(m_s - M) / sum_s' exp(m_s' - M) l_s', lane = slice
+  float *wn = &ored[0][0][0];                             // [G][used], used <= 256 <= WAVES*HD
+  for (int g = wave; g < G; g += WAVES) {
+    const float *p = part + (size_t)(r * nq + hq0 + g) * n_splits * PS;
+    float M = -INFINITY;
+    for (int s0 = 0; s0 < used; s0 += 64) {
+      const int sl = s0 + lane;
+      M = fmaxf(M, sl < used ? p[(size_t)sl * PS + HD] : -INFINITY);
+    }
+    M = wave_max(M);
+    float den = 0.f;
+    for (int s0 = 0; s0 < used; s0 += 64) {
+      const int sl = s0 + lane;
+      if (sl < used) {
+        const float w = expf(p[(size_t)sl * PS + HD] - M);
+        wn[g * used + sl] = w;
+        den += w * p[(size_t)sl * PS + HD + 1];
+      }
+    }
+    den = wave_sum(den);
+    const float inv = 1.0f / den;
+    for (int s0 = 0; s0 < used; s0 += 64)
+      if (s0 + lane < used) wn[g * used + s0 + lane] *= inv;
+  }
+  __syncthreads();
+  for (int i = tid; i < G * (HD / 4); i += ATTN_THREADS) {
+    const int g = i / (HD / 4), c = (i - g * (HD / 4)) * 4;
+    const float *p = part + (size_t)(r * nq + hq0 + g) * n_splits * PS + c;
+    float4 acc4 = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+    for (int sl = 0; sl < used; ++sl) {
+      const float4 o = *(const float4 *)(p + (size_t)sl * PS);
+      const float w = wn[g * used + sl];
+      acc4.x += w * o.x; acc4.y += w * o.y; acc4.z += w * o.z; acc4.w += w * o.w;
+    }
+    *(float4 *)(out + (size_t)r * nq * HD + (hq0 + g) * HD + c) = acc4;
+  }
 }
 
 }  // namespace spark

@@ -66,6 +66,18 @@ template <> struct Elem<bf16_t> {
   }
 };
 
+// Data handed from one workgroup to another inside a kernel goes through device-scope relaxed
+// atomic accesses: they are served at the level where all XCDs agree, so neither side has to
+// flush or invalidate a whole L2 (each of the 8 XCDs has its own).
+__device__ __forceinline__ void store_device_scope(float *p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_device_scope(const float *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// wait until every memory operation this wave has issued is complete
+__device__ __forceinline__ void wait_memory_ops() { __builtin_amdgcn_s_waitcnt(0); }
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

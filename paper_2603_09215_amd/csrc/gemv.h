@@ -22,6 +22,14 @@ template <int VEC> __device__ __forceinline__ int lds_pos(int k) {
   return k;
 }
 
+// The last 512-element block of a staged row may be partial; lanes whose weights were masked to
+// zero still multiply what lies there, so it must be finite: fill it with zeros.
+template <int VEC> __device__ __forceinline__ void zero_tail(float *xrow, int klen) {
+  const int end = (klen + 511) & ~511;
+  for (int k = klen + threadIdx.x * 4; k < end; k += GEMV_THREADS * 4)
+    *(float4 *)(xrow + lds_pos<VEC>(k)) = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
 // ------------------------------------------------------------------ prologues (fill LDS)
 
 // rows come straight from a buffer: row r of the pass, or the row's hidden-state slot
@@ -38,6 +46,7 @@ struct ProPlain {
       const float *row = src + (size_t)(indirect ? rd[mm].x_slot : tile0 + mm) * stride + k0;
       for (int k = threadIdx.x * 4; k < klen; k += GEMV_THREADS * 4)
         *(float4 *)(xs + m * kc + lds_pos<VEC>(k)) = *(const float4 *)(row + k);
+      zero_tail<VEC>(xs + m * kc, klen);
     }
   }
 };
@@ -80,6 +89,7 @@ struct ProNorm {
         float4 o = make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w);
         *(float4 *)(xs + m * kc + lds_pos<VEC>(k)) = o;
       }
+      zero_tail<VEC>(xs + m * kc, d);
     }
   }
 };
@@ -232,6 +242,33 @@ __device__ __forceinline__ uint4 load_weights16(const void *p) {
   return make_uint4(t.x, t.y, t.z, t.w);
 }
 
+constexpr int GEMV_U = 2;  // 16-byte loads in flight per weight row and pipeline stage
+
+// One pipeline stage of weights: GEMV_U consecutive 1 KiB segments of both rows of a task.
+struct WStage {
+  uint4 a[GEMV_U], b[GEMV_U];
+};
+
+// Issue the loads of elements [kb, kb + U*WSTEP) of a chunk of length klen (lanes beyond klen and
+// waves without a task get zeros).
+template <typename WT>
+__device__ __forceinline__ void issue_stage(WStage &s, const WT *p0, const WT *p1, int kb, int klen,
+                                            int lane, bool valid) {
+  constexpr int VEC = Elem<WT>::VEC;
+  constexpr int WSTEP = 64 * VEC;
+#pragma unroll
+  for (int u = 0; u < GEMV_U; ++u) {
+    const int k = kb + u * WSTEP + lane * VEC;
+    if (valid && k < klen) {
+      s.a[u] = load_weights16(p0 + k);
+      s.b[u] = load_weights16(p1 + k);
+    } else {
+      s.a[u] = make_uint4(0, 0, 0, 0);
+      s.b[u] = make_uint4(0, 0, 0, 0);
+    }
+  }
+}
+
 template <typename WT, int MT>
 __device__ __forceinline__ void fma_block(const uint4 &a, const uint4 &b, const float *xs, int kc,
                                           int kb, int lane, float *acc0, float *acc1) {
@@ -256,6 +293,12 @@ __device__ __forceinline__ void fma_block(const uint4 &a, const uint4 &b, const 
 // grid.x: blocks that share the weight rows; grid.y: tiles of MT activation rows.
 // kc: activation elements of one row held in LDS at a time (multiple of 512).
 // Dynamic LDS: (MT*kc + GEMV_WAVES*MT) floats.
+//
+// The weight stream is software-pipelined across everything else the wave does: the loads of the
+// next stage (next segments of the row, next chunk, or the first segments of the wave's next
+// task) are issued before the current stage is consumed, and the very first stage is issued
+// before the prologue touches the activations, so the norm, the reduction and the epilogue all
+// run under outstanding HBM requests.
 template <typename WT, int MT, typename Pro, typename Epi>
 __global__ void __launch_bounds__(GEMV_THREADS)
 gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int n_in, int n_tasks,
@@ -265,7 +308,7 @@ gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int 
   float *red = xs + MT * kc;           // [GEMV_WAVES][MT] partial sums of squares
   constexpr int VEC = Elem<WT>::VEC;
   constexpr int WSTEP = 64 * VEC;
-  constexpr int U = 4;
+  constexpr int GSTEP = GEMV_U * WSTEP;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int tile0 = blockIdx.y * MT;
   const int n_valid = min(MT, m_rows - tile0);
@@ -280,11 +323,19 @@ gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int 
   typename Epi::State st;
   epi.init(st);
 
+  // prime the pipeline: first stage of this wave's first task
+  WStage nxt;
+  const WT *r0, *r1;
+  bool valid = wave_global < n_tasks;
+  epi.weight_rows(valid ? wave_global : 0, r0, r1);
+  issue_stage<WT>(nxt, r0, r1, 0, min(kc, n_in), lane, valid);
+
   for (int round = 0; round < rounds; ++round) {
     const int task = round * n_waves + wave_global;
-    const bool valid = task < n_tasks;
-    const WT *r0, *r1;
-    epi.weight_rows(valid ? task : 0, r0, r1);
+    const int task_n = task + n_waves;
+    const bool valid_n = round + 1 < rounds && task_n < n_tasks;
+    const WT *r0n, *r1n;
+    epi.weight_rows(valid_n ? task_n : 0, r0n, r1n);
     float acc0[MT], acc1[MT];
 #pragma unroll
     for (int m = 0; m < MT; ++m) acc0[m] = acc1[m] = 0.f;
@@ -296,24 +347,21 @@ gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int 
         pro.template stage<VEC, MT>(xs, kc, rd, tile0, n_valid, k0, klen, red);
         __syncthreads();
       }
-      if (valid) {
-        const WT *p0 = r0 + k0 + lane * VEC, *p1 = r1 + k0 + lane * VEC;
-        int kb = 0;
-        for (; kb + U * WSTEP <= klen; kb += U * WSTEP) {
-          uint4 a[U], b[U];
-#pragma unroll
-          for (int u = 0; u < U; ++u) {
-            a[u] = load_weights16(p0 + kb + u * WSTEP);
-            b[u] = load_weights16(p1 + kb + u * WSTEP);
-          }
-#pragma unroll
-          for (int u = 0; u < U; ++u)
-            fma_block<WT, MT>(a[u], b[u], xs, kc, kb + u * WSTEP, lane, acc0, acc1);
+      const int n_groups = (klen + GSTEP - 1) / GSTEP;
+      for (int g = 0; g < n_groups; ++g) {
+        const WStage cur = nxt;
+        if (g + 1 < n_groups) {
+          issue_stage<WT>(nxt, r0 + k0, r1 + k0, (g + 1) * GSTEP, klen, lane, valid);
+        } else if (chunk + 1 < n_chunks) {
+          issue_stage<WT>(nxt, r0 + k0 + kc, r1 + k0 + kc, 0, min(kc, n_in - k0 - kc), lane, valid);
+        } else if (round + 1 < rounds) {
+          issue_stage<WT>(nxt, r0n, r1n, 0, min(kc, n_in), lane, valid_n);
         }
-        for (; kb < klen; kb += WSTEP) {
-          if (kb + lane * VEC < klen) {
-            uint4 a = load_weights16(p0 + kb), b = load_weights16(p1 + kb);
-            fma_block<WT, MT>(a, b, xs, kc, kb, lane, acc0, acc1);
+        if (valid) {
+#pragma unroll
+          for (int u = 0; u < GEMV_U; ++u) {
+            const int kb = g * GSTEP + u * WSTEP;
+            if (kb < klen) fma_block<WT, MT>(cur.a[u], cur.b[u], xs, kc, kb, lane, acc0, acc1);
           }
         }
       }
@@ -328,6 +376,9 @@ gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int 
       }
       if (lane < n_valid) epi.finish(task, tile0 + lane, mine, y0, y1, st);
     }
+    valid = valid_n;
+    r0 = r0n;
+    r1 = r1n;
   }
   if (lane < n_valid) {
     RowDesc mine = rd[0];

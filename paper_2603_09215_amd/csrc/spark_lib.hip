@@ -26,7 +26,7 @@ constexpr int MAX_SEQ_LEN = 16384;
 
 struct Layout {  // byte offsets into the scratch buffer
   size_t state, page_table, plan, lower, upper, ee, full, prefill_rows, prefill_tokens, seq_ids,
-      forced, step_flags, out_tokens, out_depth, best, hidden, qbuf, attn_out, part, act, lens_u,
+      forced, step_flags, out_tokens, out_depth, best, arrivals, hidden, qbuf, attn_out, part, act, lens_u,
       logits, rope, inv_freq, total;
 };
 
@@ -154,10 +154,11 @@ void layout(const spark_config &c, const Derived &d, Layout &l) {
   l.out_tokens = take(sizeof(int) * (size_t)MAX_STEPS_PER_CALL * c.max_batch);
   l.out_depth = take(sizeof(int) * (size_t)MAX_STEPS_PER_CALL * c.max_batch);
   l.best = take(sizeof(unsigned long long) * c.max_batch);
+  l.arrivals = take(sizeof(int) * (size_t)d.max_rows * c.n_kv_heads);
   l.hidden = take(sizeof(float) * ((size_t)c.max_batch * d.rmax + PREFILL_CHUNK) * c.d_model);
   l.qbuf = take(sizeof(float) * d.max_rows * qw);
   l.attn_out = take(sizeof(float) * d.max_rows * qw);
-  l.part = take(sizeof(float) * (size_t)d.max_rows * c.n_q_heads * d.n_splits * (c.head_dim + 2));
+  l.part = take(sizeof(float) * (size_t)d.max_rows * c.n_q_heads * d.n_splits * (c.head_dim + 4));
   l.act = take(sizeof(float) * (size_t)d.max_rows * c.d_ffn);
   l.lens_u = take(sizeof(float) * (size_t)c.max_batch * c.d_model);
   l.logits = take(sizeof(float) * (size_t)c.max_batch * d.V);
@@ -205,16 +206,23 @@ int launch_gemv(spark_ctx *c, const Pro &pro, const Epi &epi, const RowDesc *row
   int kc = std::min((int)align_up(n_in, 512), kc_cap);
   if (whole_row && kc < n_in) return fail(c, SPARK_EINVAL, "row of %d does not fit in LDS", n_in);
   size_t lds = sizeof(float) * ((size_t)mt * kc + GEMV_WAVES * mt);
-  int bx = std::min((n_tasks + GEMV_WAVES - 1) / GEMV_WAVES, c->n_cu * (lds > 32768 ? 2 : 4));
+  // one resident set of blocks: the kernel loops over its tasks, so the grid is sized to what the
+  // chip holds at once (no second wave of blocks with a cold pipeline)
+  void (*kern)(Pro, Epi, const RowDesc *, int, int, int, int) = nullptr;
+  switch (mt) {
+    case 1: kern = gemv_rows_k<WT, 1, Pro, Epi>; break;
+    case 2: kern = gemv_rows_k<WT, 2, Pro, Epi>; break;
+    case 3: kern = gemv_rows_k<WT, 3, Pro, Epi>; break;
+    default: kern = gemv_rows_k<WT, 4, Pro, Epi>; break;
+  }
+  int occ = 0;
+  HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, GEMV_THREADS, lds));
+  occ = std::max(1, std::min(occ, 4));
+  int bx = std::min((n_tasks + GEMV_WAVES - 1) / GEMV_WAVES, c->n_cu * occ);
   dim3 grid(bx, (m_rows + mt - 1) / mt), block(GEMV_THREADS);
   int rc = prof_begin(c, kclass);
   if (rc) return rc;
-  switch (mt) {
-    case 1: gemv_rows_k<WT, 1, Pro, Epi><<<grid, block, lds, c->stream>>>(pro, epi, rows, m_rows, n_in, n_tasks, kc); break;
-    case 2: gemv_rows_k<WT, 2, Pro, Epi><<<grid, block, lds, c->stream>>>(pro, epi, rows, m_rows, n_in, n_tasks, kc); break;
-    case 3: gemv_rows_k<WT, 3, Pro, Epi><<<grid, block, lds, c->stream>>>(pro, epi, rows, m_rows, n_in, n_tasks, kc); break;
-    default: gemv_rows_k<WT, 4, Pro, Epi><<<grid, block, lds, c->stream>>>(pro, epi, rows, m_rows, n_in, n_tasks, kc); break;
-  }
+  kern<<<grid, block, lds, c->stream>>>(pro, epi, rows, m_rows, n_in, n_tasks, kc);
   HIP_TRY(c, hipGetLastError());
   return prof_end(c, kclass);
 }
@@ -236,11 +244,9 @@ void launch_attention_g(spark_ctx *c, const RowDesc *rows, int m, int layer) {
   const spark_config &g = c->cfg;
   const Derived &d = c->dv;
   float *part = at<float>(c, c->lo.part);
-  attn_partial_k<WT, HD, G><<<dim3(d.n_splits, g.n_kv_heads, m), ATTN_THREADS, 0, c->stream>>>(
+  attn_rows_k<WT, HD, G><<<dim3(d.n_splits, g.n_kv_heads, m), ATTN_THREADS, 0, c->stream>>>(
       rows, at<float>(c, c->lo.qbuf), kv_view(c), layer, g.n_q_heads, d.n_splits,
-      1.0f / sqrtf((float)HD), part);
-  attn_merge_k<HD><<<dim3(g.n_q_heads, m), HD, 0, c->stream>>>(rows, part, g.n_q_heads, d.n_splits,
-                                                              at<float>(c, c->lo.attn_out));
+      1.0f / sqrtf((float)HD), part, at<int>(c, c->lo.arrivals), at<float>(c, c->lo.attn_out));
 }
 
 template <typename WT, int HD>
