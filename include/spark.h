@@ -175,7 +175,8 @@ const char *spark_last_error(const spark_ctx *ctx);
 #define SPARK_KC_DOWN 4
 #define SPARK_KC_LENS 5
 #define SPARK_KC_HEAD 6
-#define SPARK_KC_COUNT 7
+#define SPARK_KC_PASS 7   /* the persistent kernel that runs a whole run of layers in one launch */
+#define SPARK_KC_COUNT 8
 int spark_profile_select(spark_ctx *ctx, int32_t kernel_class);
 int spark_profile_read(spark_ctx *ctx, int64_t *n_launches, double *total_ms);
 

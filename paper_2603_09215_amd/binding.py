@@ -15,7 +15,7 @@ HERE = pathlib.Path(__file__).resolve().parent
 LIB_PATH = HERE / "libspark.so"
 
 SPARK_MAX_PERIOD = 16
-KC = {"qkv": 0, "attn": 1, "oproj": 2, "gateup": 3, "down": 4, "lens": 5, "head": 6}
+KC = {"qkv": 0, "attn": 1, "oproj": 2, "gateup": 3, "down": 4, "lens": 5, "head": 6, "pass": 7}
 
 ERRORS = {-1: "SPARK_EINVAL", -2: "SPARK_ENOSEQ", -3: "SPARK_ENOMEM", -4: "SPARK_ESTATE",
           -5: "SPARK_EHIP", -6: "SPARK_ENAN"}

@@ -1,45 +1,53 @@
 // Grouped-query attention of a few query rows over the paged KV cache (decode, flush, prefill
-// chunks).  Row r attends cache entries 0..pos_r of its own sequence; since the projection kernel
+// chunks).  Row r attends cache entries 0..pos_r of its own sequence; since the projection step
 // has already written K/V of every row of the pass, this is causal inside a batch of pending
 // positions as well (the "length-K causal mask" of Sec. IV-B.3).
 //
-// Few KV heads cannot fill 256 CUs, so the context is cut into slices of 64 tokens: one block per
+// Few KV heads cannot fill 256 CUs, so the context is cut into slices of 64 tokens: one task per
 // (slice, kv head, row) produces an unnormalised partial (max, sum, weighted values) for all the
-// query heads of the group, and the block that finishes last for a (row, kv head) merges the
-// slices (arrival counter, device-scope accesses), so no second launch is needed.  Inside a block a token's key
-// (and value) vector is spread over LPT consecutive lanes, 16 bytes each, so a wave reads
-// 64/LPT whole rows per instruction; all K and V loads of the slice are issued before any use.
+// query heads of the group, and the workgroup that finishes last for a (row, kv head) merges the
+// slices (arrival counter, device-scope accesses), so no second launch is needed.  Inside a task a
+// token's key (and value) vector is spread over LPT consecutive lanes, 16 bytes each, so a wave
+// reads 64/LPT whole rows per instruction; all K and V loads of the slice are issued before any
+// use.
 #pragma once
 #include "device_common.h"
 
 namespace spark {
 
 constexpr int ATTN_THREADS = 256;
-constexpr int ATTN_SLICE = 64;      // tokens per block
+constexpr int ATTN_SLICE = 64;      // tokens per task
 constexpr int ATTN_MAX_GROUP = 16;  // query heads per KV head
 static_assert(ATTN_SLICE == 64, "the softmax step maps one token to one lane of a wave");
 
+// floats of LDS one task needs with NT threads
+template <int HD, int G, int NT> constexpr int attn_lds_floats() {
+  return G * ATTN_SLICE + G * 2 + (NT / 64) * G * HD + 4;
+}
+
 // partial layout: part[((r*nq + hq)*n_splits + split)*(HD+4)] = {o[HD], m, l, pad, pad}
-template <typename KT, int HD, int G>
-__global__ void __launch_bounds__(ATTN_THREADS)
-attn_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbuf, KVView kv,
-            int layer, int nq, int n_splits, float scale, float *__restrict__ part,
-            int *__restrict__ arrivals, float *__restrict__ out) {
+//
+// One task, executed by all NT threads of a workgroup.  DS: the queries were written, and the
+// output will be read, by other workgroups of the same kernel (device-scope accesses).
+template <typename KT, int HD, int G, int NT, bool DS>
+__device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int split,
+                                          const float *__restrict__ qbuf, const KVView &kv,
+                                          int layer, int nq, int n_splits, float scale,
+                                          float *__restrict__ part, int *__restrict__ arrivals,
+                                          float *__restrict__ out, float *lds) {
   constexpr int VEC = Elem<KT>::VEC;
   constexpr int LPT = HD / VEC;                   // lanes per token
-  constexpr int TPI = ATTN_THREADS / LPT;         // tokens per iteration of the block
-  constexpr int ITERS = ATTN_SLICE / TPI;
-  constexpr int WAVES = ATTN_THREADS / 64;
-  __shared__ float sc[G][ATTN_SLICE];             // scores, then probabilities
-  __shared__ float ml[G][2];
-  __shared__ float ored[WAVES][G][HD];
-  __shared__ int s_last;
+  constexpr int TPI = NT / LPT;                   // tokens per iteration of the workgroup
+  constexpr int ITERS = (ATTN_SLICE + TPI - 1) / TPI;
+  constexpr int WAVES = NT / 64;
+  constexpr int PS = HD + 4;
+  float *sc = lds;                                // [G][ATTN_SLICE] scores, then probabilities
+  float *ml = sc + G * ATTN_SLICE;                // [G][2]
+  float *ored = ml + G * 2;                       // [WAVES][G][HD]
+  int *s_last = (int *)(ored + WAVES * G * HD);
 
-  const int split = blockIdx.x, hk = blockIdx.y, r = blockIdx.z;
-  const RowDesc rd = rows[r];
   const int ctx = rd.pos + 1;
   const int t0 = split * ATTN_SLICE;
-  if (t0 >= ctx) return;                          // the merge only reads slices below the context
   const int n_tok = min(ATTN_SLICE, ctx - t0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int tg = tid / LPT, dc = tid % LPT;       // token slot in an iteration, 16-byte chunk of the row
@@ -67,9 +75,9 @@ attn_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbuf, KV
   for (int g = 0; g < G; ++g) {
     const float *qp = qbuf + (size_t)r * nq * HD + (hq0 + g) * HD + dc * VEC;
 #pragma unroll
-    for (int e = 0; e < VEC; e += 4) {
-      float4 v = *(const float4 *)(qp + e);
-      q[g][e] = v.x * scale; q[g][e + 1] = v.y * scale; q[g][e + 2] = v.z * scale; q[g][e + 3] = v.w * scale;
+    for (int e = 0; e < VEC; e += 2) {
+      float2 v = load2_maybe_ds<DS>(qp + e);
+      q[g][e] = v.x * scale; q[g][e + 1] = v.y * scale;
     }
   }
 
@@ -86,19 +94,19 @@ attn_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbuf, KV
       for (int e = 0; e < VEC; ++e) s += q[g][e] * kf[e];
 #pragma unroll
       for (int o = LPT / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-      if (dc == 0) sc[g][t] = t < n_tok ? s : -INFINITY;
+      if (dc == 0 && t < ATTN_SLICE) sc[g * ATTN_SLICE + t] = t < n_tok ? s : -INFINITY;
     }
   }
   __syncthreads();
 
   // softmax statistics of the slice, one wave per query head at a time (lane = token)
   for (int g = wave; g < G; g += WAVES) {
-    float s = sc[g][lane];
+    float s = sc[g * ATTN_SLICE + lane];
     float mx = wave_max(s);
     float p = lane < n_tok ? expf(s - mx) : 0.f;
-    sc[g][lane] = p;
+    sc[g * ATTN_SLICE + lane] = p;
     float sum = wave_sum(p);
-    if (lane == 0) { ml[g][0] = mx; ml[g][1] = sum; }
+    if (lane == 0) { ml[g * 2] = mx; ml[g * 2 + 1] = sum; }
   }
   __syncthreads();
 
@@ -111,13 +119,15 @@ attn_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbuf, KV
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) {
     const int t = it * TPI + tg;
-    float vf[VEC];
-    Elem<KT>::unpack(vraw[it], vf);
+    if (t < ATTN_SLICE) {
+      float vf[VEC];
+      Elem<KT>::unpack(vraw[it], vf);
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      const float p = sc[g][t];
+      for (int g = 0; g < G; ++g) {
+        const float p = sc[g * ATTN_SLICE + t];
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) acc[g][e] += p * vf[e];
+        for (int e = 0; e < VEC; ++e) acc[g][e] += p * vf[e];
+      }
     }
   }
 #pragma unroll
@@ -127,43 +137,43 @@ attn_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbuf, KV
       float a = acc[g][e];
 #pragma unroll
       for (int o = LPT; o < 64; o <<= 1) a += __shfl_xor(a, o, 64);
-      if (lane < LPT) ored[wave][g][dc * VEC + e] = a;
+      if (lane < LPT) ored[(wave * G + g) * HD + dc * VEC + e] = a;
     }
   __syncthreads();
-  constexpr int PS = HD + 4;   // floats per partial: o[HD], m, l, 2 pad (keeps rows 16-byte aligned)
-  for (int i = tid; i < G * HD; i += ATTN_THREADS) {
+  for (int i = tid; i < G * HD; i += NT) {
     const int g = i / HD, c = i - g * HD;
     float o = 0.f;
 #pragma unroll
-    for (int w = 0; w < WAVES; ++w) o += ored[w][g][c];
+    for (int w = 0; w < WAVES; ++w) o += ored[(w * G + g) * HD + c];
     store_device_scope(part + ((size_t)(r * nq + hq0 + g) * n_splits + split) * PS + c, o);
   }
   if (tid < G * 2) {
     const int g = tid >> 1, w = tid & 1;
-    store_device_scope(part + ((size_t)(r * nq + hq0 + g) * n_splits + split) * PS + HD + w, ml[g][w]);
+    store_device_scope(part + ((size_t)(r * nq + hq0 + g) * n_splits + split) * PS + HD + w,
+                       ml[g * 2 + w]);
   }
 
-  // The block that arrives last for this (row, kv head) merges the slices:
+  // The workgroup that arrives last for this (row, kv head) merges the slices:
   // out = sum_s exp(m_s - M) o_s / sum_s exp(m_s - M) l_s.
   // Partials are written through to memory (device-scope stores) and counted with a device-scope
-  // atomic; the merging block drops its stale cache lines once and then reads them normally.
+  // atomic; the merging workgroup drops its stale cache lines once and then reads them normally.
   const int used = (rd.pos + ATTN_SLICE) / ATTN_SLICE;   // slices that intersect the context
   wait_memory_ops();                                      // partials written before the count
   __syncthreads();
   if (tid == 0) {
     int *cnt = arrivals + r * (nq / G) + hk;
     const int prev = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    s_last = prev == used - 1;
-    if (s_last) {
+    *s_last = prev == used - 1;
+    if (*s_last) {
       __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next layer
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // one cache invalidate for the block
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // one cache invalidate for the workgroup
     }
   }
   __syncthreads();
-  if (!s_last) return;
+  if (!*s_last) return;
 
   // normalised slice weights wn[g][s] = exp(m_s - M) / sum_s' exp(m_s' - M) l_s', lane = slice
-  float *wn = &ored[0][0][0];                             // [G][used], used <= 256 <= WAVES*HD
+  float *wn = ored;                                       // [G][used], used <= 256 <= WAVES*HD
   for (int g = wave; g < G; g += WAVES) {
     const float *p = part + (size_t)(r * nq + hq0 + g) * n_splits * PS;
     float M = -INFINITY;
@@ -187,7 +197,7 @@ attn_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbuf, KV
       if (s0 + lane < used) wn[g * used + s0 + lane] *= inv;
   }
   __syncthreads();
-  for (int i = tid; i < G * (HD / 4); i += ATTN_THREADS) {
+  for (int i = tid; i < G * (HD / 4); i += NT) {
     const int g = i / (HD / 4), c = (i - g * (HD / 4)) * 4;
     const float *p = part + (size_t)(r * nq + hq0 + g) * n_splits * PS + c;
     float4 acc4 = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -197,8 +207,24 @@ attn_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbuf, KV
       const float w = wn[g * used + sl];
       acc4.x += w * o.x; acc4.y += w * o.y; acc4.z += w * o.z; acc4.w += w * o.w;
     }
-    *(float4 *)(out + (size_t)r * nq * HD + (hq0 + g) * HD + c) = acc4;
+    float *dst = out + (size_t)r * nq * HD + (hq0 + g) * HD + c;
+    store2_maybe_ds<DS>(dst, make_float2(acc4.x, acc4.y));
+    store2_maybe_ds<DS>(dst + 2, make_float2(acc4.z, acc4.w));
   }
+}
+
+// stand-alone launch: one workgroup per (slice, kv head, row)
+template <typename KT, int HD, int G>
+__global__ void __launch_bounds__(ATTN_THREADS)
+attn_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbuf, KVView kv,
+            int layer, int nq, int n_splits, float scale, float *__restrict__ part,
+            int *__restrict__ arrivals, float *__restrict__ out) {
+  __shared__ float lds[attn_lds_floats<HD, G, ATTN_THREADS>()];
+  const int split = blockIdx.x, hk = blockIdx.y, r = blockIdx.z;
+  const RowDesc rd = rows[r];
+  if (split * ATTN_SLICE > rd.pos) return;        // slice beyond the row's context
+  attn_task<KT, HD, G, ATTN_THREADS, false>(rd, r, hk, split, qbuf, kv, layer, nq, n_splits, scale,
+                                            part, arrivals, out, lds);
 }
 
 }  // namespace spark

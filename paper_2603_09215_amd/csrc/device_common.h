@@ -75,6 +75,30 @@ __device__ __forceinline__ void store_device_scope(float *p, float v) {
 __device__ __forceinline__ float load_device_scope(const float *p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ float2 load_device_scope2(const float *p) {   // p 8-byte aligned
+  unsigned long long v = __hip_atomic_load((const unsigned long long *)p, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+  return make_float2(__uint_as_float((uint32_t)v), __uint_as_float((uint32_t)(v >> 32)));
+}
+__device__ __forceinline__ void store_device_scope2(float *p, float2 v) {
+  unsigned long long u = (unsigned long long)__float_as_uint(v.x) |
+                         ((unsigned long long)__float_as_uint(v.y) << 32);
+  __hip_atomic_store((unsigned long long *)p, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_device_scope(bf16_t *p, bf16_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// DS selects device-scope (cross-workgroup, same kernel) or ordinary accesses at compile time
+template <bool DS, typename T> __device__ __forceinline__ void store_maybe_ds(T *p, T v) {
+  if (DS) store_device_scope(p, v); else *p = v;
+}
+template <bool DS> __device__ __forceinline__ float2 load2_maybe_ds(const float *p) {
+  if (DS) return load_device_scope2(p);
+  return *(const float2 *)p;
+}
+template <bool DS> __device__ __forceinline__ void store2_maybe_ds(float *p, float2 v) {
+  if (DS) store_device_scope2(p, v); else *(float2 *)p = v;
+}
 // wait until every memory operation this wave has issued is complete
 __device__ __forceinline__ void wait_memory_ops() { __builtin_amdgcn_s_waitcnt(0); }
 

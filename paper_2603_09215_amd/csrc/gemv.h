@@ -102,7 +102,7 @@ struct NoState {};
 // q, k, v projection + rotary embedding + KV-cache write.  Task t -> head t / (hd/2), pair index
 // i = t % (hd/2): weight rows (head*hd + i) and (head*hd + i + hd/2), the two elements that the
 // rotary embedding mixes.  Heads [0,nq) are queries, [nq,nq+nkv) keys, the rest values.
-template <typename WT> struct EpiQKV {
+template <typename WT, bool DS = false> struct EpiQKV {
   typedef NoState State;
   const WT *wq, *wk, *wv;  // this layer
   int d, nq, nkv, hd, layer;
@@ -129,20 +129,21 @@ template <typename WT> struct EpiQKV {
     }
     if (head < nq) {
       float *q = qbuf + (size_t)r * nq * hd + head * hd + i;
-      q[0] = y0; q[half] = y1;
+      store_maybe_ds<DS>(q, y0);
+      store_maybe_ds<DS>(q + half, y1);
     } else {
       int which = head < nq + nkv ? 0 : 1;
       int h = head - nq - which * nkv;
       WT *dst = (WT *)kv.pool + kv_elem_offset(kv, rd.seq, rd.pos, layer, which, h) + i;
-      dst[0] = Elem<WT>::narrow(y0);
-      dst[half] = Elem<WT>::narrow(y1);
+      store_maybe_ds<DS>(dst, Elem<WT>::narrow(y0));
+      store_maybe_ds<DS>(dst + half, Elem<WT>::narrow(y1));
     }
   }
   __device__ void end(int, const RowDesc &, State &) const {}
 };
 
 // hidden[x_slot][i] += y  (attention output projection, MLP down projection)
-template <typename WT> struct EpiResidual {
+template <typename WT, bool DS = false> struct EpiResidual {
   typedef NoState State;
   const WT *w;
   int n_in, n_out;
@@ -154,16 +155,16 @@ template <typename WT> struct EpiResidual {
     r1 = r0 + n_in;
   }
   __device__ void finish(int task, int r, const RowDesc &rd, float y0, float y1, State &) const {
-    float2 *h = (float2 *)(hidden + (size_t)rd.x_slot * d + 2 * task);
-    float2 v = *h;
+    float *h = hidden + (size_t)rd.x_slot * d + 2 * task;
+    float2 v = load2_maybe_ds<DS>(h);
     v.x += y0; v.y += y1;
-    *h = v;
+    store2_maybe_ds<DS>(h, v);
   }
   __device__ void end(int, const RowDesc &, State &) const {}
 };
 
 // act[r][i] = silu(Wg_i . n) * (Wu_i . n)
-template <typename WT> struct EpiSwiGLU {
+template <typename WT, bool DS = false> struct EpiSwiGLU {
   typedef NoState State;
   const WT *wg, *wu;
   int d, F;
@@ -175,7 +176,7 @@ template <typename WT> struct EpiSwiGLU {
   }
   __device__ void finish(int task, int r, const RowDesc &, float y0, float y1, State &) const {
     float s = y0 / (1.0f + expf(-y0));
-    act[(size_t)r * F + task] = s * y1;
+    store_maybe_ds<DS>(act + (size_t)r * F + task, s * y1);
   }
   __device__ void end(int, const RowDesc &, State &) const {}
 };
@@ -244,20 +245,20 @@ __device__ __forceinline__ uint4 load_weights16(const void *p) {
 
 constexpr int GEMV_U = 2;  // 16-byte loads in flight per weight row and pipeline stage
 
-// One pipeline stage of weights: GEMV_U consecutive 1 KiB segments of both rows of a task.
-struct WStage {
-  uint4 a[GEMV_U], b[GEMV_U];
+// One pipeline stage of weights: U consecutive 1 KiB segments of both rows of a task.
+template <int U> struct WStage {
+  uint4 a[U], b[U];
 };
 
 // Issue the loads of elements [kb, kb + U*WSTEP) of a chunk of length klen (lanes beyond klen and
 // waves without a task get zeros).
-template <typename WT>
-__device__ __forceinline__ void issue_stage(WStage &s, const WT *p0, const WT *p1, int kb, int klen,
+template <typename WT, int U>
+__device__ __forceinline__ void issue_stage(WStage<U> &s, const WT *p0, const WT *p1, int kb, int klen,
                                             int lane, bool valid) {
   constexpr int VEC = Elem<WT>::VEC;
   constexpr int WSTEP = 64 * VEC;
 #pragma unroll
-  for (int u = 0; u < GEMV_U; ++u) {
+  for (int u = 0; u < U; ++u) {
     const int k = kb + u * WSTEP + lane * VEC;
     if (valid && k < klen) {
       s.a[u] = load_weights16(p0 + k);
@@ -324,7 +325,7 @@ gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int 
   epi.init(st);
 
   // prime the pipeline: first stage of this wave's first task
-  WStage nxt;
+  WStage<GEMV_U> nxt;
   const WT *r0, *r1;
   bool valid = wave_global < n_tasks;
   epi.weight_rows(valid ? wave_global : 0, r0, r1);
@@ -349,7 +350,7 @@ gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int 
       }
       const int n_groups = (klen + GSTEP - 1) / GSTEP;
       for (int g = 0; g < n_groups; ++g) {
-        const WStage cur = nxt;
+        const WStage<GEMV_U> cur = nxt;
         if (g + 1 < n_groups) {
           issue_stage<WT>(nxt, r0 + k0, r1 + k0, (g + 1) * GSTEP, klen, lane, valid);
         } else if (chunk + 1 < n_chunks) {

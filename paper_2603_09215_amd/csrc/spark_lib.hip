@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <type_traits>
 #include <vector>
@@ -14,6 +15,7 @@
 #include "attention.h"
 #include "device_common.h"
 #include "gemv.h"
+#include "pass_kernel.h"
 #include "sched.h"
 
 using namespace spark;
@@ -26,7 +28,7 @@ constexpr int MAX_SEQ_LEN = 16384;
 
 struct Layout {  // byte offsets into the scratch buffer
   size_t state, page_table, plan, lower, upper, ee, full, prefill_rows, prefill_tokens, seq_ids,
-      forced, step_flags, out_tokens, out_depth, best, arrivals, hidden, qbuf, attn_out, part, act, lens_u,
+      forced, step_flags, out_tokens, out_depth, best, arrivals, barrier, hidden, qbuf, attn_out, part, act, lens_u,
       logits, rope, inv_freq, total;
 };
 
@@ -60,6 +62,10 @@ struct spark_ctx {
   int *h_in;   // pinned: seq_ids[max_batch] + forced[MAX_STEPS][max_batch]
   int *h_out;  // pinned: tokens[MAX_STEPS][max_batch] + depth[...] + plan[PL_WORDS]
   char err[512];
+  // persistent layer-pass kernel
+  bool use_pass_kernel = true;
+  unsigned bar_round = 0;      // grid barriers passed since the barrier words were zeroed
+  unsigned long long *timeline_dev = nullptr;  // debugging aid, see SPARK_PASS_TIMELINE
   // profiling of one kernel class
   int prof_class = -1;
   std::vector<hipEvent_t> prof_ev;
@@ -155,6 +161,7 @@ void layout(const spark_config &c, const Derived &d, Layout &l) {
   l.out_depth = take(sizeof(int) * (size_t)MAX_STEPS_PER_CALL * c.max_batch);
   l.best = take(sizeof(unsigned long long) * c.max_batch);
   l.arrivals = take(sizeof(int) * (size_t)d.max_rows * c.n_kv_heads);
+  l.barrier = take(sizeof(unsigned) * (8 * 32 + 32));
   l.hidden = take(sizeof(float) * ((size_t)c.max_batch * d.rmax + PREFILL_CHUNK) * c.d_model);
   l.qbuf = take(sizeof(float) * d.max_rows * qw);
   l.attn_out = take(sizeof(float) * d.max_rows * qw);
@@ -270,9 +277,117 @@ template <typename WT> int launch_attention(spark_ctx *c, const RowDesc *rows, i
   return prof_end(c, SPARK_KC_ATTN);
 }
 
-// layers [l0, l1) on m rows described by `rows` (device)
-template <typename WT> int run_layers(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
+// ------------------------------------------------------------------ persistent layer pass
+
+constexpr size_t PASS_LDS_BUDGET = 128 * 1024;
+
+template <typename WT, int MT, int HD, int G>
+int launch_pass_inst(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
   const spark_config &g = c->cfg;
+  const Derived &dv = c->dv;
+  auto kern = spark_pass_k<WT, MT, HD, G>;
+  // LDS: the larger of the attention workspace and MT activation rows of one chunk
+  const size_t attn_bytes = sizeof(float) * attn_lds_floats<HD, G, PASS_THREADS>();
+  const int qw = g.n_q_heads * HD;
+  auto chunk = [&](int n_in) {
+    int cap = (int)(PASS_LDS_BUDGET / (sizeof(float) * MT)) / 512 * 512;
+    return std::min((int)align_up(n_in, 512), cap);
+  };
+  PassParams<WT> p;
+  p.kc_d = chunk(g.d_model); p.kc_q = chunk(qw); p.kc_f = chunk(g.d_ffn);
+  if (p.kc_d < g.d_model) return fail(c, SPARK_EINVAL, "row of %d does not fit in LDS", g.d_model);
+  size_t lds = sizeof(float) * MT * (size_t)std::max(p.kc_d, std::max(p.kc_q, p.kc_f));
+  lds = std::max(lds, attn_bytes);
+  static bool configured = false;   // per instantiation
+  if (!configured) {
+    HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)PASS_LDS_BUDGET));
+    int occ = 0;
+    HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, PASS_THREADS, lds));
+    if (occ < 1) return fail(c, SPARK_EHIP, "the layer-pass kernel does not fit on a CU");
+    configured = true;
+  }
+  p.d = g.d_model; p.nq = g.n_q_heads; p.nkv = g.n_kv_heads; p.hd = HD; p.F = g.d_ffn;
+  p.eps = g.rms_eps;
+  p.wq = (const WT *)c->w.wq; p.wk = (const WT *)c->w.wk; p.wv = (const WT *)c->w.wv;
+  p.wo = (const WT *)c->w.wo; p.wg = (const WT *)c->w.wg; p.wu = (const WT *)c->w.wu;
+  p.wd = (const WT *)c->w.wd;
+  p.attn_norm = c->w.attn_norm; p.mlp_norm = c->w.mlp_norm;
+  p.l0 = l0; p.l1 = l1; p.rows = rows; p.m_rows = m;
+  p.hidden = at<float>(c, c->lo.hidden); p.qbuf = at<float>(c, c->lo.qbuf);
+  p.attn_out = at<float>(c, c->lo.attn_out); p.act = at<float>(c, c->lo.act);
+  p.part = at<float>(c, c->lo.part); p.arrivals = at<int>(c, c->lo.arrivals);
+  p.rope = at<float2>(c, c->lo.rope); p.kv = kv_view(c);
+  p.n_splits = dv.n_splits; p.scale = 1.0f / sqrtf((float)HD);
+  unsigned *bw = at<unsigned>(c, c->lo.barrier);
+  p.gb = GridBarrier{bw, bw + 8 * 32, (unsigned *)(at<int>(c, c->lo.plan) + PL_BARRIER_ERR)};
+  p.round_base = c->bar_round;
+  if (getenv("SPARK_PROBE_NOSYNC")) p.gb.error_word = nullptr;
+  p.timeline = c->timeline_dev;
+  int rc = prof_begin(c, SPARK_KC_PASS);
+  if (rc) return rc;
+  kern<<<c->n_cu, PASS_THREADS, lds, c->stream>>>(p);
+  HIP_TRY(c, hipGetLastError());
+  c->bar_round += 5u * (unsigned)(l1 - l0) - 1u;
+  if (c->timeline_dev) {  // debugging aid: print the phase times of this launch
+    std::vector<unsigned long long> t(10 * (l1 - l0));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipMemcpy(t.data(), c->timeline_dev, t.size() * 8, hipMemcpyDeviceToHost));
+    double work[5] = {0}, wait[5] = {0};
+    for (int l = 0; l < l1 - l0; ++l)
+      for (int ph = 0; ph < 5; ++ph) {
+        work[ph] += (double)(t[l * 10 + ph * 2 + 1] - t[l * 10 + ph * 2]) * 0.01;
+        if (ph < 4 || l + 1 < l1 - l0)
+          wait[ph] += (double)(t[l * 10 + ph * 2 + 2] - t[l * 10 + ph * 2 + 1]) * 0.01;
+      }
+    const int nl = l1 - l0;
+    fprintf(stderr, "[pass m=%d layers %d..%d] us/layer  qkv %.1f+%.1f  attn %.1f+%.1f  o %.1f+%.1f  "
+            "gateup %.1f+%.1f  down %.1f+%.1f  total %.1f\n", m, l0, l1,
+            work[0] / nl, wait[0] / nl, work[1] / nl, wait[1] / nl, work[2] / nl, wait[2] / nl,
+            work[3] / nl, wait[3] / nl, work[4] / nl, wait[4] / nl,
+            (double)(t[nl * 10 - 1] - t[0]) * 0.01 / nl);
+  }
+  return prof_end(c, SPARK_KC_PASS);
+}
+
+template <typename WT, int HD, int G>
+int launch_pass_mt(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
+  switch (m) {
+    case 1: return launch_pass_inst<WT, 1, HD, G>(c, l0, l1, rows, m);
+    case 2: return launch_pass_inst<WT, 2, HD, G>(c, l0, l1, rows, m);
+    case 3: return launch_pass_inst<WT, 3, HD, G>(c, l0, l1, rows, m);
+    default: return launch_pass_inst<WT, 4, HD, G>(c, l0, l1, rows, m);
+  }
+}
+
+// Shapes the persistent kernel is built for; others take the kernel-per-operation path.
+template <typename WT> bool pass_supported(int hd, int group);
+template <> bool pass_supported<bf16_t>(int hd, int group) {
+  return (hd == 128 && (group == 7 || group == 16)) || (hd == 64 && (group == 2 || group == 16));
+}
+template <> bool pass_supported<float>(int hd, int group) { return group == 2; }
+
+template <typename WT> int launch_pass(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m);
+template <> int launch_pass<bf16_t>(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
+  const int hd = c->cfg.head_dim, grp = c->dv.group;
+  if (hd == 128 && grp == 7) return launch_pass_mt<bf16_t, 128, 7>(c, l0, l1, rows, m);
+  if (hd == 128 && grp == 16) return launch_pass_mt<bf16_t, 128, 16>(c, l0, l1, rows, m);
+  if (hd == 64 && grp == 2) return launch_pass_mt<bf16_t, 64, 2>(c, l0, l1, rows, m);
+  return launch_pass_mt<bf16_t, 64, 16>(c, l0, l1, rows, m);
+}
+template <> int launch_pass<float>(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
+  if (c->cfg.head_dim == 128) return launch_pass_mt<float, 128, 2>(c, l0, l1, rows, m);
+  return launch_pass_mt<float, 64, 2>(c, l0, l1, rows, m);
+}
+
+// layers [l0, l1) on m rows described by `rows` (device)
+template <typename WT>
+int run_layers(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m, bool one_sequence = false) {
+  const spark_config &g = c->cfg;
+  if (l0 >= l1 || m <= 0) return SPARK_OK;
+  // up to four consecutive positions of one sequence: the whole run of layers is one launch
+  if (one_sequence && m <= 4 && c->use_pass_kernel && pass_supported<WT>(g.head_dim, c->dv.group))
+    return launch_pass<WT>(c, l0, l1, rows, m);
   const int d = g.d_model, hd = g.head_dim, nq = g.n_q_heads, nkv = g.n_kv_heads, F = g.d_ffn;
   const size_t qw = (size_t)nq * hd, kvw = (size_t)nkv * hd;
   float *hidden = at<float>(c, c->lo.hidden);
@@ -378,10 +493,10 @@ int enqueue_step(spark_ctx *c, int n, int n_upper, int n_ee, int n_full, const i
   embed_rows_k<WT><<<n, 256, 0, c->stream>>>(lower, state, nullptr, (const WT *)c->w.embed,
                                              g.d_model, at<float>(c, c->lo.hidden));
   HIP_TRY(c, hipGetLastError());
-  if ((rc = run_layers<WT>(c, 0, g.exit_layer, lower, n))) return rc;
+  if ((rc = run_layers<WT>(c, 0, g.exit_layer, lower, n, n == 1))) return rc;
   if (n_ee && (rc = run_lens_head<WT>(c, ee, n_ee))) return rc;
   if (n_full) {
-    if ((rc = run_layers<WT>(c, g.exit_layer, g.n_layers, upper, n_upper))) return rc;
+    if ((rc = run_layers<WT>(c, g.exit_layer, g.n_layers, upper, n_upper, n == 1))) return rc;
     if ((rc = run_final_head<WT>(c, full, n_full))) return rc;
   }
   emit_k<<<1, SCHED_THREADS, 0, c->stream>>>(n, seq_ids, forced_dev, flags, best, state, plan,
@@ -486,10 +601,16 @@ int decode_chunk(spark_ctx *c, int steps, int n, const int32_t *seq_ids, const i
     Seq &s = c->seqs[seq_ids[i]];
     s.g = mir[i].g; s.j_stream = mir[i].j; s.n_pending = mir[i].npend; s.len = mir[i].len;
   }
+  if (h_plan[PL_BARRIER_ERR]) h_plan[PL_ERR] |= ERR_BARRIER;
   if (h_plan[PL_ERR]) {
     int e = h_plan[PL_ERR];
     int zero = 0;  // error path only: clear the flag so that the context stays usable
     (void)hipMemcpy(at<int>(c, c->lo.plan) + PL_ERR, &zero, sizeof(int), hipMemcpyHostToDevice);
+    (void)hipMemcpy(at<int>(c, c->lo.plan) + PL_BARRIER_ERR, &zero, sizeof(int), hipMemcpyHostToDevice);
+    if (e & ERR_BARRIER) {
+      c->use_pass_kernel = false;
+      return fail(c, SPARK_EHIP, "a grid barrier of the layer-pass kernel timed out");
+    }
     if (e & ERR_NAN) return fail(c, SPARK_ENAN, "a head produced a NaN logit");
     return fail(c, SPARK_ESTATE, "device saw an inactive sequence");
   }
@@ -568,6 +689,12 @@ int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_p
   if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
     return bail(SPARK_EHIP);
   c->n_cu = prop.multiProcessorCount;
+  const char *no_pass = getenv("SPARK_NO_PASS_KERNEL");
+  c->use_pass_kernel = !(no_pass && no_pass[0] == '1');
+  const char *tl = getenv("SPARK_PASS_TIMELINE");   // debugging aid: per-phase times on stderr
+  if (tl && tl[0] == '1' &&
+      hipMalloc((void **)&c->timeline_dev, sizeof(unsigned long long) * 10 * cfg->n_layers) != hipSuccess)
+    return bail(SPARK_EHIP);
   size_t in_ints = (size_t)cfg->max_batch * (1 + MAX_STEPS_PER_CALL);
   size_t out_ints = (size_t)cfg->max_batch * 2 * MAX_STEPS_PER_CALL + PL_WORDS;
   if (hipHostMalloc((void **)&c->h_in, sizeof(int) * in_ints, hipHostMallocDefault) != hipSuccess ||
@@ -759,6 +886,7 @@ void spark_destroy(spark_ctx *c) {
   if (!c) return;
   (void)hipStreamSynchronize(c->stream);
   for (hipEvent_t ev : c->prof_ev) (void)hipEventDestroy(ev);
+  if (c->timeline_dev) (void)hipFree(c->timeline_dev);
   if (c->h_in) (void)hipHostFree(c->h_in);
   if (c->h_out) (void)hipHostFree(c->h_out);
   delete c;
