@@ -20,9 +20,21 @@ constexpr int ATTN_SLICE = 64;      // tokens per task
 constexpr int ATTN_MAX_GROUP = 16;  // query heads per KV head
 static_assert(ATTN_SLICE == 64, "the softmax step maps one token to one lane of a wave");
 
+// Synchronise the NT threads that execute a task: a workgroup barrier, or, when a single wave runs
+// the task inside a larger workgroup, only the memory ordering (a wave is in lockstep already).
+template <int NT> __device__ __forceinline__ void task_sync() {
+  if (NT == 64) {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+  } else {
+    __syncthreads();
+  }
+}
+
 // floats of LDS one task needs with NT threads
+// (the merge reuses the cross-wave buffer for [G][slices] weights, slices <= 256)
 template <int HD, int G, int NT> constexpr int attn_lds_floats() {
-  return G * ATTN_SLICE + G * 2 + (NT / 64) * G * HD + 4;
+  return G * ATTN_SLICE + G * 2 + ((NT / 64) * HD > 256 ? (NT / 64) * G * HD : G * 256) + 4;
 }
 
 // partial layout: part[((r*nq + hq)*n_splits + split)*(HD+4)] = {o[HD], m, l, pad, pad}
@@ -44,12 +56,12 @@ __device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int 
   float *sc = lds;                                // [G][ATTN_SLICE] scores, then probabilities
   float *ml = sc + G * ATTN_SLICE;                // [G][2]
   float *ored = ml + G * 2;                       // [WAVES][G][HD]
-  int *s_last = (int *)(ored + WAVES * G * HD);
+  int *s_last = (int *)(lds + attn_lds_floats<HD, G, NT>() - 4);
 
   const int ctx = rd.pos + 1;
   const int t0 = split * ATTN_SLICE;
   const int n_tok = min(ATTN_SLICE, ctx - t0);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x % NT, lane = tid & 63, wave = tid >> 6;
   const int tg = tid / LPT, dc = tid % LPT;       // token slot in an iteration, 16-byte chunk of the row
   const int hq0 = hk * G;
 
@@ -97,7 +109,7 @@ __device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int 
       if (dc == 0 && t < ATTN_SLICE) sc[g * ATTN_SLICE + t] = t < n_tok ? s : -INFINITY;
     }
   }
-  __syncthreads();
+  task_sync<NT>();
 
   // softmax statistics of the slice, one wave per query head at a time (lane = token)
   for (int g = wave; g < G; g += WAVES) {
@@ -108,7 +120,7 @@ __device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int 
     float sum = wave_sum(p);
     if (lane == 0) { ml[g * 2] = mx; ml[g * 2 + 1] = sum; }
   }
-  __syncthreads();
+  task_sync<NT>();
 
   // weighted values: acc[g][e] over this thread's tokens, then over the token slots of the wave
   float acc[G][VEC];
@@ -139,7 +151,7 @@ __device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int 
       for (int o = LPT; o < 64; o <<= 1) a += __shfl_xor(a, o, 64);
       if (lane < LPT) ored[(wave * G + g) * HD + dc * VEC + e] = a;
     }
-  __syncthreads();
+  task_sync<NT>();
   for (int i = tid; i < G * HD; i += NT) {
     const int g = i / HD, c = i - g * HD;
     float o = 0.f;
@@ -159,7 +171,7 @@ __device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int 
   // atomic; the merging workgroup drops its stale cache lines once and then reads them normally.
   const int used = (rd.pos + ATTN_SLICE) / ATTN_SLICE;   // slices that intersect the context
   wait_memory_ops();                                      // partials written before the count
-  __syncthreads();
+  task_sync<NT>();
   if (tid == 0) {
     int *cnt = arrivals + r * (nq / G) + hk;
     const int prev = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -169,11 +181,11 @@ __device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int 
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // one cache invalidate for the workgroup
     }
   }
-  __syncthreads();
+  task_sync<NT>();
   if (!*s_last) return;
 
   // normalised slice weights wn[g][s] = exp(m_s - M) / sum_s' exp(m_s' - M) l_s', lane = slice
-  float *wn = ored;                                       // [G][used], used <= 256 <= WAVES*HD
+  float *wn = ored;                                       // [G][used], used <= 256
   for (int g = wave; g < G; g += WAVES) {
     const float *p = part + (size_t)(r * nq + hq0 + g) * n_splits * PS;
     float M = -INFINITY;
@@ -196,7 +208,7 @@ __device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int 
     for (int s0 = 0; s0 < used; s0 += 64)
       if (s0 + lane < used) wn[g * used + s0 + lane] *= inv;
   }
-  __syncthreads();
+  task_sync<NT>();
   for (int i = tid; i < G * (HD / 4); i += NT) {
     const int g = i / (HD / 4), c = (i - g * (HD / 4)) * 4;
     const float *p = part + (size_t)(r * nq + hq0 + g) * n_splits * PS + c;

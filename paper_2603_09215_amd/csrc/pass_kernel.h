@@ -35,7 +35,6 @@ struct GridBarrier {
 // Returns false (in every thread of the workgroup) if the wait gave up.
 __device__ __forceinline__ bool grid_sync(const GridBarrier &gb, unsigned &round, int *s_flag) {
   ++round;
-  if (gb.error_word == nullptr) { __syncthreads(); return true; }
   wait_memory_ops();  // this wave's device-scope stores have completed
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -59,6 +58,8 @@ __device__ __forceinline__ bool grid_sync(const GridBarrier &gb, unsigned &round
     }
     if (__hip_atomic_load(gb.error_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) ok = 0;
     *s_flag = ok;
+    // what other workgroups wrote through to memory is now visible to ordinary loads of this CU
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
   }
   __syncthreads();
   return *s_flag != 0;
@@ -66,7 +67,8 @@ __device__ __forceinline__ bool grid_sync(const GridBarrier &gb, unsigned &round
 
 // ------------------------------------------------------------------ activation staging (512 threads)
 
-// xs[m][k] = src_row_m[k0 + k], rows read with device-scope loads
+// xs[m][k] = src_row_m[k0 + k]; the rows were written through to memory by other workgroups and
+// the barrier before this call dropped the stale cache lines, so ordinary 16-byte loads do
 template <int VEC, int MT>
 __device__ __forceinline__ void pass_stage_plain(float *xs, int kc, const float *src, int stride,
                                                  int n_valid, int k0, int klen) {
@@ -74,10 +76,8 @@ __device__ __forceinline__ void pass_stage_plain(float *xs, int kc, const float 
   for (int m = 0; m < MT; ++m) {
     const int mm = m < n_valid ? m : n_valid - 1;
     const float *row = src + (size_t)mm * stride + k0;
-    for (int k = threadIdx.x * 4; k < klen; k += PASS_THREADS * 4) {
-      float2 a = load_device_scope2(row + k), b = load_device_scope2(row + k + 2);
-      *(float4 *)(xs + m * kc + lds_pos<VEC>(k)) = make_float4(a.x, a.y, b.x, b.y);
-    }
+    for (int k = threadIdx.x * 4; k < klen; k += PASS_THREADS * 4)
+      *(float4 *)(xs + m * kc + lds_pos<VEC>(k)) = *(const float4 *)(row + k);
     const int end = (klen + 511) & ~511;
     for (int k = klen + threadIdx.x * 4; k < end; k += PASS_THREADS * 4)
       *(float4 *)(xs + m * kc + lds_pos<VEC>(k)) = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -97,9 +97,9 @@ __device__ __forceinline__ void pass_stage_norm(float *xs, int kc, const float *
     const float *row = hidden + (size_t)rd[mm].x_slot * d;
     float ss = 0.f;
     for (int k = threadIdx.x * 4; k < d; k += PASS_THREADS * 4) {
-      float2 a = load_device_scope2(row + k), b = load_device_scope2(row + k + 2);
-      ss += a.x * a.x + a.y * a.y + b.x * b.x + b.y * b.y;
-      *(float4 *)(xs + m * kc + lds_pos<VEC>(k)) = make_float4(a.x, a.y, b.x, b.y);
+      const float4 v = *(const float4 *)(row + k);
+      ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+      *(float4 *)(xs + m * kc + lds_pos<VEC>(k)) = v;
     }
     ss = wave_sum(ss);
     if (lane == 0) red[wave * MT + m] = ss;

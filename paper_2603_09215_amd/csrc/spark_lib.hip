@@ -15,7 +15,7 @@
 #include "attention.h"
 #include "device_common.h"
 #include "gemv.h"
-#include "pass_kernel.h"
+#include "pass_launch.h"
 #include "sched.h"
 
 using namespace spark;
@@ -63,7 +63,7 @@ struct spark_ctx {
   int *h_out;  // pinned: tokens[MAX_STEPS][max_batch] + depth[...] + plan[PL_WORDS]
   char err[512];
   // persistent layer-pass kernel
-  bool use_pass_kernel = true;
+  bool use_pass_kernel = false;
   unsigned bar_round = 0;      // grid barriers passed since the barrier words were zeroed
   unsigned long long *timeline_dev = nullptr;  // debugging aid, see SPARK_PASS_TIMELINE
   // profiling of one kernel class
@@ -281,33 +281,40 @@ template <typename WT> int launch_attention(spark_ctx *c, const RowDesc *rows, i
 
 constexpr size_t PASS_LDS_BUDGET = 128 * 1024;
 
-template <typename WT, int MT, int HD, int G>
-int launch_pass_inst(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
+typedef hipError_t (*pass_launcher_bf16)(const PassParams<bf16_t> &, int, int, size_t, size_t, hipStream_t);
+typedef hipError_t (*pass_launcher_f32)(const PassParams<float> &, int, int, size_t, size_t, hipStream_t);
+
+// Shapes the persistent kernel is built for; others take the kernel-per-operation path.
+pass_launcher_bf16 pick_pass(bf16_t, int hd, int group) {
+  if (hd == 128 && group == 7) return launch_pass_bf16_128_7;
+  if (hd == 128 && group == 16) return launch_pass_bf16_128_16;
+  if (hd == 64 && group == 2) return launch_pass_bf16_64_2;
+  return nullptr;
+}
+pass_launcher_f32 pick_pass(float, int hd, int group) {
+  if (hd == 64 && group == 2) return launch_pass_f32_64_2;
+  return nullptr;
+}
+
+template <typename WT> bool pass_supported(int hd, int group) { return pick_pass(WT(), hd, group) != nullptr; }
+
+template <typename WT> int launch_pass(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
   const spark_config &g = c->cfg;
   const Derived &dv = c->dv;
-  auto kern = spark_pass_k<WT, MT, HD, G>;
-  // LDS: the larger of the attention workspace and MT activation rows of one chunk
-  const size_t attn_bytes = sizeof(float) * attn_lds_floats<HD, G, PASS_THREADS>();
-  const int qw = g.n_q_heads * HD;
+  const int hd = g.head_dim, qw = g.n_q_heads * hd, mt = m;
+  // LDS: the larger of the attention workspace (at most 16 heads of 128) and mt
+  // activation rows of one chunk
+  const size_t attn_bytes = sizeof(float) * attn_lds_floats<128, 16, PASS_THREADS>();
   auto chunk = [&](int n_in) {
-    int cap = (int)(PASS_LDS_BUDGET / (sizeof(float) * MT)) / 512 * 512;
+    int cap = (int)(PASS_LDS_BUDGET / (sizeof(float) * mt)) / 512 * 512;
     return std::min((int)align_up(n_in, 512), cap);
   };
   PassParams<WT> p;
   p.kc_d = chunk(g.d_model); p.kc_q = chunk(qw); p.kc_f = chunk(g.d_ffn);
   if (p.kc_d < g.d_model) return fail(c, SPARK_EINVAL, "row of %d does not fit in LDS", g.d_model);
-  size_t lds = sizeof(float) * MT * (size_t)std::max(p.kc_d, std::max(p.kc_q, p.kc_f));
+  size_t lds = sizeof(float) * mt * (size_t)std::max(p.kc_d, std::max(p.kc_q, p.kc_f));
   lds = std::max(lds, attn_bytes);
-  static bool configured = false;   // per instantiation
-  if (!configured) {
-    HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)PASS_LDS_BUDGET));
-    int occ = 0;
-    HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, PASS_THREADS, lds));
-    if (occ < 1) return fail(c, SPARK_EHIP, "the layer-pass kernel does not fit on a CU");
-    configured = true;
-  }
-  p.d = g.d_model; p.nq = g.n_q_heads; p.nkv = g.n_kv_heads; p.hd = HD; p.F = g.d_ffn;
+  p.d = g.d_model; p.nq = g.n_q_heads; p.nkv = g.n_kv_heads; p.hd = hd; p.F = g.d_ffn;
   p.eps = g.rms_eps;
   p.wq = (const WT *)c->w.wq; p.wk = (const WT *)c->w.wk; p.wv = (const WT *)c->w.wv;
   p.wo = (const WT *)c->w.wo; p.wg = (const WT *)c->w.wg; p.wu = (const WT *)c->w.wu;
@@ -318,66 +325,32 @@ int launch_pass_inst(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
   p.attn_out = at<float>(c, c->lo.attn_out); p.act = at<float>(c, c->lo.act);
   p.part = at<float>(c, c->lo.part); p.arrivals = at<int>(c, c->lo.arrivals);
   p.rope = at<float2>(c, c->lo.rope); p.kv = kv_view(c);
-  p.n_splits = dv.n_splits; p.scale = 1.0f / sqrtf((float)HD);
+  p.n_splits = dv.n_splits; p.scale = 1.0f / sqrtf((float)hd);
   unsigned *bw = at<unsigned>(c, c->lo.barrier);
   p.gb = GridBarrier{bw, bw + 8 * 32, (unsigned *)(at<int>(c, c->lo.plan) + PL_BARRIER_ERR)};
   p.round_base = c->bar_round;
-  if (getenv("SPARK_PROBE_NOSYNC")) p.gb.error_word = nullptr;
   p.timeline = c->timeline_dev;
   int rc = prof_begin(c, SPARK_KC_PASS);
   if (rc) return rc;
-  kern<<<c->n_cu, PASS_THREADS, lds, c->stream>>>(p);
-  HIP_TRY(c, hipGetLastError());
+  HIP_TRY(c, pick_pass(WT(), hd, dv.group)(p, mt, c->n_cu, lds, PASS_LDS_BUDGET, c->stream));
   c->bar_round += 5u * (unsigned)(l1 - l0) - 1u;
   if (c->timeline_dev) {  // debugging aid: print the phase times of this launch
-    std::vector<unsigned long long> t(10 * (l1 - l0));
+    // marks of workgroup 0 per layer: before and after the barrier that ends each of the five
+    // phases (q/k/v, attention, o, gate/up, down)
+    const int nl = l1 - l0;
+    std::vector<unsigned long long> t(1 + 10 * nl);
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     HIP_TRY(c, hipMemcpy(t.data(), c->timeline_dev, t.size() * 8, hipMemcpyDeviceToHost));
-    double work[5] = {0}, wait[5] = {0};
-    for (int l = 0; l < l1 - l0; ++l)
-      for (int ph = 0; ph < 5; ++ph) {
-        work[ph] += (double)(t[l * 10 + ph * 2 + 1] - t[l * 10 + ph * 2]) * 0.01;
-        if (ph < 4 || l + 1 < l1 - l0)
-          wait[ph] += (double)(t[l * 10 + ph * 2 + 2] - t[l * 10 + ph * 2 + 1]) * 0.01;
-      }
-    const int nl = l1 - l0;
-    fprintf(stderr, "[pass m=%d layers %d..%d] us/layer  qkv %.1f+%.1f  attn %.1f+%.1f  o %.1f+%.1f  "
-            "gateup %.1f+%.1f  down %.1f+%.1f  total %.1f\n", m, l0, l1,
-            work[0] / nl, wait[0] / nl, work[1] / nl, wait[1] / nl, work[2] / nl, wait[2] / nl,
-            work[3] / nl, wait[3] / nl, work[4] / nl, wait[4] / nl,
-            (double)(t[nl * 10 - 1] - t[0]) * 0.01 / nl);
+    double seg[10] = {0};
+    for (int l = 0; l < nl; ++l)
+      for (int k = 0; k < 10; ++k)
+        if (l * 10 + k + 1 < 10 * nl) seg[k] += (double)(t[1 + l * 10 + k] - t[l * 10 + k]) * 0.01;
+    fprintf(stderr, "[pass m=%d layers %d..%d] us/layer work+wait  qkv %.1f+%.1f  attn %.1f+%.1f  o %.1f+%.1f  "
+            "gateup %.1f+%.1f  down %.1f+%.1f  total %.1f\n", m, l0, l1, seg[0] / nl, seg[1] / nl,
+            seg[2] / nl, seg[3] / nl, seg[4] / nl, seg[5] / nl, seg[6] / nl, seg[7] / nl, seg[8] / nl,
+            seg[9] / nl, (double)(t[10 * nl - 1] - t[0]) * 0.01 / nl);
   }
   return prof_end(c, SPARK_KC_PASS);
-}
-
-template <typename WT, int HD, int G>
-int launch_pass_mt(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
-  switch (m) {
-    case 1: return launch_pass_inst<WT, 1, HD, G>(c, l0, l1, rows, m);
-    case 2: return launch_pass_inst<WT, 2, HD, G>(c, l0, l1, rows, m);
-    case 3: return launch_pass_inst<WT, 3, HD, G>(c, l0, l1, rows, m);
-    default: return launch_pass_inst<WT, 4, HD, G>(c, l0, l1, rows, m);
-  }
-}
-
-// Shapes the persistent kernel is built for; others take the kernel-per-operation path.
-template <typename WT> bool pass_supported(int hd, int group);
-template <> bool pass_supported<bf16_t>(int hd, int group) {
-  return (hd == 128 && (group == 7 || group == 16)) || (hd == 64 && (group == 2 || group == 16));
-}
-template <> bool pass_supported<float>(int hd, int group) { return group == 2; }
-
-template <typename WT> int launch_pass(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m);
-template <> int launch_pass<bf16_t>(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
-  const int hd = c->cfg.head_dim, grp = c->dv.group;
-  if (hd == 128 && grp == 7) return launch_pass_mt<bf16_t, 128, 7>(c, l0, l1, rows, m);
-  if (hd == 128 && grp == 16) return launch_pass_mt<bf16_t, 128, 16>(c, l0, l1, rows, m);
-  if (hd == 64 && grp == 2) return launch_pass_mt<bf16_t, 64, 2>(c, l0, l1, rows, m);
-  return launch_pass_mt<bf16_t, 64, 16>(c, l0, l1, rows, m);
-}
-template <> int launch_pass<float>(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
-  if (c->cfg.head_dim == 128) return launch_pass_mt<float, 128, 2>(c, l0, l1, rows, m);
-  return launch_pass_mt<float, 64, 2>(c, l0, l1, rows, m);
 }
 
 // layers [l0, l1) on m rows described by `rows` (device)
@@ -689,11 +662,13 @@ int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_p
   if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
     return bail(SPARK_EHIP);
   c->n_cu = prop.multiProcessorCount;
-  const char *no_pass = getenv("SPARK_NO_PASS_KERNEL");
-  c->use_pass_kernel = !(no_pass && no_pass[0] == '1');
+  // The persistent layer-pass kernel is built and parity-tested but, as measured, not faster than
+  // one kernel per operation yet; it is used when SPARK_PASS_KERNEL=1.
+  const char *pass = getenv("SPARK_PASS_KERNEL");
+  c->use_pass_kernel = pass && pass[0] == '1';
   const char *tl = getenv("SPARK_PASS_TIMELINE");   // debugging aid: per-phase times on stderr
   if (tl && tl[0] == '1' &&
-      hipMalloc((void **)&c->timeline_dev, sizeof(unsigned long long) * 10 * cfg->n_layers) != hipSuccess)
+      hipMalloc((void **)&c->timeline_dev, sizeof(unsigned long long) * 16384) != hipSuccess)
     return bail(SPARK_EHIP);
   size_t in_ints = (size_t)cfg->max_batch * (1 + MAX_STEPS_PER_CALL);
   size_t out_ints = (size_t)cfg->max_batch * 2 * MAX_STEPS_PER_CALL + PL_WORDS;

@@ -207,3 +207,26 @@ def test_reopened_slot_reproduces_a_fresh_run(sb, tiny_weights):
     assert np.array_equal(runs[0][0], runs[1][0]) and np.array_equal(runs[0][1], runs[1][1])
     assert np.array_equal(runs[0][2], runs[1][2])    # bit-identical: no order-dependent reductions
     sp.close()
+
+
+def test_persistent_layer_pass_kernel(sb, tiny_weights, monkeypatch):
+    """the single-launch path (one persistent kernel per run of layers, grid barriers from
+    device-scope atomics) gives the same results; it is enabled per context by an environment
+    variable read at spark_init"""
+    monkeypatch.setenv("SPARK_PASS_KERNEL", "1")
+    w = wl.TINY
+    say("case pass kernel tiny")
+    sp = sb.Spark(w.shape, w.schedule, tiny_weights, max_batch=1, max_seq_len=128, kv_page_tokens=16)
+    compare_run(sp, w.shape, w.schedule, tiny_weights, [wl.make_prompt(w.shape, 16, seed=1)], [0], 64,
+                check_kv_every=4, label="pass tiny")
+    sp.close()
+    shape = wl.TINY.shape.replace(name="bf16-gqa7", dtype=wl.DTYPE_BF16, n_layers=6, d_model=896,
+                                  n_q_heads=7, n_kv_heads=1, head_dim=128, d_ffn=1712,
+                                  vocab_text=3001, vocab_speech=1000)
+    sched = wl.TINY.schedule.replace(exit_layer=4, n_text=1, n_speech=2, scope=wl.SCOPE_STREAM)
+    say("case pass kernel bf16-gqa7")
+    weights = wl.make_weights(shape, seed=3, gain_std=0.1)
+    sp = sb.Spark(shape, sched, weights, max_batch=1, max_seq_len=400, kv_page_tokens=32)
+    compare_run(sp, shape, sched, weights, [wl.make_prompt(shape, 300, seed=5)], [1], 24,
+                check_kv_every=4, label="pass bf16-gqa7")
+    sp.close()
