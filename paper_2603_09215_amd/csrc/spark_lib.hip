@@ -15,6 +15,7 @@
 #include "attention.h"
 #include "device_common.h"
 #include "gemv.h"
+#include "mfma_gemm.h"
 #include "pass_launch.h"
 #include "sched.h"
 
@@ -22,13 +23,14 @@ using namespace spark;
 
 namespace {
 
-constexpr int PREFILL_CHUNK = 64;    // prompt rows pushed through the layers together
+constexpr int PREFILL_CHUNK = 128;   // prompt rows pushed through the layers together
+constexpr size_t MFMA_PARTIAL_BYTES = 48u << 20;  // k-split partial sums of one projection
 constexpr int MAX_STEPS_PER_CALL = 256;
 constexpr int MAX_SEQ_LEN = 16384;
 
 struct Layout {  // byte offsets into the scratch buffer
   size_t state, page_table, plan, lower, upper, ee, full, prefill_rows, prefill_tokens, seq_ids,
-      forced, step_flags, out_tokens, out_depth, best, arrivals, barrier, hidden, qbuf, attn_out, part, act, lens_u,
+      forced, step_flags, out_tokens, out_depth, best, arrivals, barrier, hidden, xhi, xlo, mfma_part, qbuf, attn_out, part, act, lens_u,
       logits, rope, inv_freq, total;
 };
 
@@ -64,6 +66,7 @@ struct spark_ctx {
   char err[512];
   // persistent layer-pass kernel
   bool use_pass_kernel = false;
+  bool use_mfma = true;        // SPARK_NO_MFMA=1 keeps every row count on the vector kernels
   unsigned bar_round = 0;      // grid barriers passed since the barrier words were zeroed
   unsigned long long *timeline_dev = nullptr;  // debugging aid, see SPARK_PASS_TIMELINE
   // profiling of one kernel class
@@ -168,6 +171,12 @@ void layout(const spark_config &c, const Derived &d, Layout &l) {
   l.part = take(sizeof(float) * (size_t)d.max_rows * c.n_q_heads * d.n_splits * (c.head_dim + 4));
   l.act = take(sizeof(float) * (size_t)d.max_rows * c.d_ffn);
   l.lens_u = take(sizeof(float) * (size_t)c.max_batch * c.d_model);
+  {
+    const size_t widest = std::max((size_t)c.d_ffn, std::max((size_t)c.d_model, qw));
+    l.xhi = take(sizeof(bf16_t) * (size_t)d.max_rows * widest);
+    l.xlo = take(sizeof(bf16_t) * (size_t)d.max_rows * widest);
+    l.mfma_part = take(c.dtype == SPARK_DTYPE_BF16 ? MFMA_PARTIAL_BYTES : 256);
+  }
   l.logits = take(sizeof(float) * (size_t)c.max_batch * d.V);
   l.rope = take(sizeof(float2) * (size_t)c.max_seq_len * (c.head_dim / 2));
   l.inv_freq = take(sizeof(float) * (c.head_dim / 2));
@@ -203,13 +212,19 @@ template <typename WT, typename Pro, typename Epi>
 int launch_gemv(spark_ctx *c, const Pro &pro, const Epi &epi, const RowDesc *rows, int m_rows,
                 int n_in, int n_tasks, int kclass) {
   if (m_rows <= 0) return SPARK_OK;
-  // activation rows per pass over the weights: as many as fit in 64 KiB of LDS next to the
-  // partial-sum words; a norm prologue needs the whole row resident
-  constexpr size_t LDS_BUDGET = 65536 - sizeof(float) * GEMV_WAVES * 4;
+  // activation rows per pass over the weights: as many as fit in the LDS budget next to the
+  // partial-sum words; a norm prologue needs the whole row resident.  The budget is 64 KiB, or
+  // 80 KiB when that lets a single row (e.g. the 18944-wide MLP activation) stay in one chunk:
+  // two such workgroups still fit in a CU's 160 KiB.
   const bool whole_row = std::is_same<Pro, ProNorm>::value;
   int mt = std::min(4, m_rows);
-  while (mt > 1 && whole_row && sizeof(float) * mt * align_up(n_in, 512) > LDS_BUDGET) --mt;
-  int kc_cap = (int)(LDS_BUDGET / (sizeof(float) * mt)) / 512 * 512;
+  size_t budget = 65536;
+  if (mt == 1 && sizeof(float) * align_up(n_in, 512) + 64 > budget &&
+      sizeof(float) * align_up(n_in, 512) + 64 <= 81920)
+    budget = 81920;
+  const size_t lds_budget = budget - sizeof(float) * GEMV_WAVES * 4;
+  while (mt > 1 && whole_row && sizeof(float) * mt * align_up(n_in, 512) > lds_budget) --mt;
+  int kc_cap = (int)(lds_budget / (sizeof(float) * mt)) / 512 * 512;
   int kc = std::min((int)align_up(n_in, 512), kc_cap);
   if (whole_row && kc < n_in) return fail(c, SPARK_EINVAL, "row of %d does not fit in LDS", n_in);
   size_t lds = sizeof(float) * ((size_t)mt * kc + GEMV_WAVES * mt);
@@ -222,6 +237,8 @@ int launch_gemv(spark_ctx *c, const Pro &pro, const Epi &epi, const RowDesc *row
     case 3: kern = gemv_rows_k<WT, 3, Pro, Epi>; break;
     default: kern = gemv_rows_k<WT, 4, Pro, Epi>; break;
   }
+  if (lds > 65536)
+    HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 81920));
   int occ = 0;
   HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, GEMV_THREADS, lds));
   occ = std::max(1, std::min(occ, 4));
@@ -353,6 +370,103 @@ template <typename WT> int launch_pass(spark_ctx *c, int l0, int l1, const RowDe
   return prof_end(c, SPARK_KC_PASS);
 }
 
+// ------------------------------------------------------------------ MFMA path (16..128+ rows, bf16)
+
+constexpr int MFMA_MIN_ROWS = 16;
+
+int launch_prep(spark_ctx *c, const RowDesc *rows, int m, const float *src, int stride, int indirect,
+                const float *gamma, int n) {
+  prep_rows_k<<<m, 256, 0, c->stream>>>(rows, src, stride, indirect, gamma, c->cfg.rms_eps, n,
+                                        at<bf16_t>(c, c->lo.xhi), at<bf16_t>(c, c->lo.xlo));
+  HIP_TRY(c, hipGetLastError());
+  return SPARK_OK;
+}
+
+template <int MTILES, typename Epi>
+int launch_mfma_tiles(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, int n_in, int n_tasks,
+                      bool may_split) {
+  const int mrows = 32 * MTILES;
+  const int z = (m + mrows - 1) / mrows;
+  const int bx = (n_tasks + MG_TASKS_PER_BLOCK - 1) / MG_TASKS_PER_BLOCK;
+  const int n_chunks = (n_in + MG_KC - 1) / MG_KC;
+  const int m_pad = (int)align_up(m, 32);
+  int split = 1;
+  if (may_split) {
+    split = std::max(1, std::min(n_chunks, (2 * c->n_cu) / std::max(1, bx * z)));
+    const size_t per_split = sizeof(float) * (size_t)n_tasks * 2 * m_pad;
+    split = (int)std::min<size_t>(split, std::max<size_t>(1, MFMA_PARTIAL_BYTES / per_split));
+  }
+  const int cps = (n_chunks + split - 1) / split;
+  split = (n_chunks + cps - 1) / cps;
+  const bf16_t *xhi = at<bf16_t>(c, c->lo.xhi), *xlo = at<bf16_t>(c, c->lo.xlo);
+  float *part = at<float>(c, c->lo.mfma_part);
+  dim3 grid(bx, split, z);
+  if (split > 1) {
+    mfma_rows_k<MTILES, Epi, true><<<grid, MG_THREADS, 0, c->stream>>>(epi, rows, m, xhi, xlo, n_in,
+                                                                       n_tasks, cps, part, m_pad);
+    const int total = n_tasks * m_pad;
+    mfma_finish_k<Epi><<<(total + 255) / 256, 256, 0, c->stream>>>(epi, rows, m, n_tasks, split, part, m_pad);
+  } else {
+    mfma_rows_k<MTILES, Epi, false><<<grid, MG_THREADS, 0, c->stream>>>(epi, rows, m, xhi, xlo, n_in,
+                                                                        n_tasks, cps, part, m_pad);
+  }
+  HIP_TRY(c, hipGetLastError());
+  return SPARK_OK;
+}
+
+// y = W x for m rows whose hi/lo split sits in the xhi/xlo buffers
+template <typename Epi>
+int launch_mfma(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, int n_in, int n_tasks,
+                bool may_split, int kclass) {
+  int rc = prof_begin(c, kclass);
+  if (rc) return rc;
+  if (m <= 32) rc = launch_mfma_tiles<1>(c, epi, rows, m, n_in, n_tasks, may_split);
+  else if (m <= 64) rc = launch_mfma_tiles<2>(c, epi, rows, m, n_in, n_tasks, may_split);
+  else rc = launch_mfma_tiles<4>(c, epi, rows, m, n_in, n_tasks, may_split);
+  if (rc) return rc;
+  return prof_end(c, kclass);
+}
+
+template <typename WT> int launch_attention(spark_ctx *c, const RowDesc *rows, int m, int layer);
+
+// layers [l0, l1) on m >= 16 rows, bf16 weights
+int run_layers_mfma(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
+  typedef bf16_t WT;
+  const spark_config &g = c->cfg;
+  const int d = g.d_model, hd = g.head_dim, nq = g.n_q_heads, nkv = g.n_kv_heads, F = g.d_ffn;
+  const size_t qw = (size_t)nq * hd, kvw = (size_t)nkv * hd;
+  float *hidden = at<float>(c, c->lo.hidden);
+  int rc;
+  for (int l = l0; l < l1; ++l) {
+    if ((rc = launch_prep(c, rows, m, hidden, d, 1, c->w.attn_norm + (size_t)l * d, d))) return rc;
+    EpiQKV<WT> eq;
+    eq.wq = (const WT *)c->w.wq + (size_t)l * qw * d;
+    eq.wk = (const WT *)c->w.wk + (size_t)l * kvw * d;
+    eq.wv = (const WT *)c->w.wv + (size_t)l * kvw * d;
+    eq.d = d; eq.nq = nq; eq.nkv = nkv; eq.hd = hd; eq.layer = l;
+    eq.qbuf = at<float>(c, c->lo.qbuf);
+    eq.rope = at<float2>(c, c->lo.rope);
+    eq.kv = kv_view(c);
+    if ((rc = launch_mfma(c, eq, rows, m, d, (nq + 2 * nkv) * (hd / 2), true, SPARK_KC_QKV))) return rc;
+
+    if ((rc = launch_attention<WT>(c, rows, m, l))) return rc;
+
+    if ((rc = launch_prep(c, rows, m, at<float>(c, c->lo.attn_out), (int)qw, 0, nullptr, (int)qw))) return rc;
+    EpiResidual<WT> eo{(const WT *)c->w.wo + (size_t)l * d * qw, (int)qw, d, hidden, d};
+    if ((rc = launch_mfma(c, eo, rows, m, (int)qw, d / 2, true, SPARK_KC_OPROJ))) return rc;
+
+    if ((rc = launch_prep(c, rows, m, hidden, d, 1, c->w.mlp_norm + (size_t)l * d, d))) return rc;
+    EpiSwiGLU<WT> eg{(const WT *)c->w.wg + (size_t)l * F * d, (const WT *)c->w.wu + (size_t)l * F * d,
+                     d, F, at<float>(c, c->lo.act)};
+    if ((rc = launch_mfma(c, eg, rows, m, d, F, true, SPARK_KC_GATEUP))) return rc;
+
+    if ((rc = launch_prep(c, rows, m, at<float>(c, c->lo.act), F, 0, nullptr, F))) return rc;
+    EpiResidual<WT> ed{(const WT *)c->w.wd + (size_t)l * d * F, F, d, hidden, d};
+    if ((rc = launch_mfma(c, ed, rows, m, F, d / 2, true, SPARK_KC_DOWN))) return rc;
+  }
+  return SPARK_OK;
+}
+
 // layers [l0, l1) on m rows described by `rows` (device)
 template <typename WT>
 int run_layers(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m, bool one_sequence = false) {
@@ -361,6 +475,9 @@ int run_layers(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m, bool on
   // up to four consecutive positions of one sequence: the whole run of layers is one launch
   if (one_sequence && m <= 4 && c->use_pass_kernel && pass_supported<WT>(g.head_dim, c->dv.group))
     return launch_pass<WT>(c, l0, l1, rows, m);
+  // many rows: the projections are dense contractions for the MFMA units
+  if (std::is_same<WT, bf16_t>::value && m >= MFMA_MIN_ROWS && c->use_mfma)
+    return run_layers_mfma(c, l0, l1, rows, m);
   const int d = g.d_model, hd = g.head_dim, nq = g.n_q_heads, nkv = g.n_kv_heads, F = g.d_ffn;
   const size_t qw = (size_t)nq * hd, kvw = (size_t)nkv * hd;
   float *hidden = at<float>(c, c->lo.hidden);
@@ -400,6 +517,18 @@ template <typename WT> int run_lens_head(spark_ctx *c, const RowDesc *rows, int 
   const int d = g.d_model, V = c->dv.V;
   float *hidden = at<float>(c, c->lo.hidden), *u = at<float>(c, c->lo.lens_u);
   int rc;
+  if (std::is_same<WT, bf16_t>::value && m >= MFMA_MIN_ROWS && c->use_mfma) {
+    if ((rc = launch_prep(c, rows, m, hidden, d, 1, nullptr, d))) return rc;
+    EpiLensAffine<bf16_t> ea{(const bf16_t *)c->w.lens_a, c->w.lens_b, hidden, u, d};
+    if ((rc = launch_mfma(c, ea, rows, m, d, d / 2, true, SPARK_KC_LENS))) return rc;
+    if ((rc = launch_prep(c, rows, m, u, d, 0, c->w.lens_norm, d))) return rc;
+    EpiVocab<bf16_t> ev{(const bf16_t *)c->w.lens_head, d, V, at<float>(c, c->lo.logits),
+                        at<unsigned long long>(c, c->lo.best)};
+    rc = prof_begin(c, SPARK_KC_LENS);
+    if (rc) return rc;
+    if ((rc = launch_mfma_tiles<1>(c, ev, rows, m, d, (V + 1) / 2, false))) return rc;
+    return prof_end(c, SPARK_KC_LENS);
+  }
   ProPlain ph{hidden, d, 1};
   EpiLensAffine<WT> ea{(const WT *)c->w.lens_a, c->w.lens_b, hidden, u, d};
   if ((rc = launch_gemv<WT>(c, ph, ea, rows, m, d, d / 2, SPARK_KC_LENS))) return rc;
@@ -413,6 +542,16 @@ template <typename WT> int run_lens_head(spark_ctx *c, const RowDesc *rows, int 
 template <typename WT> int run_final_head(spark_ctx *c, const RowDesc *rows, int m) {
   const spark_config &g = c->cfg;
   const int d = g.d_model, V = c->dv.V;
+  if (std::is_same<WT, bf16_t>::value && m >= MFMA_MIN_ROWS && c->use_mfma) {
+    int rc;
+    if ((rc = launch_prep(c, rows, m, at<float>(c, c->lo.hidden), d, 1, c->w.final_norm, d))) return rc;
+    EpiVocab<bf16_t> ev{(const bf16_t *)c->w.lm_head, d, V, at<float>(c, c->lo.logits),
+                        at<unsigned long long>(c, c->lo.best)};
+    rc = prof_begin(c, SPARK_KC_HEAD);
+    if (rc) return rc;
+    if ((rc = launch_mfma_tiles<1>(c, ev, rows, m, d, (V + 1) / 2, false))) return rc;
+    return prof_end(c, SPARK_KC_HEAD);
+  }
   ProNorm pn{at<float>(c, c->lo.hidden), c->w.final_norm, g.rms_eps, d, 1};
   EpiVocab<WT> ev{(const WT *)c->w.lm_head, d, V, at<float>(c, c->lo.logits),
                   at<unsigned long long>(c, c->lo.best)};
@@ -666,6 +805,8 @@ int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_p
   // one kernel per operation yet; it is used when SPARK_PASS_KERNEL=1.
   const char *pass = getenv("SPARK_PASS_KERNEL");
   c->use_pass_kernel = pass && pass[0] == '1';
+  const char *no_mfma = getenv("SPARK_NO_MFMA");
+  c->use_mfma = !(no_mfma && no_mfma[0] == '1');
   const char *tl = getenv("SPARK_PASS_TIMELINE");   // debugging aid: per-phase times on stderr
   if (tl && tl[0] == '1' &&
       hipMalloc((void **)&c->timeline_dev, sizeof(unsigned long long) * 16384) != hipSuccess)

@@ -230,3 +230,24 @@ def test_persistent_layer_pass_kernel(sb, tiny_weights, monkeypatch):
     compare_run(sp, shape, sched, weights, [wl.make_prompt(shape, 300, seed=5)], [1], 24,
                 check_kv_every=4, label="pass bf16-gqa7")
     sp.close()
+
+
+def test_batched_decode_on_the_mfma_path(sb):
+    """24 bf16 sequences with mixed schedules in every step: 24 rows through layers 1..e, the
+    early-exit rows through the layer-specific head, the full-depth rows with their pending rows
+    (up to 4 each) through layers e+1..L and the final head -- all as MFMA contractions"""
+    shape = wl.TINY.shape.replace(name="bf16-batch", dtype=wl.DTYPE_BF16, n_layers=4, d_model=512,
+                                  n_q_heads=8, n_kv_heads=4, head_dim=64, d_ffn=1536 + 72,
+                                  vocab_text=1500, vocab_speech=701)
+    sched = wl.TINY.schedule
+    say("case batched mfma")
+    weights = wl.make_weights(shape, seed=6, gain_std=0.1)
+    B = 24
+    lens = wl.make_prompt_lengths(B, 3, 90, seed=3)
+    prompts = [wl.make_prompt(shape, int(n), seed=40 + i) for i, n in enumerate(lens)]
+    offsets = [i % 6 for i in range(B)]
+    sp = sb.Spark(shape, sched, weights, max_batch=B, max_seq_len=160, kv_page_tokens=16)
+    a = compare_run(sp, shape, sched, weights, prompts, offsets, 14, check_kv_every=7,
+                    label="batch24 bf16")
+    assert len(np.unique(a["depths"], axis=1)) > 1
+    sp.close()
