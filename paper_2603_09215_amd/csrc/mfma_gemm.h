@@ -2,9 +2,11 @@
 // units.  With that many rows a projection is a real dense contraction: every weight element is
 // used 32..128 times, so the vector kernel that serves a handful of rows would be ALU-bound.
 //
-// Weights are bf16.  Activations are fp32; each is split into a bf16 "hi" part and a bf16 "lo"
-// part of the remainder (x = hi + lo to about 2^-17), and both go through the MFMA, which keeps
-// the result at fp32-level accuracy instead of rounding the activations to 8 bits of mantissa.
+// Weights are bf16.  Activations are fp32; each is split into three bf16 parts (x = hi + mid + lo
+// exactly, 3 x 8 mantissa bits) and all three go through the MFMA, which keeps the result at fp32
+// accuracy instead of rounding the activations to 8 bits of mantissa.  (Two parts leave 2^-17
+// relative error per element; re-rounded to bf16 in the KV cache that is enough to double the
+// deviation from the oracle, so the third part is kept.)
 //
 // v_mfma_f32_32x32x16_bf16: A is 32 weight rows x 16 k, B is 16 k x 32 activation rows; lane l
 // supplies 8 consecutive k of row (l % 32), k-block (l / 32); of the 16 results in a lane,
@@ -33,11 +35,12 @@ constexpr int MG_TASKS_PER_BLOCK = MG_WAVES * MG_TASKS_PER_WAVE;
 
 // ------------------------------------------------------------------ activation preparation
 
-// xhi/xlo[r][k] = split(x_r[k]), x_r = src row (plain) or RMSNorm(hidden[x_slot_r]; gamma)
+// xs[part][r][k] = the three bf16 parts of x_r[k], x_r = src row (plain) or
+// RMSNorm(hidden[x_slot_r]; gamma); part p starts at xs + p * part_stride
 __global__ void __launch_bounds__(256)
 prep_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ src, int stride, int indirect,
-            const float *__restrict__ gamma, float eps, int n, bf16_t *__restrict__ xhi,
-            bf16_t *__restrict__ xlo) {
+            const float *__restrict__ gamma, float eps, int n, bf16_t *__restrict__ xs,
+            size_t part_stride) {
   __shared__ float red[4];
   const int r = blockIdx.x;
   const float *row = src + (size_t)(indirect ? rows[r].x_slot : r) * stride;
@@ -60,14 +63,18 @@ prep_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ src, int
       v = make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w);
     }
     const float f[4] = {v.x, v.y, v.z, v.w};
-    bf16_t h[4], l[4];
+    bf16_t h[4], mid[4], l[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       h[e] = f32_to_bf16(f[e]);
-      l[e] = f32_to_bf16(f[e] - bf16_to_f32(h[e]));
+      const float rem = f[e] - bf16_to_f32(h[e]);      // exact
+      mid[e] = f32_to_bf16(rem);
+      l[e] = f32_to_bf16(rem - bf16_to_f32(mid[e]));   // exact remainder has at most 8 bits left
     }
-    *(uint2 *)(xhi + (size_t)r * n + k) = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
-    *(uint2 *)(xlo + (size_t)r * n + k) = make_uint2(l[0] | ((uint32_t)l[1] << 16), l[2] | ((uint32_t)l[3] << 16));
+    bf16_t *dst = xs + (size_t)r * n + k;
+    *(uint2 *)dst = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
+    *(uint2 *)(dst + part_stride) = make_uint2(mid[0] | ((uint32_t)mid[1] << 16), mid[2] | ((uint32_t)mid[3] << 16));
+    *(uint2 *)(dst + 2 * part_stride) = make_uint2(l[0] | ((uint32_t)l[1] << 16), l[2] | ((uint32_t)l[3] << 16));
   }
 }
 
@@ -77,12 +84,11 @@ prep_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ src, int
 // SPLIT: write partial sums part[split][task][2][m_pad] instead of running the epilogue.
 template <int MTILES, typename Epi, bool SPLIT>
 __global__ void __launch_bounds__(MG_THREADS)
-mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t *__restrict__ xhi,
-            const bf16_t *__restrict__ xlo, int n_in, int n_tasks, int chunks_per_split,
+mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t *__restrict__ xs,
+            size_t part_stride, int n_in, int n_tasks, int chunks_per_split,
             float *__restrict__ part, int m_pad) {
   constexpr int MROWS = 32 * MTILES;
-  __shared__ __attribute__((aligned(16))) bf16_t s_hi[MROWS * MG_ROWPAD];
-  __shared__ __attribute__((aligned(16))) bf16_t s_lo[MROWS * MG_ROWPAD];
+  __shared__ __attribute__((aligned(16))) bf16_t s_x[3][MROWS * MG_ROWPAD];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row0 = blockIdx.z * MROWS;
   const int task0 = blockIdx.x * MG_TASKS_PER_BLOCK + wave * MG_TASKS_PER_WAVE;
@@ -128,13 +134,14 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
     for (int v = threadIdx.x; v < MROWS * (MG_KC / 8); v += MG_THREADS) {
       const int m = v / (MG_KC / 8), kv = (v - m * (MG_KC / 8)) * 8;
       const int k = chunk * MG_KC + kv;
-      uint4 h = make_uint4(0, 0, 0, 0), l = make_uint4(0, 0, 0, 0);
+      uint4 x3[3] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
       if (row0 + m < m_rows && k < n_in) {
-        h = *(const uint4 *)(xhi + (size_t)(row0 + m) * n_in + k);
-        l = *(const uint4 *)(xlo + (size_t)(row0 + m) * n_in + k);
+        const bf16_t *src = xs + (size_t)(row0 + m) * n_in + k;
+#pragma unroll
+        for (int p = 0; p < 3; ++p) x3[p] = *(const uint4 *)(src + p * part_stride);
       }
-      *(uint4 *)(s_hi + m * MG_ROWPAD + kv) = h;
-      *(uint4 *)(s_lo + m * MG_ROWPAD + kv) = l;
+#pragma unroll
+      for (int p = 0; p < 3; ++p) *(uint4 *)(s_x[p] + m * MG_ROWPAD + kv) = x3[p];
     }
     if (chunk + 1 < c_end) load_chunk(chunk + 1);   // next chunk's weights fly during the MFMAs
     __syncthreads();
@@ -145,12 +152,13 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
 #pragma unroll
       for (int c = 0; c < MTILES; ++c) {
         const int off = (c * 32 + (lane & 31)) * MG_ROWPAD + s * 16 + koff;
-        const bf16x8_t bh = __builtin_bit_cast(bf16x8_t, *(const uint4 *)(s_hi + off));
-        const bf16x8_t bl = __builtin_bit_cast(bf16x8_t, *(const uint4 *)(s_lo + off));
-        acc0[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bh, acc0[c], 0, 0, 0);
-        acc0[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bl, acc0[c], 0, 0, 0);
-        acc1[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bh, acc1[c], 0, 0, 0);
-        acc1[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bl, acc1[c], 0, 0, 0);
+        // smallest part first, so that the large terms are added last
+#pragma unroll
+        for (int p = 2; p >= 0; --p) {
+          const bf16x8_t b = __builtin_bit_cast(bf16x8_t, *(const uint4 *)(s_x[p] + off));
+          acc0[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc0[c], 0, 0, 0);
+          acc1[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc1[c], 0, 0, 0);
+        }
       }
     }
   }

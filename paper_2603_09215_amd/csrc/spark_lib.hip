@@ -30,7 +30,7 @@ constexpr int MAX_SEQ_LEN = 16384;
 
 struct Layout {  // byte offsets into the scratch buffer
   size_t state, page_table, plan, lower, upper, ee, full, prefill_rows, prefill_tokens, seq_ids,
-      forced, step_flags, out_tokens, out_depth, best, arrivals, barrier, hidden, xhi, xlo, mfma_part, qbuf, attn_out, part, act, lens_u,
+      forced, step_flags, out_tokens, out_depth, best, arrivals, barrier, hidden, xsplit, mfma_part, qbuf, attn_out, part, act, lens_u,
       logits, rope, inv_freq, total;
 };
 
@@ -173,8 +173,7 @@ void layout(const spark_config &c, const Derived &d, Layout &l) {
   l.lens_u = take(sizeof(float) * (size_t)c.max_batch * c.d_model);
   {
     const size_t widest = std::max((size_t)c.d_ffn, std::max((size_t)c.d_model, qw));
-    l.xhi = take(sizeof(bf16_t) * (size_t)d.max_rows * widest);
-    l.xlo = take(sizeof(bf16_t) * (size_t)d.max_rows * widest);
+    l.xsplit = take(sizeof(bf16_t) * 3 * (size_t)d.max_rows * widest);
     l.mfma_part = take(c.dtype == SPARK_DTYPE_BF16 ? MFMA_PARTIAL_BYTES : 256);
   }
   l.logits = take(sizeof(float) * (size_t)c.max_batch * d.V);
@@ -374,10 +373,17 @@ template <typename WT> int launch_pass(spark_ctx *c, int l0, int l1, const RowDe
 
 constexpr int MFMA_MIN_ROWS = 16;
 
+// the three bf16 parts of the split activations are stored one after the other
+size_t xsplit_stride(spark_ctx *c) {
+  const spark_config &g = c->cfg;
+  const size_t widest = std::max((size_t)g.d_ffn, std::max((size_t)g.d_model, (size_t)g.n_q_heads * g.head_dim));
+  return (size_t)c->dv.max_rows * widest;
+}
+
 int launch_prep(spark_ctx *c, const RowDesc *rows, int m, const float *src, int stride, int indirect,
                 const float *gamma, int n) {
   prep_rows_k<<<m, 256, 0, c->stream>>>(rows, src, stride, indirect, gamma, c->cfg.rms_eps, n,
-                                        at<bf16_t>(c, c->lo.xhi), at<bf16_t>(c, c->lo.xlo));
+                                        at<bf16_t>(c, c->lo.xsplit), xsplit_stride(c));
   HIP_TRY(c, hipGetLastError());
   return SPARK_OK;
 }
@@ -398,16 +404,17 @@ int launch_mfma_tiles(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, 
   }
   const int cps = (n_chunks + split - 1) / split;
   split = (n_chunks + cps - 1) / cps;
-  const bf16_t *xhi = at<bf16_t>(c, c->lo.xhi), *xlo = at<bf16_t>(c, c->lo.xlo);
+  const bf16_t *xs = at<bf16_t>(c, c->lo.xsplit);
+  const size_t xst = xsplit_stride(c);
   float *part = at<float>(c, c->lo.mfma_part);
   dim3 grid(bx, split, z);
   if (split > 1) {
-    mfma_rows_k<MTILES, Epi, true><<<grid, MG_THREADS, 0, c->stream>>>(epi, rows, m, xhi, xlo, n_in,
+    mfma_rows_k<MTILES, Epi, true><<<grid, MG_THREADS, 0, c->stream>>>(epi, rows, m, xs, xst, n_in,
                                                                        n_tasks, cps, part, m_pad);
     const int total = n_tasks * m_pad;
     mfma_finish_k<Epi><<<(total + 255) / 256, 256, 0, c->stream>>>(epi, rows, m, n_tasks, split, part, m_pad);
   } else {
-    mfma_rows_k<MTILES, Epi, false><<<grid, MG_THREADS, 0, c->stream>>>(epi, rows, m, xhi, xlo, n_in,
+    mfma_rows_k<MTILES, Epi, false><<<grid, MG_THREADS, 0, c->stream>>>(epi, rows, m, xs, xst, n_in,
                                                                         n_tasks, cps, part, m_pad);
   }
   HIP_TRY(c, hipGetLastError());
