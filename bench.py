@@ -24,6 +24,19 @@ import numpy as np
 import workloads as wl
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16
+
+
+def measured_traffic(shape):
+    """HBM bytes per launch of the gate/up kernel from the committed rocprofv3 counter summary
+    (FETCH_SIZE + WRITE_SIZE, scaled), if there is one for this shape; else None"""
+    import pathlib
+    import re
+    f = pathlib.Path(__file__).resolve().parent / "profiles" / f"gateup_gemv_{shape.name}_hbm_traffic.txt"
+    if not f.exists():
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*(\d+)", f.read_text(), flags=re.M)
+    return int(m.group(1)) if m else None
 
 
 def step_bytes(shape, sched, ctx_len: float):
@@ -49,6 +62,9 @@ def main() -> int:
     ap.add_argument("--prompt-len", type=int, default=None)
     ap.add_argument("--cpu-steps", type=int, default=12, help="oracle steps timed for cpu_baseline (0 = skip)")
     ap.add_argument("--profile-steps", type=int, default=48)
+    ap.add_argument("--batch", type=int, default=1,
+                    help="sequences decoded together (default 1: the headline workload); >1 gives "
+                         "random prompt lengths in 256..2048 and mixed cycle offsets")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (no collectives, no "
@@ -74,32 +90,54 @@ def main() -> int:
         dev_w = wl.make_weights_on_device(shape, seed=0, device="cuda:0")
     else:
         dev_w = wl.make_weights(shape, seed=0)
-    sp = Spark(shape, sched, dev_w, max_batch=1, max_seq_len=max_seq, kv_page_tokens=64, device="cuda:0")
-    prompt = wl.make_prompt(shape, prompt_len, seed=1, ids=w.prompt_ids)
-    sid = sp.seq_open(0)
+    B = args.batch
+    if B > 1:
+        plens = [int(x) for x in wl.make_prompt_lengths(B, 256, 2048, seed=3)]
+        max_seq = min(16384, (max(plens) + W + K + args.profile_steps + 64 + 63) // 64 * 64)
+    else:
+        plens = [prompt_len]
+    sp = Spark(shape, sched, dev_w, max_batch=B, max_seq_len=max_seq, kv_page_tokens=64, device="cuda:0")
+    cyc = sched.n_text + sched.n_speech
+    sids = [sp.seq_open(i % cyc if B > 1 else 0) for i in range(B)]
+    prompts = [wl.make_prompt(shape, n, seed=1 + i, ids=w.prompt_ids) for i, n in enumerate(plens)]
+    prompt = prompts[0]
+    sid = sids[0]
     torch.cuda.synchronize()
     tp0 = time.perf_counter()
-    sp.prefill(sid, prompt)
+    for s_, p_ in zip(sids, prompts):
+        sp.prefill(s_, p_)
     torch.cuda.synchronize()
     prefill_s = time.perf_counter() - tp0
-    print(f"[bench] weights + prefill({prompt_len}) ready in {time.time() - t0:.1f}s "
+    print(f"[bench] weights + prefill({sum(plens)} tokens) ready in {time.time() - t0:.1f}s "
           f"(prefill {prefill_s * 1e3:.1f} ms)", file=sys.stderr, flush=True)
+    # useful flops of the prompt pass: 2 per weight element and row, plus causal attention
+    esz_ = 2 if shape.dtype == wl.DTYPE_BF16 else 4
+    qd = shape.n_q_heads * shape.head_dim
+    kvd = shape.n_kv_heads * shape.head_dim
+    w_elems_layer = (qd + 2 * kvd) * shape.d_model + shape.d_model * qd + 3 * shape.d_ffn * shape.d_model
+    pre_rows = sum(n - 1 for n in plens)
+    pre_flops = 2.0 * w_elems_layer * shape.n_layers * pre_rows + \
+        sum(2.0 * (n - 1) ** 2 * qd * shape.n_layers for n in plens)
+    prefill = {"tokens": pre_rows, "ms": round(prefill_s * 1e3, 2),
+               "tokens_per_s": round(pre_rows / prefill_s, 1),
+               "useful_TFLOPs": round(pre_flops / prefill_s / 1e12, 2),
+               "frac_of_mfma_bf16_peak": round(pre_flops / prefill_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
 
     # ---- warm-up, then the timed region: exactly K steps, tokens fed back on the device
-    sp.decode(W, [sid])
+    sp.decode(W, sids)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    tok, dep = sp.decode(K, [sid])
+    tok, dep = sp.decode(K, sids)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t1
     ms_per_step = elapsed * 1e3 / K
-    value = K / elapsed
+    value = K * B / elapsed
 
     # ---- per-class step times (one synchronous spark_step per token), same sequence continues
     n_cls = min(args.profile_steps, 48)
     cls = {}
     ctx_now = prompt_len - 1 + W + K
-    for i in range(n_cls):
+    for i in range(n_cls if B == 1 else 0):
         torch.cuda.synchronize()
         a = time.perf_counter()
         t_, d_ = sp.step([sid])
@@ -119,20 +157,31 @@ def main() -> int:
     esz = 2 if shape.dtype == wl.DTYPE_BF16 else 4
     gateup_bytes = 2 * shape.d_ffn * shape.d_model * esz
     sp.profile_select("gateup")
-    sp.decode(args.profile_steps, [sid])
+    if args.profile_steps > 0:
+        sp.decode(args.profile_steps, sids)
     n_launch, tot_ms = sp.profile_read()
     sp.profile_select(-1)
     avg_ms = tot_ms / max(1, n_launch)
     achieved = gateup_bytes / (avg_ms * 1e-3) / 1e9 if n_launch else 0.0
     roofline = {"bound": "hbm", "kernel": "gemv_rows_k<gate/up + SwiGLU>", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": None, "bytes_per_launch": gateup_bytes, "avg_launch_ms": round(avg_ms, 5),
+                "traffic": measured_traffic(shape), "bytes_per_launch": gateup_bytes, "avg_launch_ms": round(avg_ms, 5),
                 "launches_timed": int(n_launch)}
 
     depth_all = dep[:, 0]
     mix = {"full_steps": int((depth_all == shape.n_layers).sum()), "ee_steps": int((depth_all != shape.n_layers).sum())}
     stats = sp.get_stats(sid)
-    avg_bytes = (mix["full_steps"] * full_b + mix["ee_steps"] * ee_b) / K
+    if B > 1:   # any full-depth row in a step streams the upper layers; both heads usually run
+        any_full = int((dep == shape.n_layers).any(axis=1).sum())
+        any_ee = int((dep != shape.n_layers).any(axis=1).sum())
+        head_b = shape.vocab * shape.d_model * esz
+        lower = sched.exit_layer * w_layer
+        upper = (shape.n_layers - sched.exit_layer) * w_layer
+        avg_bytes = (K * lower + any_full * (upper + head_b) +
+                     any_ee * (head_b + shape.d_model ** 2 * esz)) / K
+        mix = {"steps_with_a_full_depth_row": any_full, "steps_with_an_early_exit_row": any_ee}
+    else:
+        avg_bytes = (mix["full_steps"] * full_b + mix["ee_steps"] * ee_b) / K
     whole = {"algorithmic_GB_per_step": round(avg_bytes / 1e9, 3),
              "GBps": round(avg_bytes / (ms_per_step * 1e-3) / 1e9, 1),
              "frac_of_hbm_peak": round(avg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
@@ -156,20 +205,20 @@ def main() -> int:
         osq.close(); om.close()
 
     line = {
-        "metric": "decode tokens/s per GPU (batch 1)", "value": round(value, 2), "unit": "tokens/s",
+        "metric": f"decode tokens/s per GPU (batch {B})", "value": round(value, 2), "unit": "tokens/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if shape.dtype == wl.DTYPE_BF16 else "f32", "data": "synthetic",
         "config": {"workload": f"{shape.name}: L={shape.n_layers} d={shape.d_model} "
                                f"{shape.n_q_heads}q/{shape.n_kv_heads}kv hd={shape.head_dim} F={shape.d_ffn} "
-                               f"V={shape.vocab}; prompt {prompt_len}, decode {K}, batch 1, "
+                               f"V={shape.vocab}; prompt {prompt_len if B == 1 else '256..2048'}, decode {K}, batch {B}, "
                                f"{sched.n_text}:{sched.n_speech} text:speech, e={sched.exit_layer}, "
                                f"K={sched.period_k}, phase={sched.phase}, "
                                f"scope={'chunk' if sched.scope == 0 else 'stream'}",
                    "weights": "random N(0,0.02), fp32 accumulation", "kv_cache": "paged, 64 tokens/page",
                    "step_mix": mix, "mean_speech_depth": stats["mean_speech_depth"],
                    "speech_layer_saving_pct": round(stats["speech_layer_saving"], 2),
-                   "prefill_ms": round(prefill_s * 1e3, 1)},
+                   "prefill": prefill},
         "roofline": roofline, "whole_step": whole, "step_classes": classes, "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)

@@ -167,7 +167,8 @@ const char *spark_last_error(const spark_ctx *ctx);
 /* Measurement support.  While `kernel_class` is >= 0, every launch of that class of kernel during
  * spark_step / spark_decode is bracketed by HIP events on the context's stream;
  * spark_profile_read waits for them and reports the number of bracketed launches and their summed
- * duration in milliseconds since the last read.  Classes: see SPARK_KC_*.  -1 switches it off. */
+ * duration in milliseconds since the last read, net of the cost of an empty bracket (measured
+ * with a third event behind every bracket).  Classes: see SPARK_KC_*.  -1 switches it off. */
 #define SPARK_KC_QKV 0
 #define SPARK_KC_ATTN 1
 #define SPARK_KC_OPROJ 2

@@ -186,14 +186,15 @@ template <typename T> T *at(spark_ctx *c, size_t off) { return (T *)(c->scratch 
 
 // ------------------------------------------------------------------ profiling brackets
 
+// Every bracketed launch takes three events: before, after, and one more right behind it.  The
+// last pair has nothing in between and measures what the event mechanism itself adds to a bracket;
+// spark_profile_read subtracts its mean.
 int prof_begin(spark_ctx *c, int kclass) {
   if (c->prof_class != kclass) return SPARK_OK;
-  if (c->prof_used + 2 > c->prof_ev.size()) {
-    for (int i = 0; i < 2; ++i) {
-      hipEvent_t ev;
-      HIP_TRY(c, hipEventCreate(&ev));
-      c->prof_ev.push_back(ev);
-    }
+  while (c->prof_used + 3 > c->prof_ev.size()) {
+    hipEvent_t ev;
+    HIP_TRY(c, hipEventCreate(&ev));
+    c->prof_ev.push_back(ev);
   }
   HIP_TRY(c, hipEventRecord(c->prof_ev[c->prof_used], c->stream));
   return SPARK_OK;
@@ -201,7 +202,8 @@ int prof_begin(spark_ctx *c, int kclass) {
 int prof_end(spark_ctx *c, int kclass) {
   if (c->prof_class != kclass) return SPARK_OK;
   HIP_TRY(c, hipEventRecord(c->prof_ev[c->prof_used + 1], c->stream));
-  c->prof_used += 2;
+  HIP_TRY(c, hipEventRecord(c->prof_ev[c->prof_used + 2], c->stream));
+  c->prof_used += 3;
   return SPARK_OK;
 }
 
@@ -1028,13 +1030,16 @@ int spark_profile_select(spark_ctx *c, int32_t kernel_class) {
 int spark_profile_read(spark_ctx *c, int64_t *n_launches, double *total_ms) {
   if (!c || !n_launches || !total_ms) return SPARK_EINVAL;
   HIP_TRY(c, hipStreamSynchronize(c->stream));
-  double tot = 0;
-  for (size_t i = 0; i + 1 < c->prof_used; i += 2) {
-    float ms = 0;
+  double tot = 0, empty = 0;
+  for (size_t i = 0; i + 2 < c->prof_used; i += 3) {
+    float ms = 0, ms0 = 0;
     HIP_TRY(c, hipEventElapsedTime(&ms, c->prof_ev[i], c->prof_ev[i + 1]));
+    HIP_TRY(c, hipEventElapsedTime(&ms0, c->prof_ev[i + 1], c->prof_ev[i + 2]));
     tot += ms;
+    empty += ms0;
   }
-  *n_launches = (int64_t)(c->prof_used / 2);
+  tot -= empty;   // what the brackets themselves cost
+  *n_launches = (int64_t)(c->prof_used / 3);
   *total_ms = tot;
   c->prof_used = 0;
   return SPARK_OK;
