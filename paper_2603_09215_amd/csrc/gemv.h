@@ -243,7 +243,8 @@ __device__ __forceinline__ uint4 load_weights16(const void *p) {
   return make_uint4(t.x, t.y, t.z, t.w);
 }
 
-constexpr int GEMV_U = 2;  // 16-byte loads in flight per weight row and pipeline stage
+constexpr int GEMV_U = 2;  // 16-byte loads per weight row and pipeline stage (many waves per CU)
+constexpr int GEMV_U_DEEP = 4;  // same, for launches whose LDS use leaves only two workgroups per CU
 
 // One pipeline stage of weights: U consecutive 1 KiB segments of both rows of a task.
 template <int U> struct WStage {
@@ -300,7 +301,7 @@ __device__ __forceinline__ void fma_block(const uint4 &a, const uint4 &b, const 
 // task) are issued before the current stage is consumed, and the very first stage is issued
 // before the prologue touches the activations, so the norm, the reduction and the epilogue all
 // run under outstanding HBM requests.
-template <typename WT, int MT, typename Pro, typename Epi>
+template <typename WT, int MT, typename Pro, typename Epi, int U = GEMV_U>
 __global__ void __launch_bounds__(GEMV_THREADS)
 gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int n_in, int n_tasks,
             int kc) {
@@ -309,7 +310,7 @@ gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int 
   float *red = xs + MT * kc;           // [GEMV_WAVES][MT] partial sums of squares
   constexpr int VEC = Elem<WT>::VEC;
   constexpr int WSTEP = 64 * VEC;
-  constexpr int GSTEP = GEMV_U * WSTEP;
+  constexpr int GSTEP = U * WSTEP;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int tile0 = blockIdx.y * MT;
   const int n_valid = min(MT, m_rows - tile0);
@@ -325,7 +326,7 @@ gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int 
   epi.init(st);
 
   // prime the pipeline: first stage of this wave's first task
-  WStage<GEMV_U> nxt;
+  WStage<U> nxt;
   const WT *r0, *r1;
   bool valid = wave_global < n_tasks;
   epi.weight_rows(valid ? wave_global : 0, r0, r1);
@@ -350,7 +351,7 @@ gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int 
       }
       const int n_groups = (klen + GSTEP - 1) / GSTEP;
       for (int g = 0; g < n_groups; ++g) {
-        const WStage<GEMV_U> cur = nxt;
+        const WStage<U> cur = nxt;
         if (g + 1 < n_groups) {
           issue_stage<WT>(nxt, r0 + k0, r1 + k0, (g + 1) * GSTEP, klen, lane, valid);
         } else if (chunk + 1 < n_chunks) {
@@ -360,7 +361,7 @@ gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int 
         }
         if (valid) {
 #pragma unroll
-          for (int u = 0; u < GEMV_U; ++u) {
+          for (int u = 0; u < U; ++u) {
             const int kb = g * GSTEP + u * WSTEP;
             if (kb < klen) fma_block<WT, MT>(cur.a[u], cur.b[u], xs, kc, kb, lane, acc0, acc1);
           }

@@ -232,11 +232,13 @@ int launch_gemv(spark_ctx *c, const Pro &pro, const Epi &epi, const RowDesc *row
   // one resident set of blocks: the kernel loops over its tasks, so the grid is sized to what the
   // chip holds at once (no second wave of blocks with a cold pipeline)
   void (*kern)(Pro, Epi, const RowDesc *, int, int, int, int) = nullptr;
+  // much LDS per workgroup means few waves per CU: those launches keep more loads in flight
+  const bool deep = lds > 40960;
   switch (mt) {
-    case 1: kern = gemv_rows_k<WT, 1, Pro, Epi>; break;
-    case 2: kern = gemv_rows_k<WT, 2, Pro, Epi>; break;
-    case 3: kern = gemv_rows_k<WT, 3, Pro, Epi>; break;
-    default: kern = gemv_rows_k<WT, 4, Pro, Epi>; break;
+    case 1: kern = deep ? gemv_rows_k<WT, 1, Pro, Epi, GEMV_U_DEEP> : gemv_rows_k<WT, 1, Pro, Epi>; break;
+    case 2: kern = deep ? gemv_rows_k<WT, 2, Pro, Epi, GEMV_U_DEEP> : gemv_rows_k<WT, 2, Pro, Epi>; break;
+    case 3: kern = deep ? gemv_rows_k<WT, 3, Pro, Epi, GEMV_U_DEEP> : gemv_rows_k<WT, 3, Pro, Epi>; break;
+    default: kern = deep ? gemv_rows_k<WT, 4, Pro, Epi, GEMV_U_DEEP> : gemv_rows_k<WT, 4, Pro, Epi>; break;
   }
   if (lds > 65536)
     HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 81920));
