@@ -223,6 +223,7 @@ __device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int 
     store2_maybe_ds<DS>(dst, make_float2(acc4.x, acc4.y));
     store2_maybe_ds<DS>(dst + 2, make_float2(acc4.z, acc4.w));
   }
+  if (DS) wait_memory_ops();   // the caller's next barrier arrival does not wait for these stores
 }
 
 // stand-alone launch: one workgroup per (slice, kv head, row)

@@ -160,8 +160,17 @@ template <typename WT, bool DS = false> struct EpiResidual {
     v.x += y0; v.y += y1;
     store2_maybe_ds<DS>(h, v);
   }
+  // the same in two halves, for a caller that fetches the old value long before the sum is ready
+  __device__ float2 load_old(int task, const RowDesc &rd) const {
+    return load2_maybe_ds<DS>(hidden + (size_t)rd.x_slot * d + 2 * task);
+  }
+  __device__ void finish_old(int task, const RowDesc &rd, float y0, float y1, float2 old) const {
+    store2_maybe_ds<DS>(hidden + (size_t)rd.x_slot * d + 2 * task, make_float2(old.x + y0, old.y + y1));
+  }
   __device__ void end(int, const RowDesc &, State &) const {}
 };
+template <typename E> struct EpiReadsOld { static constexpr bool value = false; };
+template <typename WT, bool DS> struct EpiReadsOld<EpiResidual<WT, DS>> { static constexpr bool value = true; };
 
 // act[r][i] = silu(Wg_i . n) * (Wu_i . n)
 template <typename WT, bool DS = false> struct EpiSwiGLU {
@@ -245,6 +254,7 @@ __device__ __forceinline__ uint4 load_weights16(const void *p) {
 
 constexpr int GEMV_U = 2;  // 16-byte loads per weight row and pipeline stage (many waves per CU)
 constexpr int GEMV_U_DEEP = 4;  // same, for launches whose LDS use leaves only two workgroups per CU
+constexpr int GEMV_D = 2;  // stages in the register ring
 
 // One pipeline stage of weights: U consecutive 1 KiB segments of both rows of a task.
 template <int U> struct WStage {
@@ -292,16 +302,36 @@ __device__ __forceinline__ void fma_block(const uint4 &a, const uint4 &b, const 
   }
 }
 
+// Same loads without a branch around them: a lane beyond klen, or a wave without a task, reads the
+// first 16 bytes of the row instead (a cache hit) and its products meet zeros in the staged
+// activations (or are discarded).  With every load issued unconditionally the compiler knows how
+// many are outstanding at each point and waits for exactly the stage it is about to use; a
+// conditional load makes it wait for all of them, which empties the pipeline at every stage.
+template <typename WT, int U>
+__device__ __forceinline__ void issue_stage_nb(WStage<U> &s, const WT *p0, const WT *p1, int kb, int klen,
+                                               int lane, bool valid) {
+  constexpr int VEC = Elem<WT>::VEC;
+  constexpr int WSTEP = 64 * VEC;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int k = kb + u * WSTEP + lane * VEC;
+    const int ko = (valid && k < klen) ? k : 0;
+    s.a[u] = load_weights16(p0 + ko);
+    s.b[u] = load_weights16(p1 + ko);
+  }
+}
+
 // grid.x: blocks that share the weight rows; grid.y: tiles of MT activation rows.
 // kc: activation elements of one row held in LDS at a time (multiple of 512).
 // Dynamic LDS: (MT*kc + GEMV_WAVES*MT) floats.
 //
-// The weight stream is software-pipelined across everything else the wave does: the loads of the
-// next stage (next segments of the row, next chunk, or the first segments of the wave's next
-// task) are issued before the current stage is consumed, and the very first stage is issued
-// before the prologue touches the activations, so the norm, the reduction and the epilogue all
-// run under outstanding HBM requests.
-template <typename WT, int MT, typename Pro, typename Epi, int U = GEMV_U>
+// A wave walks its weights as one sequence of stages (U 16-byte loads per row and lane): for each
+// of its tasks, for each LDS chunk of the input, for each group of the chunk.  D stages live in a
+// ring of registers; a slot is refilled with the stage D ahead as soon as it has been consumed, so
+// D-1 stages are in flight while one is multiplied, across chunk and task boundaries, and the
+// first D stages are issued before the prologue touches the activations: the norm, the
+// reductions and the epilogues all run under outstanding HBM requests.
+template <typename WT, int MT, typename Pro, typename Epi, int U = GEMV_U, int D = GEMV_D>
 __global__ void __launch_bounds__(GEMV_THREADS)
 gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int n_in, int n_tasks,
             int kc) {
@@ -320,67 +350,79 @@ gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int 
   for (int m = 0; m < MT; ++m) rd[m] = rows[tile0 + (m < n_valid ? m : n_valid - 1)];
 
   const int n_chunks = (n_in + kc - 1) / kc;
+  const int n_groups = (min(kc, n_in) + GSTEP - 1) / GSTEP;   // of a full chunk; a short last chunk masks
   const int n_waves = gridDim.x * GEMV_WAVES, wave_global = blockIdx.x * GEMV_WAVES + wave;
-  const int rounds = (n_tasks + n_waves - 1) / n_waves;
+  const int rounds = (n_tasks + n_waves - 1) / n_waves;       // same for every wave: the chunk staging synchronises the workgroup
+  const int n_stages = rounds * n_chunks * n_groups;
   typename Epi::State st;
   epi.init(st);
 
-  // prime the pipeline: first stage of this wave's first task
-  WStage<U> nxt;
-  const WT *r0, *r1;
-  bool valid = wave_global < n_tasks;
-  epi.weight_rows(valid ? wave_global : 0, r0, r1);
-  issue_stage<WT>(nxt, r0, r1, 0, min(kc, n_in), lane, valid);
-
-  for (int round = 0; round < rounds; ++round) {
-    const int task = round * n_waves + wave_global;
-    const int task_n = task + n_waves;
-    const bool valid_n = round + 1 < rounds && task_n < n_tasks;
-    const WT *r0n, *r1n;
-    epi.weight_rows(valid_n ? task_n : 0, r0n, r1n);
-    float acc0[MT], acc1[MT];
-#pragma unroll
-    for (int m = 0; m < MT; ++m) acc0[m] = acc1[m] = 0.f;
-
-    for (int chunk = 0; chunk < n_chunks; ++chunk) {
-      const int k0 = chunk * kc, klen = min(kc, n_in - k0);
-      if (round == 0 || n_chunks > 1) {
-        __syncthreads();
-        pro.template stage<VEC, MT>(xs, kc, rd, tile0, n_valid, k0, klen, red);
-        __syncthreads();
+  // issue cursor: runs D stages ahead of the consumption and past the last stage (no task: dummy loads)
+  int ig = 0, ichunk = 0, itask = wave_global;
+  bool ivalid = itask < n_tasks;
+  const WT *ir0, *ir1;
+  epi.weight_rows(ivalid ? itask : 0, ir0, ir1);
+  auto issue = [&](WStage<U> &s) {
+    const int k0 = ichunk * kc;
+    issue_stage_nb<WT>(s, ir0 + k0, ir1 + k0, ig * GSTEP, min(kc, n_in - k0), lane, ivalid);
+    if (++ig == n_groups) {
+      ig = 0;
+      if (++ichunk == n_chunks) {
+        ichunk = 0;
+        itask += n_waves;
+        ivalid = itask < n_tasks;
+        epi.weight_rows(ivalid ? itask : 0, ir0, ir1);
       }
-      const int n_groups = (klen + GSTEP - 1) / GSTEP;
-      for (int g = 0; g < n_groups; ++g) {
-        const WStage<U> cur = nxt;
-        if (g + 1 < n_groups) {
-          issue_stage<WT>(nxt, r0 + k0, r1 + k0, (g + 1) * GSTEP, klen, lane, valid);
-        } else if (chunk + 1 < n_chunks) {
-          issue_stage<WT>(nxt, r0 + k0 + kc, r1 + k0 + kc, 0, min(kc, n_in - k0 - kc), lane, valid);
-        } else if (round + 1 < rounds) {
-          issue_stage<WT>(nxt, r0n, r1n, 0, min(kc, n_in), lane, valid_n);
+    }
+  };
+  WStage<U> ring[D];
+#pragma unroll
+  for (int j = 0; j < D; ++j) issue(ring[j]);
+
+  int g = 0, chunk = 0, task = wave_global;
+  bool valid = task < n_tasks;
+  float acc0[MT], acc1[MT];
+#pragma unroll
+  for (int m = 0; m < MT; ++m) acc0[m] = acc1[m] = 0.f;
+  for (int f0 = 0; f0 < n_stages; f0 += D) {
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+      if (f0 + j < n_stages) {
+        const int k0 = chunk * kc, klen = min(kc, n_in - k0);
+        if (g == 0 && (task == wave_global || n_chunks > 1)) {
+          __syncthreads();
+          pro.template stage<VEC, MT>(xs, kc, rd, tile0, n_valid, k0, klen, red);
+          __syncthreads();
         }
         if (valid) {
 #pragma unroll
           for (int u = 0; u < U; ++u) {
             const int kb = g * GSTEP + u * WSTEP;
-            if (kb < klen) fma_block<WT, MT>(cur.a[u], cur.b[u], xs, kc, kb, lane, acc0, acc1);
+            if (kb < klen) fma_block<WT, MT>(ring[j].a[u], ring[j].b[u], xs, kc, kb, lane, acc0, acc1);
+          }
+        }
+        if (++g == n_groups) {
+          g = 0;
+          if (++chunk == n_chunks) {   // the task is complete
+            chunk = 0;
+            if (valid) {
+              float y0 = 0.f, y1 = 0.f;
+              RowDesc mine = rd[0];
+#pragma unroll
+              for (int m = 0; m < MT; ++m) {
+                float s0 = wave_sum(acc0[m]), s1 = wave_sum(acc1[m]);
+                if (lane == m) { y0 = s0; y1 = s1; mine = rd[m]; }
+                acc0[m] = acc1[m] = 0.f;
+              }
+              if (lane < n_valid) epi.finish(task, tile0 + lane, mine, y0, y1, st);
+            }
+            task += n_waves;
+            valid = task < n_tasks;
           }
         }
       }
+      issue(ring[j]);
     }
-    if (valid) {
-      float y0 = 0.f, y1 = 0.f;
-      RowDesc mine = rd[0];
-#pragma unroll
-      for (int m = 0; m < MT; ++m) {
-        float s0 = wave_sum(acc0[m]), s1 = wave_sum(acc1[m]);
-        if (lane == m) { y0 = s0; y1 = s1; mine = rd[m]; }
-      }
-      if (lane < n_valid) epi.finish(task, tile0 + lane, mine, y0, y1, st);
-    }
-    valid = valid_n;
-    r0 = r0n;
-    r1 = r1n;
   }
   if (lane < n_valid) {
     RowDesc mine = rd[0];

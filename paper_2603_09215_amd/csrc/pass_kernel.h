@@ -7,9 +7,10 @@
 // single launch: one workgroup per CU stays resident, the five phases of a layer (q/k/v
 // projection, attention, output projection, gate/up, down) are separated by grid-wide barriers
 // built from device-scope atomics, and the activations that cross a barrier travel through
-// device-scope stores and loads, so no cache is flushed or invalidated between phases.  Weights do
-// not depend on activations: every wave issues the first loads of its next phase before it waits,
-// which keeps HBM busy across the barrier and the activation staging of the next phase.
+// device-scope stores, so no cache is flushed between phases.  Weights do not depend on
+// activations: every wave keeps a ring of PASS_D weight stages in flight and fills it with the
+// first stages of its next phase while it finishes the current one, which keeps HBM busy across
+// the barrier and the activation staging of the next phase.
 #pragma once
 #include "attention.h"
 #include "device_common.h"
@@ -21,10 +22,17 @@ constexpr int PASS_THREADS = 512;
 constexpr int PASS_WAVES = PASS_THREADS / 64;
 constexpr int PASS_U = 4;  // 16-byte loads per weight row and pipeline stage (2 waves per SIMD: deeper than the stand-alone kernel)
 typedef WStage<PASS_U> PStage;
+constexpr int PASS_D = 3;  // stages a wave keeps in flight (8 KB each with bf16 weights)
+struct PRing {
+  PStage s[PASS_D];
+};
+constexpr int PASS_MAX_ROUNDS = 16;  // rounds of tasks per wave and phase the result buffer holds
 constexpr unsigned PASS_SPIN_LIMIT = 1u << 22;  // polls before a barrier gives up (about a second)
 
 // Barrier state in device memory: one arrival word per XCD (workgroups are dealt to the 8 XCDs
 // round-robin), 128 bytes apart, and one global word counted by the last arrival of each XCD.
+// (Watching the eight XCD words directly, without the global word, was measured slower: 256
+// workgroups polling eight addresses delay the arrivals.)
 struct GridBarrier {
   unsigned *xcd_words;   // [8][32]
   unsigned *global_word;
@@ -35,7 +43,9 @@ struct GridBarrier {
 // Returns false (in every thread of the workgroup) if the wait gave up.
 __device__ __forceinline__ bool grid_sync(const GridBarrier &gb, unsigned &round, int *s_flag) {
   ++round;
-  wait_memory_ops();  // this wave's device-scope stores have completed
+  // Every device-scope store of the phase was issued by wave 0 (projection epilogues) or has been
+  // waited for by its own wave (attention); the other waves keep their prefetched weights in flight.
+  if (threadIdx.x < 64) wait_memory_ops();
   __syncthreads();
   if (threadIdx.x == 0) {
     const unsigned x = blockIdx.x & 7u;
@@ -47,8 +57,8 @@ __device__ __forceinline__ bool grid_sync(const GridBarrier &gb, unsigned &round
       __hip_atomic_fetch_add(gb.global_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     unsigned polls = 0;
     int ok = 1;
-    while (__hip_atomic_load(gb.global_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) <
-           round * groups) {
+    while ((int)(__hip_atomic_load(gb.global_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
+                 round * groups) < 0) {
       __builtin_amdgcn_s_sleep(1);
       if (++polls > PASS_SPIN_LIMIT) {
         atomicOr(gb.error_word, 1u);
@@ -71,15 +81,15 @@ __device__ __forceinline__ bool grid_sync(const GridBarrier &gb, unsigned &round
 // the barrier before this call dropped the stale cache lines, so ordinary 16-byte loads do
 template <int VEC, int MT>
 __device__ __forceinline__ void pass_stage_plain(float *xs, int kc, const float *src, int stride,
-                                                 int n_valid, int k0, int klen) {
+                                                 int n_valid, int k0, int klen, int tid) {
 #pragma unroll
   for (int m = 0; m < MT; ++m) {
     const int mm = m < n_valid ? m : n_valid - 1;
     const float *row = src + (size_t)mm * stride + k0;
-    for (int k = threadIdx.x * 4; k < klen; k += PASS_THREADS * 4)
+    for (int k = tid * 4; k < klen; k += PASS_THREADS * 4)
       *(float4 *)(xs + m * kc + lds_pos<VEC>(k)) = *(const float4 *)(row + k);
     const int end = (klen + 511) & ~511;
-    for (int k = klen + threadIdx.x * 4; k < end; k += PASS_THREADS * 4)
+    for (int k = klen + tid * 4; k < end; k += PASS_THREADS * 4)
       *(float4 *)(xs + m * kc + lds_pos<VEC>(k)) = make_float4(0.f, 0.f, 0.f, 0.f);
   }
 }
@@ -88,15 +98,19 @@ __device__ __forceinline__ void pass_stage_plain(float *xs, int kc, const float 
 template <int VEC, int MT>
 __device__ __forceinline__ void pass_stage_norm(float *xs, int kc, const float *hidden,
                                                 const RowDesc *rd, int n_valid, const float *gamma,
-                                                float eps, int d, float *red) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+                                                float eps, int d, float *red, int tid) {
+  const int lane = tid & 63, wave = tid >> 6;
   // raw row into LDS and the sum of squares on the way
 #pragma unroll
   for (int m = 0; m < MT; ++m) {
     const int mm = m < n_valid ? m : n_valid - 1;
-    const float *row = hidden + (size_t)rd[mm].x_slot * d;
+    int x_slot = rd[0].x_slot;
+#pragma unroll
+    for (int i = 1; i < MT; ++i)
+      if (i == mm) x_slot = rd[i].x_slot;
+    const float *row = hidden + (size_t)x_slot * d;
     float ss = 0.f;
-    for (int k = threadIdx.x * 4; k < d; k += PASS_THREADS * 4) {
+    for (int k = tid * 4; k < d; k += PASS_THREADS * 4) {
       const float4 v = *(const float4 *)(row + k);
       ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
       *(float4 *)(xs + m * kc + lds_pos<VEC>(k)) = v;
@@ -111,13 +125,13 @@ __device__ __forceinline__ void pass_stage_norm(float *xs, int kc, const float *
 #pragma unroll
     for (int w = 0; w < PASS_WAVES; ++w) tot += red[w * MT + m];
     const float inv = 1.0f / sqrtf(tot / (float)d + eps);
-    for (int k = threadIdx.x * 4; k < d; k += PASS_THREADS * 4) {   // same thread, same elements
+    for (int k = tid * 4; k < d; k += PASS_THREADS * 4) {   // same thread, same elements
       float4 *px = (float4 *)(xs + m * kc + lds_pos<VEC>(k));
       const float4 v = *px, g = *(const float4 *)(gamma + k);
       *px = make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w);
     }
     const int end = (d + 511) & ~511;
-    for (int k = d + threadIdx.x * 4; k < end; k += PASS_THREADS * 4)
+    for (int k = d + tid * 4; k < end; k += PASS_THREADS * 4)
       *(float4 *)(xs + m * kc + lds_pos<VEC>(k)) = make_float4(0.f, 0.f, 0.f, 0.f);
   }
 }
@@ -135,89 +149,217 @@ struct PhaseIn {
   float eps;
 };
 
-// Weight rows of the first stage a wave will need in a phase: primes `nxt`.
-template <typename WT, typename Epi>
-__device__ __forceinline__ void phase_prime(PStage &nxt, const Epi &epi, int n_in, int n_tasks, int kc,
-                                            int wave_global, int lane) {
-  const WT *r0, *r1;
-  const bool valid = wave_global < n_tasks;
-  epi.weight_rows(valid ? wave_global : 0, r0, r1);
-  issue_stage<WT>(nxt, r0, r1, 0, min(kc, n_in), lane, valid);
+// A wave walks the weights of a phase as a sequence of stages (PASS_U 16-byte loads per weight row
+// and lane each): for every round of tasks, for every LDS chunk of the input, for every group of
+// the chunk.  All waves of the grid have the same number of stages; the count is padded to a
+// multiple of the ring depth so that a phase always starts at ring slot 0.
+struct PhaseGeom {
+  int n_in, n_tasks, kc, n_chunks, n_groups, rounds, n_real, n_pad;
+};
+
+template <typename WT>
+__device__ __forceinline__ PhaseGeom make_geom(int n_in, int n_tasks, int kc, int n_waves) {
+  constexpr int GSTEP = PASS_U * 64 * Elem<WT>::VEC;
+  PhaseGeom g;
+  g.n_in = n_in; g.n_tasks = n_tasks; g.kc = kc;
+  g.n_chunks = (n_in + kc - 1) / kc;
+  g.n_groups = (min(kc, n_in) + GSTEP - 1) / GSTEP;
+  g.rounds = (n_tasks + n_waves - 1) / n_waves;
+  g.n_real = g.rounds * g.n_chunks * g.n_groups;
+  g.n_pad = (g.n_real + PASS_D - 1) / PASS_D * PASS_D;
+  return g;
 }
 
-// y = W x for the MT rows; `nxt` holds the already issued first stage on entry and the first
-// stage of the following phase on exit (prime_next issues it at the point where this phase's
-// pipeline would run dry).
-template <typename WT, int MT, typename Epi, typename PrimeNext>
-__device__ __forceinline__ void pass_gemv_phase(const PhaseIn &in, const Epi &epi, const RowDesc *rd,
-                                                int n_valid, int n_in, int n_tasks, int kc, float *xs,
-                                                float *red, PStage &nxt, const PrimeNext &prime_next,
-                                                int n_waves, int wave_global, int lane) {
+// Where a wave's stage sequence of a phase stands.  Past the last task the cursor has no valid
+// task and its loads turn into cache hits on the first bytes of a row.
+template <typename WT> struct StageCursor {
+  const WT *r0, *r1;
+  int g, chunk, task;
+  bool valid;
+};
+
+template <typename WT, typename Epi>
+__device__ __forceinline__ void cursor_begin(StageCursor<WT> &c, const Epi &epi, const PhaseGeom &pg,
+                                             int wave_global) {
+  c.g = 0; c.chunk = 0; c.task = wave_global;
+  c.valid = c.task < pg.n_tasks;
+  epi.weight_rows(c.valid ? c.task : 0, c.r0, c.r1);
+}
+
+template <typename WT, typename Epi>
+__device__ __forceinline__ void cursor_advance(StageCursor<WT> &c, const Epi &epi, const PhaseGeom &pg,
+                                               int n_waves) {
+  if (++c.g == pg.n_groups) {
+    c.g = 0;
+    if (++c.chunk == pg.n_chunks) {
+      c.chunk = 0;
+      c.task += n_waves;
+      c.valid = c.task < pg.n_tasks;
+      epi.weight_rows(c.valid ? c.task : 0, c.r0, c.r1);
+    }
+  }
+}
+
+// the loads of the cursor's stage, issued without a branch (see issue_stage_nb)
+template <typename WT>
+__device__ __forceinline__ void cursor_load(PStage &s, const StageCursor<WT> &c, const PhaseGeom &pg,
+                                            int lane, bool enable) {
+  constexpr int GSTEP = PASS_U * 64 * Elem<WT>::VEC;
+  const int k0 = c.chunk * pg.kc;
+  issue_stage_nb<WT>(s, c.r0 + k0, c.r1 + k0, c.g * GSTEP, min(pg.kc, pg.n_in - k0), lane,
+                     c.valid && enable);
+}
+
+// The first PASS_D stages of a phase, issued before the barrier in front of it.  Wave 0 holds back
+// all but one (its thread 0 polls the barrier, and a poll returns only after the loads the wave
+// issued before it); the phase issues the rest when it starts.
+template <typename WT, typename Epi>
+__device__ __forceinline__ void prime_ring(PRing &ring, const Epi &epi, const PhaseGeom &pg, bool enable,
+                                           int n_waves, int wave_global, int lane, int wave) {
+  StageCursor<WT> c;
+  cursor_begin(c, epi, pg, wave_global);
+#pragma unroll
+  for (int j = 0; j < PASS_D; ++j) {
+    cursor_load(ring.s[j], c, pg, lane, enable && (wave != 0 || j == 0));
+    cursor_advance(c, epi, pg, n_waves);
+  }
+}
+
+// y = W x for the MT rows.  On entry the ring holds stages 0..PASS_D-1 of this phase (wave 0: stage
+// 0); while the last PASS_D stages are consumed the slots are refilled with the first stages of
+// the following phase (prime_next), so they are in flight across the epilogue, the barrier and the
+// next activation staging.  Results go to LDS and wave 0 alone runs the epilogues after the last
+// stage: only that wave then has stores to wait for before the workgroup arrives at the barrier
+// (a wave cannot wait for its stores without also waiting for every load it has in flight).
+template <typename WT, int MT, typename Epi, typename EpiNext>
+__device__ __forceinline__ void pass_gemv_phase(const PhaseIn &in, const Epi &epi, const PhaseGeom &pg,
+                                                const EpiNext &epi_next, const PhaseGeom &pg_next,
+                                                bool prime_next, const RowDesc *rd, int n_valid,
+                                                float *xs, float *red, float *yres, PRing &ring,
+                                                int n_waves, int wave_global, int tid_in) {
   constexpr int VEC = Elem<WT>::VEC;
   constexpr int WSTEP = 64 * VEC;
   constexpr int GSTEP = PASS_U * WSTEP;
-  const int n_chunks = (n_in + kc - 1) / kc;
-  const int rounds = (n_tasks + n_waves - 1) / n_waves;
-  typename Epi::State st;
-  epi.init(st);
-  const WT *r0, *r1;
-  bool valid = wave_global < n_tasks;
-  epi.weight_rows(valid ? wave_global : 0, r0, r1);
+  // per-lane addresses are recomputed in every phase instead of being kept in registers across all
+  // of them: the ring needs the registers
+  int tid = tid_in;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, wave = tid >> 6;
 
-  for (int round = 0; round < rounds; ++round) {
-    const int task = round * n_waves + wave_global;
-    const int task_n = task + n_waves;
-    const bool valid_n = round + 1 < rounds && task_n < n_tasks;
-    const WT *r0n, *r1n;
-    epi.weight_rows(valid_n ? task_n : 0, r0n, r1n);
-    float acc0[MT], acc1[MT];
+  // wave 0 runs the epilogues; an epilogue that adds to what is in memory fetches the old values
+  // now (they were written at least one barrier ago), not at the end of the phase
+  const int per_wave = pg.rounds * MT;
+  float2 old = make_float2(0.f, 0.f);
+  if constexpr (EpiReadsOld<Epi>::value) {
+    if (wave == 0 && lane < PASS_WAVES * per_wave) {
+      const int w = lane / per_wave, rem = lane - w * per_wave;
+      const int rnd = rem / MT, m = rem - rnd * MT;
+      const int task = rnd * n_waves + blockIdx.x * PASS_WAVES + w;
+      if (task < pg.n_tasks && m < n_valid) {
+        RowDesc mine = rd[0];
 #pragma unroll
-    for (int m = 0; m < MT; ++m) acc0[m] = acc1[m] = 0.f;
+        for (int mm = 1; mm < MT; ++mm)
+          if (mm == m) mine = rd[mm];
+        old = epi.load_old(task, mine);
+      }
+    }
+  }
 
-    for (int chunk = 0; chunk < n_chunks; ++chunk) {
-      const int k0 = chunk * kc, klen = min(kc, n_in - k0);
-      if (round == 0 || n_chunks > 1) {
-        __syncthreads();
-        if (in.kind == PASS_IN_NORM)
-          pass_stage_norm<VEC, MT>(xs, kc, in.src, rd, n_valid, in.gamma, in.eps, n_in, red);
-        else
-          pass_stage_plain<VEC, MT>(xs, kc, in.src, in.stride, n_valid, k0, klen);
-        __syncthreads();
-      }
-      const int n_groups = (klen + GSTEP - 1) / GSTEP;
-      for (int g = 0; g < n_groups; ++g) {
-        const PStage cur = nxt;
-        if (g + 1 < n_groups) {
-          issue_stage<WT>(nxt, r0 + k0, r1 + k0, (g + 1) * GSTEP, klen, lane, valid);
-        } else if (chunk + 1 < n_chunks) {
-          issue_stage<WT>(nxt, r0 + k0 + kc, r1 + k0 + kc, 0, min(kc, n_in - k0 - kc), lane, valid);
-        } else if (round + 1 < rounds) {
-          issue_stage<WT>(nxt, r0n, r1n, 0, min(kc, n_in), lane, valid_n);
-        } else {
-          prime_next(nxt);
-        }
-        if (valid) {
+  StageCursor<WT> ic;
+  cursor_begin(ic, epi, pg, wave_global);
+  if (wave == 0) {   // the stages this wave held back before the barrier
+    StageCursor<WT> lc = ic;
 #pragma unroll
-          for (int u = 0; u < PASS_U; ++u) {
-            const int kb = g * GSTEP + u * WSTEP;
-            if (kb < klen) fma_block<WT, MT>(cur.a[u], cur.b[u], xs, kc, kb, lane, acc0, acc1);
-          }
-        }
-      }
+    for (int j = 1; j < PASS_D; ++j) {
+      cursor_advance(lc, epi, pg, n_waves);
+      cursor_load(ring.s[j], lc, pg, lane, true);
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < PASS_D; ++j) cursor_advance(ic, epi, pg, n_waves);   // ic: stage PASS_D
+
+  int g = 0, chunk = 0, round = 0;
+  bool valid = wave_global < pg.n_tasks;
+  float acc0[MT], acc1[MT];
+#pragma unroll
+  for (int m = 0; m < MT; ++m) acc0[m] = acc1[m] = 0.f;
+  auto consume = [&](const PStage &slot) {
+    const int k0 = chunk * pg.kc, klen = min(pg.kc, pg.n_in - k0);
+    if (g == 0 && (round == 0 || pg.n_chunks > 1)) {
+      __syncthreads();
+      if (in.kind == PASS_IN_NORM)
+        pass_stage_norm<VEC, MT>(xs, pg.kc, in.src, rd, n_valid, in.gamma, in.eps, pg.n_in, red, tid);
+      else
+        pass_stage_plain<VEC, MT>(xs, pg.kc, in.src, in.stride, n_valid, k0, klen, tid);
+      __syncthreads();
     }
     if (valid) {
-      float y0 = 0.f, y1 = 0.f;
-      RowDesc mine = rd[0];
 #pragma unroll
-      for (int m = 0; m < MT; ++m) {
-        float s0 = wave_sum(acc0[m]), s1 = wave_sum(acc1[m]);
-        if (lane == m) { y0 = s0; y1 = s1; mine = rd[m]; }
+      for (int u = 0; u < PASS_U; ++u) {
+        const int kb = g * GSTEP + u * WSTEP;
+        if (kb < klen) fma_block<WT, MT>(slot.a[u], slot.b[u], xs, pg.kc, kb, lane, acc0, acc1);
       }
-      if (lane < n_valid) epi.finish(task, lane, mine, y0, y1, st);
     }
-    valid = valid_n;
-    r0 = r0n;
-    r1 = r1n;
+    if (++g == pg.n_groups) {
+      g = 0;
+      if (++chunk == pg.n_chunks) {   // the task is complete
+        chunk = 0;
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+          const float s0 = wave_sum(acc0[m]), s1 = wave_sum(acc1[m]);
+          if (lane == 0) {
+            float *y = yres + ((wave * PASS_MAX_ROUNDS + round) * MT + m) * 2;
+            y[0] = s0; y[1] = s1;
+          }
+          acc0[m] = acc1[m] = 0.f;
+        }
+        ++round;
+        valid = round * n_waves + wave_global < pg.n_tasks;
+      }
+    }
+  };
+
+  int f0 = 0;
+  for (; f0 + PASS_D < pg.n_pad; f0 += PASS_D) {
+#pragma unroll
+    for (int j = 0; j < PASS_D; ++j) {
+      if (f0 + j < pg.n_real) consume(ring.s[j]);
+      cursor_load(ring.s[j], ic, pg, lane, true);
+      cursor_advance(ic, epi, pg, n_waves);
+    }
+  }
+  {   // the last PASS_D stages; their slots take the first stages of the following phase
+    StageCursor<WT> nc;
+    cursor_begin(nc, epi_next, pg_next, wave_global);
+#pragma unroll
+    for (int j = 0; j < PASS_D; ++j) {
+      if (f0 + j < pg.n_real) consume(ring.s[j]);
+      cursor_load(ring.s[j], nc, pg_next, lane, prime_next && (wave != 0 || j == 0));
+      cursor_advance(nc, epi_next, pg_next, n_waves);
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+    typename Epi::State st;
+    epi.init(st);
+    for (int i = lane; i < PASS_WAVES * per_wave; i += 64) {
+      const int w = i / per_wave, rem = i - w * per_wave;
+      const int rnd = rem / MT, m = rem - rnd * MT;
+      const int task = rnd * n_waves + blockIdx.x * PASS_WAVES + w;
+      if (task < pg.n_tasks && m < n_valid) {
+        RowDesc mine = rd[0];
+#pragma unroll
+        for (int mm = 1; mm < MT; ++mm)
+          if (mm == m) mine = rd[mm];
+        const float *y = yres + ((w * PASS_MAX_ROUNDS + rnd) * MT + m) * 2;
+        if constexpr (EpiReadsOld<Epi>::value) {
+          if (i == lane) epi.finish_old(task, mine, y[0], y[1], old);
+          else epi.finish(task, m, mine, y[0], y[1], st);
+        } else {
+          epi.finish(task, m, mine, y[0], y[1], st);
+        }
+      }
+    }
   }
 }
 
@@ -248,10 +390,6 @@ template <typename WT> struct PassParams {
                                                 // workgroup 0 before and after every barrier
 };
 
-struct NoPrime {
-  __device__ void operator()(PStage &) const {}
-};
-
 template <typename WT, int MT, int HD, int G>
 __global__ void __launch_bounds__(PASS_THREADS)
 spark_pass_k(PassParams<WT> p) {
@@ -259,8 +397,9 @@ spark_pass_k(PassParams<WT> p) {
   float *lds = (float *)smem4;
   __shared__ int s_flag;
   __shared__ float red[PASS_WAVES * MT];
+  __shared__ float yres[PASS_WAVES * PASS_MAX_ROUNDS * MT * 2];
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_waves = gridDim.x * PASS_WAVES, wave_global = blockIdx.x * PASS_WAVES + wave;
   const int n_valid = min(MT, p.m_rows);
   RowDesc rd[MT];
@@ -275,7 +414,10 @@ spark_pass_k(PassParams<WT> p) {
   mark();
 
   const int d = p.d, qw = p.nq * HD, kvw = p.nkv * HD, F = p.F;
-  const int t_qkv = (p.nq + 2 * p.nkv) * (HD / 2), t_o = d / 2, t_gu = F, t_dn = d / 2;
+  const PhaseGeom g_qkv = make_geom<WT>(d, (p.nq + 2 * p.nkv) * (HD / 2), p.kc_d, n_waves);
+  const PhaseGeom g_o = make_geom<WT>(qw, d / 2, p.kc_q, n_waves);
+  const PhaseGeom g_gu = make_geom<WT>(d, F, p.kc_d, n_waves);
+  const PhaseGeom g_dn = make_geom<WT>(F, d / 2, p.kc_f, n_waves);
 
   auto epi_qkv = [&](int l) {
     EpiQKV<WT, true> e;
@@ -296,18 +438,16 @@ spark_pass_k(PassParams<WT> p) {
     return EpiResidual<WT, true>{p.wd + (size_t)l * d * F, F, d, p.hidden, d};
   };
 
-  PStage nxt;
-  phase_prime<WT>(nxt, epi_qkv(p.l0), d, t_qkv, p.kc_d, wave_global, lane);
+  PRing ring;
+  prime_ring<WT>(ring, epi_qkv(p.l0), g_qkv, true, n_waves, wave_global, lane, wave);
 
   for (int l = p.l0; l < p.l1; ++l) {
-    // ---- q, k, v projections (+ rotary embedding, query store, KV-cache write)
+    // ---- q, k, v projections (+ rotary embedding, query store, KV-cache write); nothing is
+    // prefetched across the attention phase, which needs the registers
     {
-      const auto e = epi_qkv(l);
-      const auto en = epi_o(l);
       PhaseIn in{PASS_IN_NORM, p.hidden, d, p.attn_norm + (size_t)l * d, p.eps};
-      pass_gemv_phase<WT, MT>(in, e, rd, n_valid, d, t_qkv, p.kc_d, lds, red, nxt,
-                              [&](PStage &s) { phase_prime<WT>(s, en, qw, t_o, p.kc_q, wave_global, lane); },
-                              n_waves, wave_global, lane);
+      pass_gemv_phase<WT, MT>(in, epi_qkv(l), g_qkv, epi_o(l), g_o, false, rd, n_valid, lds, red,
+                              yres, ring, n_waves, wave_global, tid);
     }
     mark();
     if (!grid_sync(p.gb, round, &s_flag)) return;
@@ -331,18 +471,17 @@ spark_pass_k(PassParams<WT> p) {
         }
       }
     }
+    // the output projection's first weights fly during the barrier
+    prime_ring<WT>(ring, epi_o(l), g_o, true, n_waves, wave_global, lane, wave);
     mark();
     if (!grid_sync(p.gb, round, &s_flag)) return;
     mark();
 
     // ---- attention output projection, residual add
     {
-      const auto e = epi_o(l);
-      const auto en = epi_gu(l);
       PhaseIn in{PASS_IN_PLAIN, p.attn_out, qw, nullptr, 0.f};
-      pass_gemv_phase<WT, MT>(in, e, rd, n_valid, qw, t_o, p.kc_q, lds, red, nxt,
-                              [&](PStage &s) { phase_prime<WT>(s, en, d, t_gu, p.kc_d, wave_global, lane); },
-                              n_waves, wave_global, lane);
+      pass_gemv_phase<WT, MT>(in, epi_o(l), g_o, epi_gu(l), g_gu, true, rd, n_valid, lds, red, yres,
+                              ring, n_waves, wave_global, tid);
     }
     mark();
     if (!grid_sync(p.gb, round, &s_flag)) return;
@@ -350,12 +489,9 @@ spark_pass_k(PassParams<WT> p) {
 
     // ---- gate and up projections, SiLU(gate) * up
     {
-      const auto e = epi_gu(l);
-      const auto en = epi_dn(l);
       PhaseIn in{PASS_IN_NORM, p.hidden, d, p.mlp_norm + (size_t)l * d, p.eps};
-      pass_gemv_phase<WT, MT>(in, e, rd, n_valid, d, t_gu, p.kc_d, lds, red, nxt,
-                              [&](PStage &s) { phase_prime<WT>(s, en, F, t_dn, p.kc_f, wave_global, lane); },
-                              n_waves, wave_global, lane);
+      pass_gemv_phase<WT, MT>(in, epi_gu(l), g_gu, epi_dn(l), g_dn, true, rd, n_valid, lds, red, yres,
+                              ring, n_waves, wave_global, tid);
     }
     mark();
     if (!grid_sync(p.gb, round, &s_flag)) return;
@@ -363,19 +499,13 @@ spark_pass_k(PassParams<WT> p) {
 
     // ---- down projection, residual add
     {
-      const auto e = epi_dn(l);
       PhaseIn in{PASS_IN_PLAIN, p.act, F, nullptr, 0.f};
-      if (l + 1 < p.l1) {
-        const auto en = epi_qkv(l + 1);
-        pass_gemv_phase<WT, MT>(in, e, rd, n_valid, F, t_dn, p.kc_f, lds, red, nxt,
-                                [&](PStage &s) { phase_prime<WT>(s, en, d, t_qkv, p.kc_d, wave_global, lane); },
-                                n_waves, wave_global, lane);
-        mark();
-    if (!grid_sync(p.gb, round, &s_flag)) return;
-    mark();
-      } else {
-        pass_gemv_phase<WT, MT>(in, e, rd, n_valid, F, t_dn, p.kc_f, lds, red, nxt, NoPrime(), n_waves,
-                                wave_global, lane);
+      const bool more = l + 1 < p.l1;
+      pass_gemv_phase<WT, MT>(in, epi_dn(l), g_dn, epi_qkv(more ? l + 1 : l), g_qkv, more, rd, n_valid,
+                              lds, red, yres, ring, n_waves, wave_global, tid);
+      mark();
+      if (more) {
+        if (!grid_sync(p.gb, round, &s_flag)) return;
         mark();
       }
     }

@@ -332,6 +332,9 @@ template <typename WT> int launch_pass(spark_ctx *c, int l0, int l1, const RowDe
   PassParams<WT> p;
   p.kc_d = chunk(g.d_model); p.kc_q = chunk(qw); p.kc_f = chunk(g.d_ffn);
   if (p.kc_d < g.d_model) return fail(c, SPARK_EINVAL, "row of %d does not fit in LDS", g.d_model);
+  const int most_tasks = std::max(std::max((g.n_q_heads + 2 * g.n_kv_heads) * (hd / 2), g.d_model / 2), g.d_ffn);
+  if ((most_tasks + c->n_cu * PASS_WAVES - 1) / (c->n_cu * PASS_WAVES) > PASS_MAX_ROUNDS)
+    return fail(c, SPARK_EINVAL, "%d weight-row pairs are more than the pass kernel holds results for", most_tasks);
   size_t lds = sizeof(float) * mt * (size_t)std::max(p.kc_d, std::max(p.kc_q, p.kc_f));
   lds = std::max(lds, attn_bytes);
   p.d = g.d_model; p.nq = g.n_q_heads; p.nkv = g.n_kv_heads; p.hd = hd; p.F = g.d_ffn;
