@@ -14,6 +14,7 @@ library's stream, and the CPU oracle timed on the host cores as a reported basel
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -65,6 +66,10 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=1,
                     help="sequences decoded together (default 1: the headline workload); >1 gives "
                          "random prompt lengths in 256..2048 and mixed cycle offsets")
+    ap.add_argument("--exit-layer", type=int, default=None, help="override the workload's exit layer e")
+    ap.add_argument("--period", type=int, default=None, help="override the refresh period K (phase becomes K-1)")
+    ap.add_argument("--aligned", action="store_true",
+                    help="batch > 1: every sequence starts at cycle offset 0 (phase-aligned schedules)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (no collectives, no "
@@ -79,6 +84,10 @@ def main() -> int:
 
     w = wl.WORKLOADS[args.workload]
     shape, sched = w.shape, w.schedule
+    if args.exit_layer is not None:
+        sched = dataclasses.replace(sched, exit_layer=args.exit_layer)
+    if args.period is not None:
+        sched = dataclasses.replace(sched, period_k=args.period, phase=args.period - 1)
     prompt_len = args.prompt_len or w.prompt_len
     K, W = args.steps, args.warmup
     device = torch.device("cuda:0")
@@ -98,7 +107,7 @@ def main() -> int:
         plens = [prompt_len]
     sp = Spark(shape, sched, dev_w, max_batch=B, max_seq_len=max_seq, kv_page_tokens=64, device="cuda:0")
     cyc = sched.n_text + sched.n_speech
-    sids = [sp.seq_open(i % cyc if B > 1 else 0) for i in range(B)]
+    sids = [sp.seq_open(i % cyc if B > 1 and not args.aligned else 0) for i in range(B)]
     prompts = [wl.make_prompt(shape, n, seed=1 + i, ids=w.prompt_ids) for i, n in enumerate(plens)]
     prompt = prompts[0]
     sid = sids[0]
@@ -134,23 +143,28 @@ def main() -> int:
     value = K * B / elapsed
 
     # ---- per-class step times (one synchronous spark_step per token), same sequence continues
-    n_cls = min(args.profile_steps, 48)
+    # classes: early exit, full depth with m rows in the pass (m - 1 pending positions completed)
+    n_cls = min(2 * args.profile_steps, 96)
     cls = {}
     ctx_now = prompt_len - 1 + W + K
+    pending = sp.seq_state(sid)["pending"] if B == 1 else 0
     for i in range(n_cls if B == 1 else 0):
         torch.cuda.synchronize()
         a = time.perf_counter()
         t_, d_ = sp.step([sid])
         b = time.perf_counter()
-        st = sp.seq_state(sid)
-        key = "ee" if d_[0] != shape.n_layers else "full"
-        cls.setdefault(key, []).append((b - a) * 1e3)
+        if d_[0] != shape.n_layers:
+            cls.setdefault("ee", []).append((b - a) * 1e3)
+        else:
+            cls.setdefault("full", []).append((b - a) * 1e3)
+            cls.setdefault(f"full_m{pending + 1}", []).append((b - a) * 1e3)
+        pending = sp.seq_state(sid)["pending"]
     ee_b, full_b, w_layer = step_bytes(shape, sched, ctx_now + n_cls / 2)
     classes = {}
     for key, ts in cls.items():
         med = float(np.median(ts))
         by = ee_b if key == "ee" else full_b
-        classes[key] = {"ms": round(med, 4), "algorithmic_GB": round(by / 1e9, 3),
+        classes[key] = {"ms": round(med, 4), "steps": len(ts), "algorithmic_GB": round(by / 1e9, 3),
                         "GBps": round(by / med / 1e6, 1), "frac_of_hbm_peak": round(by / med / 1e6 / HBM_PEAK_GBS, 4)}
 
     # ---- roofline of the dominant kernel: gate/up projection, HIP events on the library's stream
@@ -204,6 +218,9 @@ def main() -> int:
                "sample": f"{args.cpu_steps} decode steps after a 4-token prompt, same shape, weights and schedule"}
         osq.close(); om.close()
 
+    if "ee" in classes and "full" in classes:
+        classes["ee_over_full"] = {"measured": round(classes["ee"]["ms"] / classes["full"]["ms"], 4),
+                                   "from_bytes": round(ee_b / full_b, 4)}
     line = {
         "metric": f"decode tokens/s per GPU (batch {B})", "value": round(value, 2), "unit": "tokens/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4),
@@ -214,7 +231,8 @@ def main() -> int:
                                f"V={shape.vocab}; prompt {prompt_len if B == 1 else '256..2048'}, decode {K}, batch {B}, "
                                f"{sched.n_text}:{sched.n_speech} text:speech, e={sched.exit_layer}, "
                                f"K={sched.period_k}, phase={sched.phase}, "
-                               f"scope={'chunk' if sched.scope == 0 else 'stream'}",
+                               f"scope={'chunk' if sched.scope == 0 else 'stream'}"
+                               f"{', cycle offsets aligned' if args.aligned and B > 1 else ''}",
                    "weights": "random N(0,0.02), fp32 accumulation", "kv_cache": "paged, 64 tokens/page",
                    "step_mix": mix, "mean_speech_depth": stats["mean_speech_depth"],
                    "speech_layer_saving_pct": round(stats["speech_layer_saving"], 2),

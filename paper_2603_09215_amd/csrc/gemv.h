@@ -37,16 +37,31 @@ struct ProPlain {
   const float *src;
   int stride;
   int indirect;  // 1: src row = x_slot of the row descriptor; 0: src row = pass row index
-  template <int VEC, int MT>
+  // BATCH: loads a thread issues before it uses any.  A loop that loads, waits and stores per
+  // iteration costs a memory round trip per iteration (18 of them for an MLP-width row); the
+  // batch costs registers, so only the launches that have them to spare ask for more than one.
+  template <int VEC, int MT, int BATCH>
   __device__ void stage(float *xs, int kc, const RowDesc *rd, int tile0, int n_valid, int k0,
                         int klen, float *red) const {
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
       int mm = m < n_valid ? m : n_valid - 1;
       const float *row = src + (size_t)(indirect ? rd[mm].x_slot : tile0 + mm) * stride + k0;
-      for (int k = threadIdx.x * 4; k < klen; k += GEMV_THREADS * 4)
-        *(float4 *)(xs + m * kc + lds_pos<VEC>(k)) = *(const float4 *)(row + k);
-      zero_tail<VEC>(xs + m * kc, klen);
+      float *xrow = xs + m * kc;
+      for (int kb = threadIdx.x * 4; kb < klen; kb += GEMV_THREADS * 4 * BATCH) {
+        float4 v[BATCH];
+#pragma unroll
+        for (int i = 0; i < BATCH; ++i) {
+          const int k = kb + i * GEMV_THREADS * 4;
+          v[i] = *(const float4 *)(row + (k < klen ? k : 0));
+        }
+#pragma unroll
+        for (int i = 0; i < BATCH; ++i) {
+          const int k = kb + i * GEMV_THREADS * 4;
+          if (k < klen) *(float4 *)(xrow + lds_pos<VEC>(k)) = v[i];
+        }
+      }
+      zero_tail<VEC>(xrow, klen);
     }
   }
 };
@@ -58,7 +73,7 @@ struct ProNorm {
   float eps;
   int d;
   int indirect;  // 1: row = x_slot of the row descriptor; 0: row = pass row index
-  template <int VEC, int MT>
+  template <int VEC, int MT, int BATCH>
   __device__ void stage(float *xs, int kc, const RowDesc *rd, int tile0, int n_valid, int k0,
                         int klen, float *red) const {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -254,7 +269,8 @@ __device__ __forceinline__ uint4 load_weights16(const void *p) {
 
 constexpr int GEMV_U = 2;  // 16-byte loads per weight row and pipeline stage (many waves per CU)
 constexpr int GEMV_U_DEEP = 4;  // same, for launches whose LDS use leaves only two workgroups per CU
-constexpr int GEMV_D = 2;  // stages in the register ring
+constexpr int GEMV_D = 2;  // stages in the register ring (measured: 2 beats 3 when many waves share a CU)
+constexpr int GEMV_D_DEEP = 2;  // same, for the launches with few waves per CU, which are latency-bound otherwise
 
 // One pipeline stage of weights: U consecutive 1 KiB segments of both rows of a task.
 template <int U> struct WStage {
@@ -391,7 +407,7 @@ gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int 
         const int k0 = chunk * kc, klen = min(kc, n_in - k0);
         if (g == 0 && (task == wave_global || n_chunks > 1)) {
           __syncthreads();
-          pro.template stage<VEC, MT>(xs, kc, rd, tile0, n_valid, k0, klen, red);
+          pro.template stage<VEC, MT, (U >= GEMV_U_DEEP ? 8 : 1)>(xs, kc, rd, tile0, n_valid, k0, klen, red);
           __syncthreads();
         }
         if (valid) {

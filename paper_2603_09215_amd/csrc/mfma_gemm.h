@@ -12,11 +12,19 @@
 // supplies 8 consecutive k of row (l % 32), k-block (l / 32); of the 16 results in a lane,
 // register r belongs to weight row (r/4)*8 + (l/32)*4 + r%4 and activation row l % 32.
 //
-// A workgroup owns 128 "tasks" (the same pairs of weight rows the vector kernel uses, so the
-// epilogues are shared: rotary pairs, gate/up pairs, adjacent rows), 32 per wave, and all rows of
-// one 32..128-row tile.  The k range may be split over blockIdx.y; partial sums then go to a
-// buffer and a second kernel finishes them, which is what fills 256 CUs when a matrix has only a
-// few thousand rows.
+// A workgroup of eight waves owns 256 "tasks" (the same pairs of weight rows the vector kernel
+// uses, so the epilogues are shared: rotary pairs, gate/up pairs, adjacent rows), 32 per wave, and
+// all rows of one tile of 32 or 64 activation rows; more rows are further tiles (grid.z), whose
+// workgroups read the same weights at about the same time.  The k range may be split over
+// blockIdx.y; partial sums then go to a buffer and a second kernel finishes them, which is what
+// fills 256 CUs when a matrix has only a few thousand rows.
+//
+// HBM delivers its bandwidth only to loads that cover whole 128-byte lines of a row in one
+// instruction (measured: 6.3 TB/s, against 2.6 TB/s when a wave instruction takes 32 bytes from
+// each of 32 rows, which is what loading straight into the A-operand layout does).  So a wave
+// loads its 64 weight rows eight lanes per row, 128 bytes per row and instruction, and turns the
+// result into the A-operand layout through a private piece of LDS: written as (row, 16-byte
+// segment), read back as (lane % 32 = row, lane / 32 = segment of the MFMA step).
 #pragma once
 #include "device_common.h"
 #include "gemv.h"
@@ -26,12 +34,21 @@ namespace spark {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 
-constexpr int MG_THREADS = 256;
-constexpr int MG_WAVES = 4;
-constexpr int MG_KC = 64;              // k per LDS chunk (4 MFMA steps of 16)
-constexpr int MG_ROWPAD = MG_KC + 8;   // bf16 per staged activation row (16-byte skew per row)
+constexpr int MG_THREADS = 512;
+constexpr int MG_WAVES = 8;
+constexpr int MG_KC = 64;              // k per chunk: one 128-byte line of a weight row, 4 MFMA steps
+constexpr int MG_KALIGN = MG_KC;       // input widths the MFMA path takes are multiples of this
+constexpr int MG_ROWPAD = MG_KC + 8;   // bf16 per staged row (a 16-byte skew per row keeps the operand reads conflict-free)
 constexpr int MG_TASKS_PER_WAVE = 32;
 constexpr int MG_TASKS_PER_BLOCK = MG_WAVES * MG_TASKS_PER_WAVE;
+constexpr int MG_MAX_MTILES = 2;       // activation rows per workgroup: 32 or 64
+// weight chunks a wave has in registers, on their way from HBM
+constexpr int MG_W_DEPTH = 2;
+// dynamic LDS of mfma_rows_k: per wave 64 padded weight rows of one chunk; two buffers of three
+// parts of 32*MTILES padded activation rows
+constexpr size_t mg_lds_bytes(int mtiles) {
+  return sizeof(bf16_t) * (MG_WAVES * 64 * MG_ROWPAD + 2 * 3 * 32 * mtiles * MG_ROWPAD);
+}
 
 // ------------------------------------------------------------------ activation preparation
 
@@ -80,26 +97,58 @@ prep_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ src, int
 
 // ------------------------------------------------------------------ the contraction
 
-// grid.x: blocks of 128 tasks; grid.y: k splits; grid.z: tiles of 32*MTILES activation rows.
+// grid.x: blocks of 256 tasks; grid.y: k splits; grid.z: tiles of 32*MTILES activation rows.
 // SPLIT: write partial sums part[split][task][2][m_pad] instead of running the epilogue.
+//
+// The loop over 64-wide chunks of k is software-pipelined.  Weights: a wave has MG_W_DEPTH chunks
+// of its 64 rows on their way in registers; the oldest is written to the wave's LDS piece, read
+// back as A operands and its registers are reloaded with the chunk MG_W_DEPTH ahead (LDS
+// operations of one wave execute in order, so the piece needs no barrier).  Activations: two LDS
+// buffers shared by the workgroup; while the MFMAs read one, the next chunk (loaded into
+// registers one iteration earlier) is written to the other and the chunk after that is requested:
+// one workgroup barrier per chunk and no load whose latency is exposed.  All loads are
+// unconditional (rows, tasks and chunks past the end are clamped to valid addresses and their
+// products skipped or discarded), which lets the compiler wait for exactly the loads a step needs;
+// loads return in issue order, so inside an iteration the activation loads are issued before the
+// weight loads and the order of the steps is pinned.
 template <int MTILES, typename Epi, bool SPLIT>
 __global__ void __launch_bounds__(MG_THREADS)
 mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t *__restrict__ xs,
             size_t part_stride, int n_in, int n_tasks, int chunks_per_split,
             float *__restrict__ part, int m_pad) {
+  static_assert(MTILES <= MG_MAX_MTILES, "accumulators and LDS are sized for 64 rows");
   constexpr int MROWS = 32 * MTILES;
-  __shared__ __attribute__((aligned(16))) bf16_t s_x[3][MROWS * MG_ROWPAD];
+  constexpr int WD = MG_W_DEPTH;
+  constexpr int XPOS = MROWS * (MG_KC / 8);                  // 16-byte vectors of one part of a chunk
+  constexpr int XV = (XPOS + MG_THREADS - 1) / MG_THREADS;   // of them per thread
+  constexpr int PART_ELEMS = MROWS * MG_ROWPAD;
+  constexpr int WI = 8;                                      // load instructions per chunk: 8 rows x 128 bytes each
+  extern __shared__ uint4 mg_smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  bf16_t *s_w = (bf16_t *)mg_smem + wave * 64 * MG_ROWPAD;             // this wave's [64][MG_ROWPAD]
+  bf16_t *s_x = (bf16_t *)mg_smem + MG_WAVES * 64 * MG_ROWPAD;         // [2][3][MROWS * MG_ROWPAD]
   const int row0 = blockIdx.z * MROWS;
   const int task0 = blockIdx.x * MG_TASKS_PER_BLOCK + wave * MG_TASKS_PER_WAVE;
-  const int my_task = task0 + (lane & 31);
-  const int n_chunks = (n_in + MG_KC - 1) / MG_KC;
+  const int n_chunks = n_in / MG_KC;
   const int c_begin = blockIdx.y * chunks_per_split;
   const int c_end = min(n_chunks, c_begin + chunks_per_split);
+  if (c_begin >= c_end) return;
 
-  const bf16_t *r0, *r1;
-  epi.weight_rows(my_task < n_tasks ? my_task : 0, r0, r1);
-  const int koff = (lane >> 5) * 8;   // this lane's k-block inside an MFMA step
+  // Load instruction i covers the wave's rows 8i..8i+7 (rows 0..31: first weight row of tasks
+  // task0.., rows 32..63: their second weight row); this lane takes segment lane % 8 of row
+  // 8i + lane / 8.
+  const bf16_t *wrow[WI];
+#pragma unroll
+  for (int i = 0; i < WI; ++i) {
+    const int q = 8 * i + (lane >> 3);
+    const int task = task0 + (q & 31);
+    const bf16_t *a, *b;
+    epi.weight_rows(task < n_tasks ? task : 0, a, b);
+    wrow[i] = (q < 32 ? a : b) + (lane & 7) * 8;
+  }
+  const int w_dst = (lane >> 3) * MG_ROWPAD + (lane & 7) * 8;          // + 8 i rows
+  const int koff = (lane >> 5) * 8;                                    // this lane's k-block inside an MFMA step
+  const int a_off = (lane & 31) * MG_ROWPAD + koff;                    // + 32 rows for the second tile, + 16 s
 
   f32x16_t acc0[MTILES], acc1[MTILES];
 #pragma unroll
@@ -107,59 +156,112 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc0[c][r] = acc1[c][r] = 0.f;
 
-  // weights of one chunk: 4 MFMA steps x 2 tiles, 16 bytes each; n_in is a multiple of 8, a
-  // chunk's tail beyond n_in reads as zero
-  uint4 wa[MG_KC / 16], wb[MG_KC / 16];
-  auto load_chunk = [&](int chunk) {
+  u32x4_t wr[WD][WI];   // (a native vector type: arrays of it are kept in registers)
+  // this thread's vectors of the three parts of a chunk's activations: xr[i][p]
+  int x_src[XV], x_dst[XV];
 #pragma unroll
-    for (int s = 0; s < MG_KC / 16; ++s) {
-      const int k = chunk * MG_KC + s * 16 + koff;
-      if (k < n_in) {
-        wa[s] = load_weights16(r0 + k);
-        wb[s] = load_weights16(r1 + k);
-      } else {
-        wa[s] = make_uint4(0, 0, 0, 0);
-        wb[s] = make_uint4(0, 0, 0, 0);
-      }
-    }
-  };
+  for (int i = 0; i < XV; ++i) {
+    const int pos = min((int)threadIdx.x + i * MG_THREADS, XPOS - 1);
+    const int m = pos / (MG_KC / 8), kv = (pos - m * (MG_KC / 8)) * 8;
+    x_src[i] = min(row0 + m, m_rows - 1) * n_in + kv;        // rows past the end repeat the last one
+    x_dst[i] = m * MG_ROWPAD + kv;
+  }
+  u32x4_t xr[XV][3];
 
-  if (c_begin < c_end) load_chunk(c_begin);
-  for (int chunk = c_begin; chunk < c_end; ++chunk) {
-    uint4 ca[MG_KC / 16], cb[MG_KC / 16];
+  {
+    const int k_ = c_begin * MG_KC;
 #pragma unroll
-    for (int s = 0; s < MG_KC / 16; ++s) { ca[s] = wa[s]; cb[s] = wb[s]; }
-    __syncthreads();   // the previous chunk's activations are no longer read
-    // stage activations of this chunk: MROWS rows x 64 k, hi and lo, 16 bytes per thread and step
-    for (int v = threadIdx.x; v < MROWS * (MG_KC / 8); v += MG_THREADS) {
-      const int m = v / (MG_KC / 8), kv = (v - m * (MG_KC / 8)) * 8;
-      const int k = chunk * MG_KC + kv;
-      uint4 x3[3] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
-      if (row0 + m < m_rows && k < n_in) {
-        const bf16_t *src = xs + (size_t)(row0 + m) * n_in + k;
+    for (int i = 0; i < XV; ++i) {
 #pragma unroll
-        for (int p = 0; p < 3; ++p) x3[p] = *(const uint4 *)(src + p * part_stride);
-      }
-#pragma unroll
-      for (int p = 0; p < 3; ++p) *(uint4 *)(s_x[p] + m * MG_ROWPAD + kv) = x3[p];
+      for (int p = 0; p < 3; ++p) xr[i][p] = *(const u32x4_t *)(xs + p * part_stride + x_src[i] + k_);
     }
-    if (chunk + 1 < c_end) load_chunk(chunk + 1);   // next chunk's weights fly during the MFMAs
-    __syncthreads();
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  {
 #pragma unroll
-    for (int s = 0; s < MG_KC / 16; ++s) {
-      const bf16x8_t a0 = __builtin_bit_cast(bf16x8_t, ca[s]);
-      const bf16x8_t a1 = __builtin_bit_cast(bf16x8_t, cb[s]);
+    for (int i = 0; i < XV; ++i) {
+      if ((int)threadIdx.x + i * MG_THREADS < XPOS) {
 #pragma unroll
-      for (int c = 0; c < MTILES; ++c) {
-        const int off = (c * 32 + (lane & 31)) * MG_ROWPAD + s * 16 + koff;
-        // smallest part first, so that the large terms are added last
+        for (int p = 0; p < 3; ++p) *(u32x4_t *)(s_x + p * PART_ELEMS + x_dst[i]) = xr[i][p];
+      }
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  {
+    const int k_ = min(c_begin + 1, c_end - 1) * MG_KC;
 #pragma unroll
-        for (int p = 2; p >= 0; --p) {
-          const bf16x8_t b = __builtin_bit_cast(bf16x8_t, *(const uint4 *)(s_x[p] + off));
-          acc0[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc0[c], 0, 0, 0);
-          acc1[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc1[c], 0, 0, 0);
+    for (int i = 0; i < XV; ++i) {
+#pragma unroll
+      for (int p = 0; p < 3; ++p) xr[i][p] = *(const u32x4_t *)(xs + p * part_stride + x_src[i] + k_);
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int j = 0; j < WD; ++j) {
+    const int k_ = min(c_begin + j, c_end - 1) * MG_KC;
+#pragma unroll
+    for (int i = 0; i < WI; ++i) wr[j][i] = __builtin_nontemporal_load((const u32x4_t *)(wrow[i] + k_));
+  }
+  __syncthreads();
+
+  for (int base = c_begin; base < c_end; base += WD) {
+#pragma unroll
+    for (int j = 0; j < WD; ++j) {
+      const int chunk = base + j;
+      const int buf = j & 1;   // WD is even, so a chunk's buffer is its slot's parity
+      // weights of this chunk into the wave's LDS piece (the MFMAs of the previous chunk have
+      // issued their reads of it: one wave's LDS operations stay in order)
+#pragma unroll
+      for (int i = 0; i < WI; ++i) *(u32x4_t *)(s_w + 8 * i * MG_ROWPAD + w_dst) = wr[j][i];
+      __builtin_amdgcn_sched_barrier(0);
+      // activations of chunk + 1, requested one iteration ago, into the other buffer
+      {
+#pragma unroll
+        for (int i = 0; i < XV; ++i) {
+          if ((int)threadIdx.x + i * MG_THREADS < XPOS) {
+#pragma unroll
+            for (int p = 0; p < 3; ++p)
+              *(u32x4_t *)(s_x + ((buf ^ 1) * 3 + p) * PART_ELEMS + x_dst[i]) = xr[i][p];
+          }
         }
       }
+      __builtin_amdgcn_sched_barrier(0);
+      {
+        const int k_ = min(chunk + 2, c_end - 1) * MG_KC;
+#pragma unroll
+        for (int i = 0; i < XV; ++i) {
+#pragma unroll
+          for (int p = 0; p < 3; ++p) xr[i][p] = *(const u32x4_t *)(xs + p * part_stride + x_src[i] + k_);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      {
+        const int k_ = min(chunk + WD, c_end - 1) * MG_KC;
+#pragma unroll
+        for (int i = 0; i < WI; ++i) wr[j][i] = __builtin_nontemporal_load((const u32x4_t *)(wrow[i] + k_));
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (chunk < c_end) {
+        const bf16_t *xb = s_x + buf * 3 * PART_ELEMS + a_off;
+#pragma unroll
+        for (int s = 0; s < MG_KC / 16; ++s) {
+          const bf16x8_t a0 = __builtin_bit_cast(bf16x8_t, *(const u32x4_t *)(s_w + a_off + s * 16));
+          const bf16x8_t a1 = __builtin_bit_cast(bf16x8_t, *(const u32x4_t *)(s_w + 32 * MG_ROWPAD + a_off + s * 16));
+          // smallest part first, so that the large terms are added last; consecutive MFMAs go to
+          // different accumulators
+#pragma unroll
+          for (int p = 2; p >= 0; --p) {
+#pragma unroll
+            for (int c = 0; c < MTILES; ++c) {
+              const bf16x8_t b = __builtin_bit_cast(
+                  bf16x8_t, *(const u32x4_t *)(xb + p * PART_ELEMS + c * 32 * MG_ROWPAD + s * 16));
+              acc0[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc0[c], 0, 0, 0);
+              acc1[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc1[c], 0, 0, 0);
+            }
+          }
+        }
+      }
+      __syncthreads();
     }
   }
 

@@ -9,6 +9,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <type_traits>
+#include <map>
 #include <vector>
 
 #include "../../include/spark.h"
@@ -69,6 +70,7 @@ struct spark_ctx {
   bool use_mfma = true;        // SPARK_NO_MFMA=1 keeps every row count on the vector kernels
   unsigned bar_round = 0;      // grid barriers passed since the barrier words were zeroed
   unsigned long long *timeline_dev = nullptr;  // debugging aid, see SPARK_PASS_TIMELINE
+  std::map<std::pair<const void *, size_t>, int> occ_cache;  // workgroups per CU of a (kernel, LDS bytes)
   // profiling of one kernel class
   int prof_class = -1;
   std::vector<hipEvent_t> prof_ev;
@@ -235,16 +237,22 @@ int launch_gemv(spark_ctx *c, const Pro &pro, const Epi &epi, const RowDesc *row
   // much LDS per workgroup means few waves per CU: those launches keep more loads in flight
   const bool deep = lds > 40960;
   switch (mt) {
-    case 1: kern = deep ? gemv_rows_k<WT, 1, Pro, Epi, GEMV_U_DEEP> : gemv_rows_k<WT, 1, Pro, Epi>; break;
-    case 2: kern = deep ? gemv_rows_k<WT, 2, Pro, Epi, GEMV_U_DEEP> : gemv_rows_k<WT, 2, Pro, Epi>; break;
-    case 3: kern = deep ? gemv_rows_k<WT, 3, Pro, Epi, GEMV_U_DEEP> : gemv_rows_k<WT, 3, Pro, Epi>; break;
-    default: kern = deep ? gemv_rows_k<WT, 4, Pro, Epi, GEMV_U_DEEP> : gemv_rows_k<WT, 4, Pro, Epi>; break;
+    case 1: kern = deep ? gemv_rows_k<WT, 1, Pro, Epi, GEMV_U_DEEP, GEMV_D_DEEP> : gemv_rows_k<WT, 1, Pro, Epi>; break;
+    case 2: kern = deep ? gemv_rows_k<WT, 2, Pro, Epi, GEMV_U_DEEP, GEMV_D_DEEP> : gemv_rows_k<WT, 2, Pro, Epi>; break;
+    case 3: kern = deep ? gemv_rows_k<WT, 3, Pro, Epi, GEMV_U_DEEP, GEMV_D_DEEP> : gemv_rows_k<WT, 3, Pro, Epi>; break;
+    default: kern = deep ? gemv_rows_k<WT, 4, Pro, Epi, GEMV_U_DEEP, GEMV_D_DEEP> : gemv_rows_k<WT, 4, Pro, Epi>; break;
   }
-  if (lds > 65536)
-    HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 81920));
-  int occ = 0;
-  HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, GEMV_THREADS, lds));
-  occ = std::max(1, std::min(occ, 4));
+  // attribute and occupancy are asked for once per (kernel, LDS size), not on every launch
+  const auto key = std::make_pair((const void *)kern, lds);
+  auto found = c->occ_cache.find(key);
+  if (found == c->occ_cache.end()) {
+    if (lds > 65536)
+      HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 81920));
+    int o = 0;
+    HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, kern, GEMV_THREADS, lds));
+    found = c->occ_cache.emplace(key, std::max(1, std::min(o, 4))).first;
+  }
+  const int occ = found->second;
   int bx = std::min((n_tasks + GEMV_WAVES - 1) / GEMV_WAVES, c->n_cu * occ);
   dim3 grid(bx, (m_rows + mt - 1) / mt), block(GEMV_THREADS);
   int rc = prof_begin(c, kclass);
@@ -395,19 +403,48 @@ int launch_prep(spark_ctx *c, const RowDesc *rows, int m, const float *src, int 
   return SPARK_OK;
 }
 
+template <int MTILES, typename Epi, bool SPLIT>
+int mfma_occupancy(spark_ctx *c) {
+  auto kern = mfma_rows_k<MTILES, Epi, SPLIT>;
+  const auto key = std::make_pair((const void *)kern, mg_lds_bytes(MTILES));
+  auto found = c->occ_cache.find(key);
+  if (found == c->occ_cache.end()) {
+    if (mg_lds_bytes(MTILES) > 65536)
+      HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)mg_lds_bytes(MTILES)));
+    int o = 0;
+    HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, kern, MG_THREADS, mg_lds_bytes(MTILES)));
+    if (o < 1) return fail(c, SPARK_EHIP, "the MFMA kernel for %d rows does not fit on a CU", 32 * MTILES);
+    found = c->occ_cache.emplace(key, o).first;
+  }
+  return found->second;
+}
+
 template <int MTILES, typename Epi>
 int launch_mfma_tiles(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, int n_in, int n_tasks,
                       bool may_split) {
+  if (n_in % MG_KALIGN) return fail(c, SPARK_EINVAL, "MFMA path needs an input width that is a multiple of %d", MG_KALIGN);
   const int mrows = 32 * MTILES;
   const int z = (m + mrows - 1) / mrows;
   const int bx = (n_tasks + MG_TASKS_PER_BLOCK - 1) / MG_TASKS_PER_BLOCK;
-  const int n_chunks = (n_in + MG_KC - 1) / MG_KC;
+  const int n_chunks = n_in / MG_KC;
   const int m_pad = (int)align_up(m, 32);
+  // resident workgroups on the chip: the k range is split until one round of them has work
+  int occ = mfma_occupancy<MTILES, Epi, true>(c);
+  if (occ < 0) return occ;
+  // k splits: the count that keeps most of the chip busy over whole rounds of resident
+  // workgroups, with at least eight chunks each (the pipeline needs a few to fill)
   int split = 1;
   if (may_split) {
-    split = std::max(1, std::min(n_chunks, (2 * c->n_cu) / std::max(1, bx * z)));
+    const int slots = occ * c->n_cu, tiles = bx * z;
     const size_t per_split = sizeof(float) * (size_t)n_tasks * 2 * m_pad;
-    split = (int)std::min<size_t>(split, std::max<size_t>(1, MFMA_PARTIAL_BYTES / per_split));
+    const int max_split = (int)std::min<size_t>(std::max(1, n_chunks / 8), std::max<size_t>(1, MFMA_PARTIAL_BYTES / per_split));
+    double best = 0.0;
+    for (int s = 1; s <= std::min(max_split, 32); ++s) {
+      const int blocks = tiles * s, rounds = (blocks + slots - 1) / slots;
+      const double util = (double)blocks / ((double)rounds * slots);
+      if (util > best + 0.02) { best = util; split = s; }
+    }
   }
   const int cps = (n_chunks + split - 1) / split;
   split = (n_chunks + cps - 1) / cps;
@@ -416,13 +453,15 @@ int launch_mfma_tiles(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, 
   float *part = at<float>(c, c->lo.mfma_part);
   dim3 grid(bx, split, z);
   if (split > 1) {
-    mfma_rows_k<MTILES, Epi, true><<<grid, MG_THREADS, 0, c->stream>>>(epi, rows, m, xs, xst, n_in,
-                                                                       n_tasks, cps, part, m_pad);
+    mfma_rows_k<MTILES, Epi, true><<<grid, MG_THREADS, mg_lds_bytes(MTILES), c->stream>>>(
+        epi, rows, m, xs, xst, n_in, n_tasks, cps, part, m_pad);
     const int total = n_tasks * m_pad;
     mfma_finish_k<Epi><<<(total + 255) / 256, 256, 0, c->stream>>>(epi, rows, m, n_tasks, split, part, m_pad);
   } else {
-    mfma_rows_k<MTILES, Epi, false><<<grid, MG_THREADS, 0, c->stream>>>(epi, rows, m, xs, xst, n_in,
-                                                                        n_tasks, cps, part, m_pad);
+    occ = mfma_occupancy<MTILES, Epi, false>(c);
+    if (occ < 0) return occ;
+    mfma_rows_k<MTILES, Epi, false><<<grid, MG_THREADS, mg_lds_bytes(MTILES), c->stream>>>(
+        epi, rows, m, xs, xst, n_in, n_tasks, cps, part, m_pad);
   }
   HIP_TRY(c, hipGetLastError());
   return SPARK_OK;
@@ -435,8 +474,7 @@ int launch_mfma(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, int n_
   int rc = prof_begin(c, kclass);
   if (rc) return rc;
   if (m <= 32) rc = launch_mfma_tiles<1>(c, epi, rows, m, n_in, n_tasks, may_split);
-  else if (m <= 64) rc = launch_mfma_tiles<2>(c, epi, rows, m, n_in, n_tasks, may_split);
-  else rc = launch_mfma_tiles<4>(c, epi, rows, m, n_in, n_tasks, may_split);
+  else rc = launch_mfma_tiles<2>(c, epi, rows, m, n_in, n_tasks, may_split);   // tiles of 64 rows
   if (rc) return rc;
   return prof_end(c, kclass);
 }
@@ -820,7 +858,9 @@ int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_p
   const char *pass = getenv("SPARK_PASS_KERNEL");
   c->use_pass_kernel = pass && pass[0] == '1';
   const char *no_mfma = getenv("SPARK_NO_MFMA");
-  c->use_mfma = !(no_mfma && no_mfma[0] == '1');
+  // the MFMA kernels walk the input in chunks of 32 or 64; other widths stay on the vector kernel
+  c->use_mfma = !(no_mfma && no_mfma[0] == '1') && cfg->d_model % MG_KALIGN == 0 &&
+                (cfg->n_q_heads * cfg->head_dim) % MG_KALIGN == 0 && cfg->d_ffn % MG_KALIGN == 0;
   const char *tl = getenv("SPARK_PASS_TIMELINE");   // debugging aid: per-phase times on stderr
   if (tl && tl[0] == '1' &&
       hipMalloc((void **)&c->timeline_dev, sizeof(unsigned long long) * 16384) != hipSuccess)
