@@ -37,7 +37,6 @@ typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 constexpr int MG_THREADS = 512;
 constexpr int MG_WAVES = 8;
 constexpr int MG_KC = 64;              // k per chunk: one 128-byte line of a weight row, 4 MFMA steps
-constexpr int MG_KALIGN = MG_KC;       // input widths the MFMA path takes are multiples of this
 constexpr int MG_ROWPAD = MG_KC + 8;   // bf16 per staged row (a 16-byte skew per row keeps the operand reads conflict-free)
 constexpr int MG_TASKS_PER_WAVE = 32;
 constexpr int MG_TASKS_PER_BLOCK = MG_WAVES * MG_TASKS_PER_WAVE;
@@ -53,10 +52,11 @@ constexpr size_t mg_lds_bytes(int mtiles) {
 // ------------------------------------------------------------------ activation preparation
 
 // xs[part][r][k] = the three bf16 parts of x_r[k], x_r = src row (plain) or
-// RMSNorm(hidden[x_slot_r]; gamma); part p starts at xs + p * part_stride
+// RMSNorm(hidden[x_slot_r]; gamma); rows are n_pad apart (n rounded up to the chunk of the
+// contraction) and zero beyond n; part p starts at xs + p * part_stride
 __global__ void __launch_bounds__(256)
 prep_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ src, int stride, int indirect,
-            const float *__restrict__ gamma, float eps, int n, bf16_t *__restrict__ xs,
+            const float *__restrict__ gamma, float eps, int n, int n_pad, bf16_t *__restrict__ xs,
             size_t part_stride) {
   __shared__ float red[4];
   const int r = blockIdx.x;
@@ -88,10 +88,16 @@ prep_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ src, int
       mid[e] = f32_to_bf16(rem);
       l[e] = f32_to_bf16(rem - bf16_to_f32(mid[e]));   // exact remainder has at most 8 bits left
     }
-    bf16_t *dst = xs + (size_t)r * n + k;
+    bf16_t *dst = xs + (size_t)r * n_pad + k;
     *(uint2 *)dst = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
     *(uint2 *)(dst + part_stride) = make_uint2(mid[0] | ((uint32_t)mid[1] << 16), mid[2] | ((uint32_t)mid[3] << 16));
     *(uint2 *)(dst + 2 * part_stride) = make_uint2(l[0] | ((uint32_t)l[1] << 16), l[2] | ((uint32_t)l[3] << 16));
+  }
+  for (int k = n + threadIdx.x * 4; k < n_pad; k += 1024) {
+    bf16_t *dst = xs + (size_t)r * n_pad + k;
+    *(uint2 *)dst = make_uint2(0, 0);
+    *(uint2 *)(dst + part_stride) = make_uint2(0, 0);
+    *(uint2 *)(dst + 2 * part_stride) = make_uint2(0, 0);
   }
 }
 
@@ -129,7 +135,8 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
   bf16_t *s_x = (bf16_t *)mg_smem + MG_WAVES * 64 * MG_ROWPAD;         // [2][3][MROWS * MG_ROWPAD]
   const int row0 = blockIdx.z * MROWS;
   const int task0 = blockIdx.x * MG_TASKS_PER_BLOCK + wave * MG_TASKS_PER_WAVE;
-  const int n_chunks = n_in / MG_KC;
+  const int n_chunks = (n_in + MG_KC - 1) / MG_KC;   // the last one may be short: activations are zero-padded
+  const int x_stride = n_chunks * MG_KC;
   const int c_begin = blockIdx.y * chunks_per_split;
   const int c_end = min(n_chunks, c_begin + chunks_per_split);
   if (c_begin >= c_end) return;
@@ -144,8 +151,9 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
     const int task = task0 + (q & 31);
     const bf16_t *a, *b;
     epi.weight_rows(task < n_tasks ? task : 0, a, b);
-    wrow[i] = (q < 32 ? a : b) + (lane & 7) * 8;
+    wrow[i] = q < 32 ? a : b;
   }
+  const int w_seg = (lane & 7) * 8;   // this lane's k inside a chunk
   const int w_dst = (lane >> 3) * MG_ROWPAD + (lane & 7) * 8;          // + 8 i rows
   const int koff = (lane >> 5) * 8;                                    // this lane's k-block inside an MFMA step
   const int a_off = (lane & 31) * MG_ROWPAD + koff;                    // + 32 rows for the second tile, + 16 s
@@ -163,7 +171,7 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
   for (int i = 0; i < XV; ++i) {
     const int pos = min((int)threadIdx.x + i * MG_THREADS, XPOS - 1);
     const int m = pos / (MG_KC / 8), kv = (pos - m * (MG_KC / 8)) * 8;
-    x_src[i] = min(row0 + m, m_rows - 1) * n_in + kv;        // rows past the end repeat the last one
+    x_src[i] = min(row0 + m, m_rows - 1) * x_stride + kv;    // rows past the end repeat the last one
     x_dst[i] = m * MG_ROWPAD + kv;
   }
   u32x4_t xr[XV][3];
@@ -198,7 +206,8 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int j = 0; j < WD; ++j) {
-    const int k_ = min(c_begin + j, c_end - 1) * MG_KC;
+    int k_ = min(c_begin + j, c_end - 1) * MG_KC + w_seg;
+    k_ = k_ < n_in ? k_ : 0;   // past the row's end: any finite weights, they meet zero activations
 #pragma unroll
     for (int i = 0; i < WI; ++i) wr[j][i] = __builtin_nontemporal_load((const u32x4_t *)(wrow[i] + k_));
   }
@@ -236,7 +245,8 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
       }
       __builtin_amdgcn_sched_barrier(0);
       {
-        const int k_ = min(chunk + WD, c_end - 1) * MG_KC;
+        int k_ = min(chunk + WD, c_end - 1) * MG_KC + w_seg;
+        k_ = k_ < n_in ? k_ : 0;
 #pragma unroll
         for (int i = 0; i < WI; ++i) wr[j][i] = __builtin_nontemporal_load((const u32x4_t *)(wrow[i] + k_));
       }

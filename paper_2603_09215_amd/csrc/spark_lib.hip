@@ -174,7 +174,7 @@ void layout(const spark_config &c, const Derived &d, Layout &l) {
   l.act = take(sizeof(float) * (size_t)d.max_rows * c.d_ffn);
   l.lens_u = take(sizeof(float) * (size_t)c.max_batch * c.d_model);
   {
-    const size_t widest = std::max((size_t)c.d_ffn, std::max((size_t)c.d_model, qw));
+    const size_t widest = align_up(std::max((size_t)c.d_ffn, std::max((size_t)c.d_model, qw)), 64);
     l.xsplit = take(sizeof(bf16_t) * 3 * (size_t)d.max_rows * widest);
     l.mfma_part = take(c.dtype == SPARK_DTYPE_BF16 ? MFMA_PARTIAL_BYTES : 256);
   }
@@ -391,14 +391,14 @@ constexpr int MFMA_MIN_ROWS = 16;
 // the three bf16 parts of the split activations are stored one after the other
 size_t xsplit_stride(spark_ctx *c) {
   const spark_config &g = c->cfg;
-  const size_t widest = std::max((size_t)g.d_ffn, std::max((size_t)g.d_model, (size_t)g.n_q_heads * g.head_dim));
+  const size_t widest = align_up(std::max((size_t)g.d_ffn, std::max((size_t)g.d_model, (size_t)g.n_q_heads * g.head_dim)), 64);
   return (size_t)c->dv.max_rows * widest;
 }
 
 int launch_prep(spark_ctx *c, const RowDesc *rows, int m, const float *src, int stride, int indirect,
                 const float *gamma, int n) {
   prep_rows_k<<<m, 256, 0, c->stream>>>(rows, src, stride, indirect, gamma, c->cfg.rms_eps, n,
-                                        at<bf16_t>(c, c->lo.xsplit), xsplit_stride(c));
+                                        (int)align_up(n, MG_KC), at<bf16_t>(c, c->lo.xsplit), xsplit_stride(c));
   HIP_TRY(c, hipGetLastError());
   return SPARK_OK;
 }
@@ -423,11 +423,11 @@ int mfma_occupancy(spark_ctx *c) {
 template <int MTILES, typename Epi>
 int launch_mfma_tiles(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, int n_in, int n_tasks,
                       bool may_split) {
-  if (n_in % MG_KALIGN) return fail(c, SPARK_EINVAL, "MFMA path needs an input width that is a multiple of %d", MG_KALIGN);
+  if (n_in % 8) return fail(c, SPARK_EINVAL, "MFMA path needs an input width that is a multiple of 8, not %d", n_in);
   const int mrows = 32 * MTILES;
   const int z = (m + mrows - 1) / mrows;
   const int bx = (n_tasks + MG_TASKS_PER_BLOCK - 1) / MG_TASKS_PER_BLOCK;
-  const int n_chunks = n_in / MG_KC;
+  const int n_chunks = (n_in + MG_KC - 1) / MG_KC;
   const int m_pad = (int)align_up(m, 32);
   // resident workgroups on the chip: the k range is split until one round of them has work
   int occ = mfma_occupancy<MTILES, Epi, true>(c);
@@ -858,9 +858,9 @@ int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_p
   const char *pass = getenv("SPARK_PASS_KERNEL");
   c->use_pass_kernel = pass && pass[0] == '1';
   const char *no_mfma = getenv("SPARK_NO_MFMA");
-  // the MFMA kernels walk the input in chunks of 32 or 64; other widths stay on the vector kernel
-  c->use_mfma = !(no_mfma && no_mfma[0] == '1') && cfg->d_model % MG_KALIGN == 0 &&
-                (cfg->n_q_heads * cfg->head_dim) % MG_KALIGN == 0 && cfg->d_ffn % MG_KALIGN == 0;
+  // the MFMA kernels load 16-byte vectors of 8 weights; other widths stay on the vector kernel
+  c->use_mfma = !(no_mfma && no_mfma[0] == '1') && cfg->d_model % 8 == 0 &&
+                (cfg->n_q_heads * cfg->head_dim) % 8 == 0 && cfg->d_ffn % 8 == 0;
   const char *tl = getenv("SPARK_PASS_TIMELINE");   // debugging aid: per-phase times on stderr
   if (tl && tl[0] == '1' &&
       hipMalloc((void **)&c->timeline_dev, sizeof(unsigned long long) * 16384) != hipSuccess)
