@@ -299,23 +299,31 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
   }
 }
 
-// sums the k-split partials and runs the epilogue: one thread per (task, activation row)
+// sums the k-split partials and runs the epilogue: one thread per activation row and group of
+// `tasks_per_thread` consecutive tasks (more than one where the epilogue keeps a running state,
+// like the arg-max of the vocabulary heads, that is worth reducing before it goes to memory)
 template <typename Epi>
 __global__ void __launch_bounds__(256)
 mfma_finish_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, int n_tasks, int n_split,
-              const float *__restrict__ part, int m_pad) {
+              const float *__restrict__ part, int m_pad, int tasks_per_thread) {
   const int idx = blockIdx.x * 256 + threadIdx.x;
-  const int task = idx / m_pad, m = idx - task * m_pad;
-  if (task >= n_tasks || m >= m_rows) return;
-  float y0 = 0.f, y1 = 0.f;
-  for (int s = 0; s < n_split; ++s) {
-    const float *p = part + (((size_t)s * n_tasks + task) * 2) * m_pad + m;
-    y0 += p[0];
-    y1 += p[m_pad];
-  }
+  const int group = idx / m_pad, m = idx - group * m_pad;
+  const int t_begin = group * tasks_per_thread;
+  if (t_begin >= n_tasks || m >= m_rows) return;
+  const int t_end = min(n_tasks, t_begin + tasks_per_thread);
   typename Epi::State st;
   epi.init(st);
-  epi.finish(task, m, rows[m], y0, y1, st);
+  const RowDesc rd = rows[m];
+  for (int task = t_begin; task < t_end; ++task) {
+    float y0 = 0.f, y1 = 0.f;
+    for (int s = 0; s < n_split; ++s) {
+      const float *p = part + (((size_t)s * n_tasks + task) * 2) * m_pad + m;
+      y0 += p[0];
+      y1 += p[m_pad];
+    }
+    epi.finish(task, m, rd, y0, y1, st);
+  }
+  epi.end(m, rd, st);
 }
 
 }  // namespace spark

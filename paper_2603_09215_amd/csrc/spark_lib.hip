@@ -386,7 +386,7 @@ template <typename WT> int launch_pass(spark_ctx *c, int l0, int l1, const RowDe
 
 // ------------------------------------------------------------------ MFMA path (16..128+ rows, bf16)
 
-constexpr int MFMA_MIN_ROWS = 16;
+constexpr int MFMA_MIN_ROWS = 5;   // up to four rows share one pass of the vector kernel; more would take several
 
 // the three bf16 parts of the split activations are stored one after the other
 size_t xsplit_stride(spark_ctx *c) {
@@ -402,6 +402,10 @@ int launch_prep(spark_ctx *c, const RowDesc *rows, int m, const float *src, int 
   HIP_TRY(c, hipGetLastError());
   return SPARK_OK;
 }
+
+// tasks one thread of the finishing kernel takes: the vocabulary heads reduce their arg-max over 64
+template <typename Epi> int finish_tasks_per_thread(const Epi &) { return 1; }
+template <typename WT> int finish_tasks_per_thread(const EpiVocab<WT> &) { return 64; }
 
 template <int MTILES, typename Epi, bool SPLIT>
 int mfma_occupancy(spark_ctx *c) {
@@ -455,8 +459,9 @@ int launch_mfma_tiles(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, 
   if (split > 1) {
     mfma_rows_k<MTILES, Epi, true><<<grid, MG_THREADS, mg_lds_bytes(MTILES), c->stream>>>(
         epi, rows, m, xs, xst, n_in, n_tasks, cps, part, m_pad);
-    const int total = n_tasks * m_pad;
-    mfma_finish_k<Epi><<<(total + 255) / 256, 256, 0, c->stream>>>(epi, rows, m, n_tasks, split, part, m_pad);
+    const int tpt = finish_tasks_per_thread(epi);
+    const int total = ((n_tasks + tpt - 1) / tpt) * m_pad;
+    mfma_finish_k<Epi><<<(total + 255) / 256, 256, 0, c->stream>>>(epi, rows, m, n_tasks, split, part, m_pad, tpt);
   } else {
     occ = mfma_occupancy<MTILES, Epi, false>(c);
     if (occ < 0) return occ;
@@ -578,7 +583,7 @@ template <typename WT> int run_lens_head(spark_ctx *c, const RowDesc *rows, int 
                         at<unsigned long long>(c, c->lo.best)};
     rc = prof_begin(c, SPARK_KC_LENS);
     if (rc) return rc;
-    if ((rc = launch_mfma_tiles<1>(c, ev, rows, m, d, (V + 1) / 2, false))) return rc;
+    if ((rc = launch_mfma_tiles<1>(c, ev, rows, m, d, (V + 1) / 2, true))) return rc;
     return prof_end(c, SPARK_KC_LENS);
   }
   ProPlain ph{hidden, d, 1};
@@ -601,7 +606,7 @@ template <typename WT> int run_final_head(spark_ctx *c, const RowDesc *rows, int
                         at<unsigned long long>(c, c->lo.best)};
     rc = prof_begin(c, SPARK_KC_HEAD);
     if (rc) return rc;
-    if ((rc = launch_mfma_tiles<1>(c, ev, rows, m, d, (V + 1) / 2, false))) return rc;
+    if ((rc = launch_mfma_tiles<1>(c, ev, rows, m, d, (V + 1) / 2, true))) return rc;
     return prof_end(c, SPARK_KC_HEAD);
   }
   ProNorm pn{at<float>(c, c->lo.hidden), c->w.final_norm, g.rms_eps, d, 1};
