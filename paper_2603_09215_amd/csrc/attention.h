@@ -39,13 +39,15 @@ template <int HD, int G, int NT> constexpr int attn_lds_floats() {
 
 // partial layout: part[((r*nq + hq)*n_splits + split)*(HD+4)] = {o[HD], m, l, pad, pad}
 //
-// One task, executed by all NT threads of a workgroup.  DS: the queries were written, and the
-// output will be read, by other workgroups of the same kernel (device-scope accesses).
+// One task, executed by all NT threads of a workgroup: query heads hq0 .. hq0 + g_count - 1
+// (g_count <= G, all sharing KV head hk) of row r over one slice; `cnt` counts the slices of this
+// (row, group of heads) that are done.  DS: the queries were written, and the output will be
+// read, by other workgroups of the same kernel (device-scope accesses).
 template <typename KT, int HD, int G, int NT, bool DS>
-__device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int split,
-                                          const float *__restrict__ qbuf, const KVView &kv,
+__device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int hq0, int g_count,
+                                          int split, const float *__restrict__ qbuf, const KVView &kv,
                                           int layer, int nq, int n_splits, float scale,
-                                          float *__restrict__ part, int *__restrict__ arrivals,
+                                          float *__restrict__ part, int *__restrict__ cnt,
                                           float *__restrict__ out, float *lds) {
   constexpr int VEC = Elem<KT>::VEC;
   constexpr int LPT = HD / VEC;                   // lanes per token
@@ -63,7 +65,6 @@ __device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int 
   const int n_tok = min(ATTN_SLICE, ctx - t0);
   const int tid = threadIdx.x % NT, lane = tid & 63, wave = tid >> 6;
   const int tg = tid / LPT, dc = tid % LPT;       // token slot in an iteration, 16-byte chunk of the row
-  const int hq0 = hk * G;
 
   // issue every K and V load of the slice
   uint4 kraw[ITERS], vraw[ITERS];
@@ -85,7 +86,7 @@ __device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int 
   float q[G][VEC];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    const float *qp = qbuf + (size_t)r * nq * HD + (hq0 + g) * HD + dc * VEC;
+    const float *qp = qbuf + (size_t)r * nq * HD + (hq0 + min(g, g_count - 1)) * HD + dc * VEC;
 #pragma unroll
     for (int e = 0; e < VEC; e += 2) {
       float2 v = load2_maybe_ds<DS>(qp + e);
@@ -112,7 +113,7 @@ __device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int 
   task_sync<NT>();
 
   // softmax statistics of the slice, one wave per query head at a time (lane = token)
-  for (int g = wave; g < G; g += WAVES) {
+  for (int g = wave; g < g_count; g += WAVES) {
     float s = sc[g * ATTN_SLICE + lane];
     float mx = wave_max(s);
     float p = lane < n_tok ? expf(s - mx) : 0.f;
@@ -152,14 +153,14 @@ __device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int 
       if (lane < LPT) ored[(wave * G + g) * HD + dc * VEC + e] = a;
     }
   task_sync<NT>();
-  for (int i = tid; i < G * HD; i += NT) {
+  for (int i = tid; i < g_count * HD; i += NT) {
     const int g = i / HD, c = i - g * HD;
     float o = 0.f;
 #pragma unroll
     for (int w = 0; w < WAVES; ++w) o += ored[(w * G + g) * HD + c];
     store_device_scope(part + ((size_t)(r * nq + hq0 + g) * n_splits + split) * PS + c, o);
   }
-  if (tid < G * 2) {
+  if (tid < g_count * 2) {
     const int g = tid >> 1, w = tid & 1;
     store_device_scope(part + ((size_t)(r * nq + hq0 + g) * n_splits + split) * PS + HD + w,
                        ml[g * 2 + w]);
@@ -173,7 +174,6 @@ __device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int 
   wait_memory_ops();                                      // partials written before the count
   task_sync<NT>();
   if (tid == 0) {
-    int *cnt = arrivals + r * (nq / G) + hk;
     const int prev = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     *s_last = prev == used - 1;
     if (*s_last) {
@@ -186,7 +186,7 @@ __device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int 
 
   // normalised slice weights wn[g][s] = exp(m_s - M) / sum_s' exp(m_s' - M) l_s', lane = slice
   float *wn = ored;                                       // [G][used], used <= 256
-  for (int g = wave; g < G; g += WAVES) {
+  for (int g = wave; g < g_count; g += WAVES) {
     const float *p = part + (size_t)(r * nq + hq0 + g) * n_splits * PS;
     float M = -INFINITY;
     for (int s0 = 0; s0 < used; s0 += 64) {
@@ -209,7 +209,7 @@ __device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int 
       if (s0 + lane < used) wn[g * used + s0 + lane] *= inv;
   }
   task_sync<NT>();
-  for (int i = tid; i < G * (HD / 4); i += NT) {
+  for (int i = tid; i < g_count * (HD / 4); i += NT) {
     const int g = i / (HD / 4), c = (i - g * (HD / 4)) * 4;
     const float *p = part + (size_t)(r * nq + hq0 + g) * n_splits * PS + c;
     float4 acc4 = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -226,18 +226,22 @@ __device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int 
   if (DS) wait_memory_ops();   // the caller's next barrier arrival does not wait for these stores
 }
 
-// stand-alone launch: one workgroup per (slice, kv head, row)
+// stand-alone launch: one workgroup per (slice, group of G query heads, row).  A KV head's `group`
+// query heads are dealt to ceil(group / G) workgroups: with few rows and few KV heads that is what
+// gives the chip enough workgroups, at the price of reading the slice's K and V once per group.
 template <typename KT, int HD, int G>
 __global__ void __launch_bounds__(ATTN_THREADS)
 attn_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbuf, KVView kv,
-            int layer, int nq, int n_splits, float scale, float *__restrict__ part,
+            int layer, int nq, int group, int n_splits, float scale, float *__restrict__ part,
             int *__restrict__ arrivals, float *__restrict__ out) {
   __shared__ float lds[attn_lds_floats<HD, G, ATTN_THREADS>()];
-  const int split = blockIdx.x, hk = blockIdx.y, r = blockIdx.z;
+  const int n_groups = (group + G - 1) / G;
+  const int split = blockIdx.x, hk = blockIdx.y / n_groups, gi = blockIdx.y - hk * n_groups, r = blockIdx.z;
   const RowDesc rd = rows[r];
   if (split * ATTN_SLICE > rd.pos) return;        // slice beyond the row's context
-  attn_task<KT, HD, G, ATTN_THREADS, false>(rd, r, hk, split, qbuf, kv, layer, nq, n_splits, scale,
-                                            part, arrivals, out, lds);
+  attn_task<KT, HD, G, ATTN_THREADS, false>(rd, r, hk, hk * group + gi * G, min(G, group - gi * G), split,
+                                            qbuf, kv, layer, nq, n_splits, scale, part,
+                                            arrivals + r * gridDim.y + blockIdx.y, out, lds);
 }
 
 }  // namespace spark

@@ -465,9 +465,9 @@ spark_pass_k(PassParams<WT> p) {
           if (m == r) mine = rd[m];
         if (split * ATTN_SLICE <= mine.pos) {
           __syncthreads();  // LDS of the previous task is free
-          attn_task<WT, HD, G, PASS_THREADS, true>(mine, r, hk, split, p.qbuf, p.kv, l, p.nq,
-                                                   p.n_splits, p.scale, p.part, p.arrivals,
-                                                   p.attn_out, lds);
+          attn_task<WT, HD, G, PASS_THREADS, true>(mine, r, hk, hk * G, G, split, p.qbuf, p.kv, l,
+                                                   p.nq, p.n_splits, p.scale, p.part,
+                                                   p.arrivals + r * p.nkv + hk, p.attn_out, lds);
         }
       }
     }

@@ -165,7 +165,7 @@ void layout(const spark_config &c, const Derived &d, Layout &l) {
   l.out_tokens = take(sizeof(int) * (size_t)MAX_STEPS_PER_CALL * c.max_batch);
   l.out_depth = take(sizeof(int) * (size_t)MAX_STEPS_PER_CALL * c.max_batch);
   l.best = take(sizeof(unsigned long long) * c.max_batch);
-  l.arrivals = take(sizeof(int) * (size_t)d.max_rows * c.n_kv_heads);
+  l.arrivals = take(sizeof(int) * (size_t)d.max_rows * c.n_q_heads);   // per (row, group of query heads)
   l.barrier = take(sizeof(unsigned) * (8 * 32 + 32));
   l.hidden = take(sizeof(float) * ((size_t)c.max_batch * d.rmax + PREFILL_CHUNK) * c.d_model);
   l.qbuf = take(sizeof(float) * d.max_rows * qw);
@@ -274,23 +274,32 @@ KVView kv_view(spark_ctx *c) {
   return v;
 }
 
-template <typename WT, int HD, int G>
+constexpr int ATTN_SPLIT_HEADS_MAX_ROWS = 4;
+
+// GT query heads per workgroup
+template <typename WT, int HD, int GT>
 void launch_attention_g(spark_ctx *c, const RowDesc *rows, int m, int layer) {
   const spark_config &g = c->cfg;
   const Derived &d = c->dv;
   float *part = at<float>(c, c->lo.part);
-  attn_rows_k<WT, HD, G><<<dim3(d.n_splits, g.n_kv_heads, m), ATTN_THREADS, 0, c->stream>>>(
-      rows, at<float>(c, c->lo.qbuf), kv_view(c), layer, g.n_q_heads, d.n_splits,
+  const int n_groups = (d.group + GT - 1) / GT;
+  attn_rows_k<WT, HD, GT><<<dim3(d.n_splits, g.n_kv_heads * n_groups, m), ATTN_THREADS, 0, c->stream>>>(
+      rows, at<float>(c, c->lo.qbuf), kv_view(c), layer, g.n_q_heads, d.group, d.n_splits,
       1.0f / sqrtf((float)HD), part, at<int>(c, c->lo.arrivals), at<float>(c, c->lo.attn_out));
 }
 
 template <typename WT, int HD>
 void launch_attention_hd(spark_ctx *c, const RowDesc *rows, int m, int layer) {
-  switch (c->dv.group) {
+  // a handful of rows: four query heads per workgroup, so that even two KV heads make enough
+  // workgroups; many rows: all heads of a KV head together, K and V are read once
+  const int group = c->dv.group;
+  const int gt = (m <= ATTN_SPLIT_HEADS_MAX_ROWS && group > 4) ? 4 : group;
+  switch (gt) {
     case 1: launch_attention_g<WT, HD, 1>(c, rows, m, layer); break;
     case 2: launch_attention_g<WT, HD, 2>(c, rows, m, layer); break;
+    case 3: launch_attention_g<WT, HD, 4>(c, rows, m, layer); break;
     case 4: launch_attention_g<WT, HD, 4>(c, rows, m, layer); break;
-    case 7: launch_attention_g<WT, HD, 7>(c, rows, m, layer); break;
+    case 5: case 6: case 7: launch_attention_g<WT, HD, 7>(c, rows, m, layer); break;
     case 8: launch_attention_g<WT, HD, 8>(c, rows, m, layer); break;
     default: launch_attention_g<WT, HD, 16>(c, rows, m, layer); break;
   }
