@@ -31,10 +31,9 @@ template <int NT> __device__ __forceinline__ void task_sync() {
   }
 }
 
-// floats of LDS one task needs with NT threads
-// (the merge reuses the cross-wave buffer for [G][slices] weights, slices <= 256)
+// floats of LDS one task needs with NT threads: scores, softmax statistics, per-wave sums
 template <int HD, int G, int NT> constexpr int attn_lds_floats() {
-  return G * ATTN_SLICE + G * 2 + ((NT / 64) * HD > 256 ? (NT / 64) * G * HD : G * 256) + 4;
+  return G * ATTN_SLICE + G * 2 + (NT / 64) * G * HD + 4;
 }
 
 // partial layout: part[((r*nq + hq)*n_splits + split)*(HD+4)] = {o[HD], m, l, pad, pad}
@@ -184,44 +183,38 @@ __device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int 
   task_sync<NT>();
   if (!*s_last) return;
 
-  // normalised slice weights wn[g][s] = exp(m_s - M) / sum_s' exp(m_s' - M) l_s', lane = slice
-  float *wn = ored;                                       // [G][used], used <= 256
-  for (int g = wave; g < g_count; g += WAVES) {
-    const float *p = part + (size_t)(r * nq + hq0 + g) * n_splits * PS;
-    float M = -INFINITY;
-    for (int s0 = 0; s0 < used; s0 += 64) {
-      const int sl = s0 + lane;
-      M = fmaxf(M, sl < used ? p[(size_t)sl * PS + HD] : -INFINITY);
-    }
-    M = wave_max(M);
-    float den = 0.f;
-    for (int s0 = 0; s0 < used; s0 += 64) {
-      const int sl = s0 + lane;
-      if (sl < used) {
-        const float w = expf(p[(size_t)sl * PS + HD] - M);
-        wn[g * used + sl] = w;
-        den += w * p[(size_t)sl * PS + HD + 1];
-      }
-    }
-    den = wave_sum(den);
-    const float inv = 1.0f / den;
-    for (int s0 = 0; s0 < used; s0 += 64)
-      if (s0 + lane < used) wn[g * used + s0 + lane] *= inv;
-  }
-  task_sync<NT>();
+  // every thread merges four output elements of one head over all slices in one pass (running
+  // maximum, rescaled sums), eight slices' loads in flight at a time
   for (int i = tid; i < g_count * (HD / 4); i += NT) {
     const int g = i / (HD / 4), c = (i - g * (HD / 4)) * 4;
-    const float *p = part + (size_t)(r * nq + hq0 + g) * n_splits * PS + c;
+    const float *p = part + (size_t)(r * nq + hq0 + g) * n_splits * PS;
+    float M = -INFINITY, L = 0.f;
     float4 acc4 = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll 4
-    for (int sl = 0; sl < used; ++sl) {
-      const float4 o = *(const float4 *)(p + (size_t)sl * PS);
-      const float w = wn[g * used + sl];
-      acc4.x += w * o.x; acc4.y += w * o.y; acc4.z += w * o.z; acc4.w += w * o.w;
+    for (int s0 = 0; s0 < used; s0 += 8) {
+      float2 ml8[8];
+      float4 o8[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int sl = min(s0 + k, used - 1);
+        ml8[k] = *(const float2 *)(p + (size_t)sl * PS + HD);
+        o8[k] = *(const float4 *)(p + (size_t)sl * PS + c);
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        if (s0 + k < used) {
+          const float Mn = fmaxf(M, ml8[k].x);
+          const float so = expf(M - Mn), sn = expf(ml8[k].x - Mn);   // exp(-inf) = 0 on the first slice
+          acc4.x = acc4.x * so + o8[k].x * sn; acc4.y = acc4.y * so + o8[k].y * sn;
+          acc4.z = acc4.z * so + o8[k].z * sn; acc4.w = acc4.w * so + o8[k].w * sn;
+          L = L * so + ml8[k].y * sn;
+          M = Mn;
+        }
+      }
     }
+    const float inv = 1.0f / L;
     float *dst = out + (size_t)r * nq * HD + (hq0 + g) * HD + c;
-    store2_maybe_ds<DS>(dst, make_float2(acc4.x, acc4.y));
-    store2_maybe_ds<DS>(dst + 2, make_float2(acc4.z, acc4.w));
+    store2_maybe_ds<DS>(dst, make_float2(acc4.x * inv, acc4.y * inv));
+    store2_maybe_ds<DS>(dst + 2, make_float2(acc4.z * inv, acc4.w * inv));
   }
   if (DS) wait_memory_ops();   // the caller's next barrier arrival does not wait for these stores
 }

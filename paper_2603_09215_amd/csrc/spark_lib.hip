@@ -70,6 +70,7 @@ struct spark_ctx {
   bool use_mfma = true;        // SPARK_NO_MFMA=1 keeps every row count on the vector kernels
   unsigned bar_round = 0;      // grid barriers passed since the barrier words were zeroed
   unsigned long long *timeline_dev = nullptr;  // debugging aid, see SPARK_PASS_TIMELINE
+  int attn_splits_now = 0;   // context slices the rows of the passes being enqueued can reach (0: unknown, launch all)
   std::map<std::pair<const void *, size_t>, int> occ_cache;  // workgroups per CU of a (kernel, LDS bytes)
   // profiling of one kernel class
   int prof_class = -1;
@@ -283,7 +284,8 @@ void launch_attention_g(spark_ctx *c, const RowDesc *rows, int m, int layer) {
   const Derived &d = c->dv;
   float *part = at<float>(c, c->lo.part);
   const int n_groups = (d.group + GT - 1) / GT;
-  attn_rows_k<WT, HD, GT><<<dim3(d.n_splits, g.n_kv_heads * n_groups, m), ATTN_THREADS, 0, c->stream>>>(
+  const int splits = c->attn_splits_now > 0 ? std::min(d.n_splits, c->attn_splits_now) : d.n_splits;
+  attn_rows_k<WT, HD, GT><<<dim3(splits, g.n_kv_heads * n_groups, m), ATTN_THREADS, 0, c->stream>>>(
       rows, at<float>(c, c->lo.qbuf), kv_view(c), layer, g.n_q_heads, d.group, d.n_splits,
       1.0f / sqrtf((float)HD), part, at<int>(c, c->lo.arrivals), at<float>(c, c->lo.attn_out));
 }
@@ -293,7 +295,7 @@ void launch_attention_hd(spark_ctx *c, const RowDesc *rows, int m, int layer) {
   // a handful of rows: four query heads per workgroup, so that even two KV heads make enough
   // workgroups; many rows: all heads of a KV head together, K and V are read once
   const int group = c->dv.group;
-  const int gt = (m <= ATTN_SPLIT_HEADS_MAX_ROWS && group > 4) ? 4 : group;
+  const int gt = (m <= ATTN_SPLIT_HEADS_MAX_ROWS && group > 2) ? 2 : group;
   switch (gt) {
     case 1: launch_attention_g<WT, HD, 1>(c, rows, m, layer); break;
     case 2: launch_attention_g<WT, HD, 2>(c, rows, m, layer); break;
@@ -724,7 +726,9 @@ int decode_chunk(spark_ctx *c, int steps, int n, const int32_t *seq_ids, const i
   std::vector<int> want_depth((size_t)steps * n), want_text((size_t)steps * n),
       want_rows((size_t)steps * n);
   for (int st = 0; st < steps; ++st) {
-    int n_upper = 0, n_ee = 0, n_full = 0;
+    int n_upper = 0, n_ee = 0, n_full = 0, max_pos = 0;
+    for (int i = 0; i < n; ++i) max_pos = std::max(max_pos, mir[i].len);   // position of the new row
+    c->attn_splits_now = max_pos / ATTN_SLICE + 1;
     for (int i = 0; i < n; ++i) {
       int is_text, full;
       schedule_decide(c->sp, mir[i].g, c->seqs[seq_ids[i]].cycle_offset, mir[i].j, is_text, full);
@@ -810,6 +814,7 @@ template <typename WT> int prefill_rows(spark_ctx *c, int id, const int32_t *pro
     embed_rows_k<WT><<<m, 256, 0, c->stream>>>(rows_dev, nullptr, tok_dev, (const WT *)c->w.embed,
                                                g.d_model, at<float>(c, c->lo.hidden));
     HIP_TRY(c, hipGetLastError());
+    c->attn_splits_now = (p0 + m - 1) / ATTN_SLICE + 1;
     if ((rc = run_layers<WT>(c, 0, g.n_layers, rows_dev, m))) return rc;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
   }
