@@ -24,7 +24,7 @@ using namespace spark;
 
 namespace {
 
-constexpr int PREFILL_CHUNK = 128;   // prompt rows pushed through the layers together
+constexpr int PREFILL_CHUNK = 256;   // most prompt rows pushed through the layers together (buffers are sized for it)
 constexpr size_t MFMA_PARTIAL_BYTES = 48u << 20;  // k-split partial sums of one projection
 constexpr int MAX_STEPS_PER_CALL = 256;
 constexpr int MAX_SEQ_LEN = 16384;
@@ -70,6 +70,7 @@ struct spark_ctx {
   bool use_mfma = true;        // SPARK_NO_MFMA=1 keeps every row count on the vector kernels
   unsigned bar_round = 0;      // grid barriers passed since the barrier words were zeroed
   unsigned long long *timeline_dev = nullptr;  // debugging aid, see SPARK_PASS_TIMELINE
+  int prefill_chunk = 128;   // prompt rows per pass, see spark_init
   int attn_splits_now = 0;   // context slices the rows of the passes being enqueued can reach (0: unknown, launch all)
   std::map<std::pair<const void *, size_t>, int> occ_cache;  // workgroups per CU of a (kernel, LDS bytes)
   // profiling of one kernel class
@@ -806,8 +807,8 @@ template <typename WT> int prefill_rows(spark_ctx *c, int id, const int32_t *pro
   RowDesc *rows_dev = at<RowDesc>(c, c->lo.prefill_rows);
   int *tok_dev = at<int>(c, c->lo.prefill_tokens);
   int rc;
-  for (int p0 = 0; p0 < n_rows; p0 += PREFILL_CHUNK) {
-    const int m = std::min(PREFILL_CHUNK, n_rows - p0);
+  for (int p0 = 0; p0 < n_rows; p0 += c->prefill_chunk) {
+    const int m = std::min(c->prefill_chunk, n_rows - p0);
     for (int r = 0; r < m; ++r) rows[r] = RowDesc{base_slot + r, id, p0 + r, -1};
     HIP_TRY(c, hipMemcpyAsync(rows_dev, rows.data(), sizeof(RowDesc) * m, hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipMemcpyAsync(tok_dev, prompt + p0, sizeof(int) * m, hipMemcpyHostToDevice, c->stream));
@@ -880,6 +881,13 @@ int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_p
   // the MFMA kernels load 16-byte vectors of 8 weights; other widths stay on the vector kernel
   c->use_mfma = !(no_mfma && no_mfma[0] == '1') && cfg->d_model % 8 == 0 &&
                 (cfg->n_q_heads * cfg->head_dim) % 8 == 0 && cfg->d_ffn % 8 == 0;
+  // Prompt rows per pass: on the MFMA path the widest projection (gate/up) is cut into tiles of 256
+  // weight-row pairs x 64 prompt rows; the row count is chosen so that one round of tiles about
+  // fills the chip, which needs no k split and no second kernel for that projection.
+  if (c->use_mfma && cfg->dtype == SPARK_DTYPE_BF16) {
+    const int x_tiles = (cfg->d_ffn + MG_TASKS_PER_BLOCK - 1) / MG_TASKS_PER_BLOCK;
+    c->prefill_chunk = std::max(128, std::min(PREFILL_CHUNK, 64 * (c->n_cu / std::max(1, x_tiles))));
+  }
   const char *tl = getenv("SPARK_PASS_TIMELINE");   // debugging aid: per-phase times on stderr
   if (tl && tl[0] == '1' &&
       hipMalloc((void **)&c->timeline_dev, sizeof(unsigned long long) * 16384) != hipSuccess)
