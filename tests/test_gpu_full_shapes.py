@@ -1,6 +1,6 @@
 """GPU parity at the full model shapes of the two benchmark backbones, in the launch configuration
 bench.py times (batch 1, 64-token KV pages), on shortened runs the oracle finishes in about a
-minute: 32-token prompt, then a few interleave cycles teacher-forced."""
+minute: 32-token prompt, then a few interleave cycles teacher-forced; and one 200-token prompt."""
 import time
 
 import numpy as np
@@ -12,11 +12,14 @@ from parity_util import compare_run, say
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("name,n_steps,offset", [
-    ("step_audio_2_mini", 36, 0),    # 3 * (1 + 2) * 4 steps: flushes of 1, 2 and 3 rows
-    ("glm_4_voice", 24, 10),         # enters the cycle 3 text slots before a 26-slot speech chunk
+@pytest.mark.parametrize("name,n_steps,offset,n_prompt", [
+    ("step_audio_2_mini", 36, 0, 32),    # 3 * (1 + 2) * 4 steps: flushes of 1, 2 and 3 rows
+    ("glm_4_voice", 24, 10, 32),         # enters the cycle 3 text slots before a 26-slot speech chunk
+    # a prompt longer than one pass of the prompt path (192 rows at this shape: three tiles of 64
+    # rows on the MFMA units, then a ragged pass), and a context of several attention slices
+    ("step_audio_2_mini", 8, 1, 200),
 ])
-def test_full_shape_short_run(name, n_steps, offset):
+def test_full_shape_short_run(name, n_steps, offset, n_prompt):
     import torch
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
@@ -27,8 +30,8 @@ def test_full_shape_short_run(name, n_steps, offset):
     dev_w = wl.make_weights_on_device(w.shape, seed=0)
     host_w = wl.device_weights_to_host(dev_w)
     say(f"  weights on device and host in {time.time() - t0:.1f}s")
-    sp = sb.Spark(w.shape, w.schedule, dev_w, max_batch=1, max_seq_len=128, kv_page_tokens=64)
-    prompt = wl.make_prompt(w.shape, 32, seed=1, ids=w.prompt_ids)
+    sp = sb.Spark(w.shape, w.schedule, dev_w, max_batch=1, max_seq_len=n_prompt + 96, kv_page_tokens=64)
+    prompt = wl.make_prompt(w.shape, n_prompt, seed=1, ids=w.prompt_ids)
     t0 = time.time()
     # Reference: the oracle's fp64 twin.  Its fp32 build sums 3584..18944-term dot products
     # sequentially, which leaves ~sqrt(n) * 2^-24 relative noise in K and V; re-rounding those to
@@ -39,7 +42,8 @@ def test_full_shape_short_run(name, n_steps, offset):
                       check_kv_every=0, label=name, oracle_kind="f64")
     say(f"  compared in {time.time() - t0:.1f}s")
     depths = res["depths"][:, 0]
-    assert set(np.unique(depths)) == {w.schedule.exit_layer, w.shape.n_layers}
+    assert set(np.unique(depths)) <= {w.schedule.exit_layer, w.shape.n_layers}
+    assert n_steps < 12 or len(np.unique(depths)) == 2
     sp.close()
     del dev_w, host_w
     torch.cuda.empty_cache()
