@@ -46,7 +46,14 @@ struct ProPlain {
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
       int mm = m < n_valid ? m : n_valid - 1;
-      const float *row = src + (size_t)(indirect ? rd[mm].x_slot : tile0 + mm) * stride + k0;
+      int slot = tile0 + mm;
+      if (indirect) {   // (a chain of selects: indexing rd[] with a variable would put it in scratch memory)
+        slot = rd[0].x_slot;
+#pragma unroll
+        for (int q = 1; q < MT; ++q)
+          if (q == mm) slot = rd[q].x_slot;
+      }
+      const float *row = src + (size_t)slot * stride + k0;
       float *xrow = xs + m * kc;
       for (int kb = threadIdx.x * 4; kb < klen; kb += GEMV_THREADS * 4 * BATCH) {
         float4 v[BATCH];
@@ -77,6 +84,73 @@ struct ProNorm {
   __device__ void stage(float *xs, int kc, const RowDesc *rd, int tile0, int n_valid, int k0,
                         int klen, float *red) const {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int NI = 4;   // 16-byte vectors per thread and row the register path holds: d <= 4096
+    if (d <= NI * GEMV_THREADS * 4) {
+      // two rows at a time: their elements are requested before any is used (one memory round
+      // trip per pair instead of two per row) and stay in registers between the two passes
+      constexpr int RB = MT < 2 ? MT : 2;
+      float4 g[NI];
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        const int k = threadIdx.x * 4 + i * GEMV_THREADS * 4;
+        g[i] = *(const float4 *)(gamma + (k < d ? k : 0));
+      }
+#pragma unroll
+      for (int m0 = 0; m0 < MT; m0 += RB) {
+        float4 v[RB][NI];
+#pragma unroll
+        for (int b = 0; b < RB; ++b) {
+          const int m = m0 + b < MT ? m0 + b : MT - 1;
+          const int mm = m < n_valid ? m : n_valid - 1;
+          int slot = tile0 + mm;
+          if (indirect) {
+            slot = rd[0].x_slot;
+#pragma unroll
+            for (int q = 1; q < MT; ++q)
+              if (q == mm) slot = rd[q].x_slot;
+          }
+          const float *row = hidden + (size_t)slot * d;
+#pragma unroll
+          for (int i = 0; i < NI; ++i) {
+            const int k = threadIdx.x * 4 + i * GEMV_THREADS * 4;
+            v[b][i] = *(const float4 *)(row + (k < d ? k : 0));
+          }
+        }
+        float ss[RB];
+#pragma unroll
+        for (int b = 0; b < RB; ++b) {
+          ss[b] = 0.f;
+#pragma unroll
+          for (int i = 0; i < NI; ++i)
+            if (threadIdx.x * 4 + i * GEMV_THREADS * 4 < d)
+              ss[b] += v[b][i].x * v[b][i].x + v[b][i].y * v[b][i].y + v[b][i].z * v[b][i].z + v[b][i].w * v[b][i].w;
+          ss[b] = wave_sum(ss[b]);
+          if (lane == 0) red[wave * RB + b] = ss[b];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int b = 0; b < RB; ++b) {
+          if (m0 + b < MT) {
+            float tot = 0.f;
+#pragma unroll
+            for (int w = 0; w < GEMV_WAVES; ++w) tot += red[w * RB + b];
+            const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+            float *xrow = xs + (m0 + b) * kc;
+#pragma unroll
+            for (int i = 0; i < NI; ++i) {
+              const int k = threadIdx.x * 4 + i * GEMV_THREADS * 4;
+              if (k < d)
+                *(float4 *)(xrow + lds_pos<VEC>(k)) =
+                    make_float4(v[b][i].x * inv * g[i].x, v[b][i].y * inv * g[i].y, v[b][i].z * inv * g[i].z,
+                                v[b][i].w * inv * g[i].w);
+            }
+            zero_tail<VEC>(xrow, d);
+          }
+        }
+        if (m0 + RB < MT) __syncthreads();   // `red` is reused by the next pair
+      }
+      return;
+    }
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
       int mm = m < n_valid ? m : n_valid - 1;

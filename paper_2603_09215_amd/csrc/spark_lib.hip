@@ -237,7 +237,7 @@ int launch_gemv(spark_ctx *c, const Pro &pro, const Epi &epi, const RowDesc *row
   // chip holds at once (no second wave of blocks with a cold pipeline)
   void (*kern)(Pro, Epi, const RowDesc *, int, int, int, int) = nullptr;
   // much LDS per workgroup means few waves per CU: those launches keep more loads in flight
-  const bool deep = lds > 40960;
+  const bool deep = lds > 54 * 1024;   // at most two workgroups per CU
   switch (mt) {
     case 1: kern = deep ? gemv_rows_k<WT, 1, Pro, Epi, GEMV_U_DEEP, GEMV_D_DEEP> : gemv_rows_k<WT, 1, Pro, Epi>; break;
     case 2: kern = deep ? gemv_rows_k<WT, 2, Pro, Epi, GEMV_U_DEEP, GEMV_D_DEEP> : gemv_rows_k<WT, 2, Pro, Epi>; break;
