@@ -13,6 +13,7 @@ namespace spark {
 
 constexpr int GEMV_THREADS = 256;
 constexpr int GEMV_WAVES = GEMV_THREADS / 64;
+constexpr int GEMV_BIG_THREADS = 512;  // for launches whose activations fill the LDS of half a CU
 
 // LDS position of activation element k (multiple of 4) of a row.  With 8 weights per lane and
 // load, a lane needs x[8*lane .. 8*lane+8); storing the two float4 halves 256 floats apart makes
@@ -24,10 +25,20 @@ template <int VEC> __device__ __forceinline__ int lds_pos(int k) {
 
 // The last 512-element block of a staged row may be partial; lanes whose weights were masked to
 // zero still multiply what lies there, so it must be finite: fill it with zeros.
-template <int VEC> __device__ __forceinline__ void zero_tail(float *xrow, int klen) {
+template <int VEC, int NT> __device__ __forceinline__ void zero_tail(float *xrow, int klen) {
   const int end = (klen + 511) & ~511;
-  for (int k = klen + threadIdx.x * 4; k < end; k += GEMV_THREADS * 4)
+  for (int k = klen + threadIdx.x * 4; k < end; k += NT * 4)
     *(float4 *)(xrow + lds_pos<VEC>(k)) = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+// hidden-state slot of pass row mm (a chain of selects: indexing rd[] with a variable would put
+// the array in scratch memory)
+template <int MT> __device__ __forceinline__ int row_slot(const RowDesc *rd, int mm) {
+  int slot = rd[0].x_slot;
+#pragma unroll
+  for (int q = 1; q < MT; ++q)
+    if (q == mm) slot = rd[q].x_slot;
+  return slot;
 }
 
 // ------------------------------------------------------------------ prologues (fill LDS)
@@ -40,35 +51,29 @@ struct ProPlain {
   // BATCH: loads a thread issues before it uses any.  A loop that loads, waits and stores per
   // iteration costs a memory round trip per iteration (18 of them for an MLP-width row); the
   // batch costs registers, so only the launches that have them to spare ask for more than one.
-  template <int VEC, int MT, int BATCH>
+  template <int VEC, int MT, int BATCH, int NT>
   __device__ void stage(float *xs, int kc, const RowDesc *rd, int tile0, int n_valid, int k0,
                         int klen, float *red) const {
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
       int mm = m < n_valid ? m : n_valid - 1;
-      int slot = tile0 + mm;
-      if (indirect) {   // (a chain of selects: indexing rd[] with a variable would put it in scratch memory)
-        slot = rd[0].x_slot;
-#pragma unroll
-        for (int q = 1; q < MT; ++q)
-          if (q == mm) slot = rd[q].x_slot;
-      }
+      const int slot = indirect ? row_slot<MT>(rd, mm) : tile0 + mm;
       const float *row = src + (size_t)slot * stride + k0;
       float *xrow = xs + m * kc;
-      for (int kb = threadIdx.x * 4; kb < klen; kb += GEMV_THREADS * 4 * BATCH) {
+      for (int kb = threadIdx.x * 4; kb < klen; kb += NT * 4 * BATCH) {
         float4 v[BATCH];
 #pragma unroll
         for (int i = 0; i < BATCH; ++i) {
-          const int k = kb + i * GEMV_THREADS * 4;
+          const int k = kb + i * NT * 4;
           v[i] = *(const float4 *)(row + (k < klen ? k : 0));
         }
 #pragma unroll
         for (int i = 0; i < BATCH; ++i) {
-          const int k = kb + i * GEMV_THREADS * 4;
+          const int k = kb + i * NT * 4;
           if (k < klen) *(float4 *)(xrow + lds_pos<VEC>(k)) = v[i];
         }
       }
-      zero_tail<VEC>(xrow, klen);
+      zero_tail<VEC, NT>(xrow, klen);
     }
   }
 };
@@ -80,19 +85,19 @@ struct ProNorm {
   float eps;
   int d;
   int indirect;  // 1: row = x_slot of the row descriptor; 0: row = pass row index
-  template <int VEC, int MT, int BATCH>
+  template <int VEC, int MT, int BATCH, int NT>
   __device__ void stage(float *xs, int kc, const RowDesc *rd, int tile0, int n_valid, int k0,
                         int klen, float *red) const {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    constexpr int NI = 4;   // 16-byte vectors per thread and row the register path holds: d <= 4096
-    if (d <= NI * GEMV_THREADS * 4) {
+    constexpr int NI = 4096 / (NT * 4);   // 16-byte vectors per thread and row the register path holds: d <= 4096
+    if (d <= NI * NT * 4) {
       // two rows at a time: their elements are requested before any is used (one memory round
       // trip per pair instead of two per row) and stay in registers between the two passes
       constexpr int RB = MT < 2 ? MT : 2;
       float4 g[NI];
 #pragma unroll
       for (int i = 0; i < NI; ++i) {
-        const int k = threadIdx.x * 4 + i * GEMV_THREADS * 4;
+        const int k = threadIdx.x * 4 + i * NT * 4;
         g[i] = *(const float4 *)(gamma + (k < d ? k : 0));
       }
 #pragma unroll
@@ -102,17 +107,10 @@ struct ProNorm {
         for (int b = 0; b < RB; ++b) {
           const int m = m0 + b < MT ? m0 + b : MT - 1;
           const int mm = m < n_valid ? m : n_valid - 1;
-          int slot = tile0 + mm;
-          if (indirect) {
-            slot = rd[0].x_slot;
-#pragma unroll
-            for (int q = 1; q < MT; ++q)
-              if (q == mm) slot = rd[q].x_slot;
-          }
-          const float *row = hidden + (size_t)slot * d;
+          const float *row = hidden + (size_t)(indirect ? row_slot<MT>(rd, mm) : tile0 + mm) * d;
 #pragma unroll
           for (int i = 0; i < NI; ++i) {
-            const int k = threadIdx.x * 4 + i * GEMV_THREADS * 4;
+            const int k = threadIdx.x * 4 + i * NT * 4;
             v[b][i] = *(const float4 *)(row + (k < d ? k : 0));
           }
         }
@@ -122,7 +120,7 @@ struct ProNorm {
           ss[b] = 0.f;
 #pragma unroll
           for (int i = 0; i < NI; ++i)
-            if (threadIdx.x * 4 + i * GEMV_THREADS * 4 < d)
+            if (threadIdx.x * 4 + i * NT * 4 < d)
               ss[b] += v[b][i].x * v[b][i].x + v[b][i].y * v[b][i].y + v[b][i].z * v[b][i].z + v[b][i].w * v[b][i].w;
           ss[b] = wave_sum(ss[b]);
           if (lane == 0) red[wave * RB + b] = ss[b];
@@ -133,18 +131,18 @@ struct ProNorm {
           if (m0 + b < MT) {
             float tot = 0.f;
 #pragma unroll
-            for (int w = 0; w < GEMV_WAVES; ++w) tot += red[w * RB + b];
+            for (int w = 0; w < (NT / 64); ++w) tot += red[w * RB + b];
             const float inv = 1.0f / sqrtf(tot / (float)d + eps);
             float *xrow = xs + (m0 + b) * kc;
 #pragma unroll
             for (int i = 0; i < NI; ++i) {
-              const int k = threadIdx.x * 4 + i * GEMV_THREADS * 4;
+              const int k = threadIdx.x * 4 + i * NT * 4;
               if (k < d)
                 *(float4 *)(xrow + lds_pos<VEC>(k)) =
                     make_float4(v[b][i].x * inv * g[i].x, v[b][i].y * inv * g[i].y, v[b][i].z * inv * g[i].z,
                                 v[b][i].w * inv * g[i].w);
             }
-            zero_tail<VEC>(xrow, d);
+            zero_tail<VEC, NT>(xrow, d);
           }
         }
         if (m0 + RB < MT) __syncthreads();   // `red` is reused by the next pair
@@ -154,9 +152,9 @@ struct ProNorm {
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
       int mm = m < n_valid ? m : n_valid - 1;
-      const float *row = hidden + (size_t)(indirect ? rd[mm].x_slot : tile0 + mm) * d;
+      const float *row = hidden + (size_t)(indirect ? row_slot<MT>(rd, mm) : tile0 + mm) * d;
       float ss = 0.f;
-      for (int k = threadIdx.x * 4; k < d; k += GEMV_THREADS * 4) {
+      for (int k = threadIdx.x * 4; k < d; k += NT * 4) {
         float4 v = *(const float4 *)(row + k);
         ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
       }
@@ -167,18 +165,18 @@ struct ProNorm {
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
       int mm = m < n_valid ? m : n_valid - 1;
-      const float *row = hidden + (size_t)(indirect ? rd[mm].x_slot : tile0 + mm) * d;
+      const float *row = hidden + (size_t)(indirect ? row_slot<MT>(rd, mm) : tile0 + mm) * d;
       float tot = 0.f;
 #pragma unroll
-      for (int w = 0; w < GEMV_WAVES; ++w) tot += red[w * MT + m];
+      for (int w = 0; w < (NT / 64); ++w) tot += red[w * MT + m];
       float inv = 1.0f / sqrtf(tot / (float)d + eps);
-      for (int k = threadIdx.x * 4; k < d; k += GEMV_THREADS * 4) {
+      for (int k = threadIdx.x * 4; k < d; k += NT * 4) {
         float4 v = *(const float4 *)(row + k);
         float4 g = *(const float4 *)(gamma + k);
         float4 o = make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w);
         *(float4 *)(xs + m * kc + lds_pos<VEC>(k)) = o;
       }
-      zero_tail<VEC>(xs + m * kc, d);
+      zero_tail<VEC, NT>(xs + m * kc, d);
     }
   }
 };
@@ -342,9 +340,7 @@ __device__ __forceinline__ uint4 load_weights16(const void *p) {
 }
 
 constexpr int GEMV_U = 2;  // 16-byte loads per weight row and pipeline stage (many waves per CU)
-constexpr int GEMV_U_DEEP = 4;  // same, for launches whose LDS use leaves only two workgroups per CU
 constexpr int GEMV_D = 2;  // stages in the register ring (measured: 2 beats 3 when many waves share a CU)
-constexpr int GEMV_D_DEEP = 2;  // same, for the launches with few waves per CU, which are latency-bound otherwise
 
 // One pipeline stage of weights: U consecutive 1 KiB segments of both rows of a task.
 template <int U> struct WStage {
@@ -413,7 +409,7 @@ __device__ __forceinline__ void issue_stage_nb(WStage<U> &s, const WT *p0, const
 
 // grid.x: blocks that share the weight rows; grid.y: tiles of MT activation rows.
 // kc: activation elements of one row held in LDS at a time (multiple of 512).
-// Dynamic LDS: (MT*kc + GEMV_WAVES*MT) floats.
+// NT threads per workgroup.  Dynamic LDS: (MT*kc + (NT/64)*MT) floats.
 //
 // A wave walks its weights as one sequence of stages (U 16-byte loads per row and lane): for each
 // of its tasks, for each LDS chunk of the input, for each group of the chunk.  D stages live in a
@@ -421,13 +417,13 @@ __device__ __forceinline__ void issue_stage_nb(WStage<U> &s, const WT *p0, const
 // D-1 stages are in flight while one is multiplied, across chunk and task boundaries, and the
 // first D stages are issued before the prologue touches the activations: the norm, the
 // reductions and the epilogues all run under outstanding HBM requests.
-template <typename WT, int MT, typename Pro, typename Epi, int U = GEMV_U, int D = GEMV_D>
-__global__ void __launch_bounds__(GEMV_THREADS)
+template <typename WT, int MT, typename Pro, typename Epi, int U = GEMV_U, int D = GEMV_D, int NT = GEMV_THREADS>
+__global__ void __launch_bounds__(NT)
 gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int n_in, int n_tasks,
             int kc) {
   extern __shared__ float4 smem4[];
   float *xs = (float *)smem4;          // [MT][kc] activations
-  float *red = xs + MT * kc;           // [GEMV_WAVES][MT] partial sums of squares
+  float *red = xs + MT * kc;           // [NT / 64][MT] partial sums of squares
   constexpr int VEC = Elem<WT>::VEC;
   constexpr int WSTEP = 64 * VEC;
   constexpr int GSTEP = U * WSTEP;
@@ -441,7 +437,7 @@ gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int 
 
   const int n_chunks = (n_in + kc - 1) / kc;
   const int n_groups = (min(kc, n_in) + GSTEP - 1) / GSTEP;   // of a full chunk; a short last chunk masks
-  const int n_waves = gridDim.x * GEMV_WAVES, wave_global = blockIdx.x * GEMV_WAVES + wave;
+  const int n_waves = gridDim.x * (NT / 64), wave_global = blockIdx.x * (NT / 64) + wave;
   const int rounds = (n_tasks + n_waves - 1) / n_waves;       // same for every wave: the chunk staging synchronises the workgroup
   const int n_stages = rounds * n_chunks * n_groups;
   typename Epi::State st;
@@ -481,7 +477,7 @@ gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int 
         const int k0 = chunk * kc, klen = min(kc, n_in - k0);
         if (g == 0 && (task == wave_global || n_chunks > 1)) {
           __syncthreads();
-          pro.template stage<VEC, MT, (U >= GEMV_U_DEEP ? 8 : 1)>(xs, kc, rd, tile0, n_valid, k0, klen, red);
+          pro.template stage<VEC, MT, (NT > GEMV_THREADS ? 4 : 1), NT>(xs, kc, rd, tile0, n_valid, k0, klen, red);
           __syncthreads();
         }
         if (valid) {

@@ -227,22 +227,24 @@ int launch_gemv(spark_ctx *c, const Pro &pro, const Epi &epi, const RowDesc *row
   if (mt == 1 && sizeof(float) * align_up(n_in, 512) + 64 > budget &&
       sizeof(float) * align_up(n_in, 512) + 64 <= 81920)
     budget = 81920;
-  const size_t lds_budget = budget - sizeof(float) * GEMV_WAVES * 4;
+  const size_t lds_budget = budget - sizeof(float) * (GEMV_BIG_THREADS / 64) * 4;
   while (mt > 1 && whole_row && sizeof(float) * mt * align_up(n_in, 512) > lds_budget) --mt;
   int kc_cap = (int)(lds_budget / (sizeof(float) * mt)) / 512 * 512;
   int kc = std::min((int)align_up(n_in, 512), kc_cap);
   if (whole_row && kc < n_in) return fail(c, SPARK_EINVAL, "row of %d does not fit in LDS", n_in);
-  size_t lds = sizeof(float) * ((size_t)mt * kc + GEMV_WAVES * mt);
+  // much LDS per workgroup means few workgroups per CU: those launches run eight waves per
+  // workgroup, so that a CU still has 16 waves streaming
+  const bool big = sizeof(float) * (size_t)mt * kc > 54 * 1024;   // at most two workgroups per CU
+  const int threads = big ? GEMV_BIG_THREADS : GEMV_THREADS, waves = threads / 64;
+  size_t lds = sizeof(float) * ((size_t)mt * kc + waves * mt);
   // one resident set of blocks: the kernel loops over its tasks, so the grid is sized to what the
   // chip holds at once (no second wave of blocks with a cold pipeline)
   void (*kern)(Pro, Epi, const RowDesc *, int, int, int, int) = nullptr;
-  // much LDS per workgroup means few waves per CU: those launches keep more loads in flight
-  const bool deep = lds > 54 * 1024;   // at most two workgroups per CU
   switch (mt) {
-    case 1: kern = deep ? gemv_rows_k<WT, 1, Pro, Epi, GEMV_U_DEEP, GEMV_D_DEEP> : gemv_rows_k<WT, 1, Pro, Epi>; break;
-    case 2: kern = deep ? gemv_rows_k<WT, 2, Pro, Epi, GEMV_U_DEEP, GEMV_D_DEEP> : gemv_rows_k<WT, 2, Pro, Epi>; break;
-    case 3: kern = deep ? gemv_rows_k<WT, 3, Pro, Epi, GEMV_U_DEEP, GEMV_D_DEEP> : gemv_rows_k<WT, 3, Pro, Epi>; break;
-    default: kern = deep ? gemv_rows_k<WT, 4, Pro, Epi, GEMV_U_DEEP, GEMV_D_DEEP> : gemv_rows_k<WT, 4, Pro, Epi>; break;
+    case 1: kern = big ? gemv_rows_k<WT, 1, Pro, Epi, GEMV_U, GEMV_D, GEMV_BIG_THREADS> : gemv_rows_k<WT, 1, Pro, Epi>; break;
+    case 2: kern = big ? gemv_rows_k<WT, 2, Pro, Epi, GEMV_U, GEMV_D, GEMV_BIG_THREADS> : gemv_rows_k<WT, 2, Pro, Epi>; break;
+    case 3: kern = big ? gemv_rows_k<WT, 3, Pro, Epi, GEMV_U, GEMV_D, GEMV_BIG_THREADS> : gemv_rows_k<WT, 3, Pro, Epi>; break;
+    default: kern = big ? gemv_rows_k<WT, 4, Pro, Epi, GEMV_U, GEMV_D, GEMV_BIG_THREADS> : gemv_rows_k<WT, 4, Pro, Epi>; break;
   }
   // attribute and occupancy are asked for once per (kernel, LDS size), not on every launch
   const auto key = std::make_pair((const void *)kern, lds);
@@ -251,12 +253,12 @@ int launch_gemv(spark_ctx *c, const Pro &pro, const Epi &epi, const RowDesc *row
     if (lds > 65536)
       HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 81920));
     int o = 0;
-    HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, kern, GEMV_THREADS, lds));
+    HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, kern, threads, lds));
     found = c->occ_cache.emplace(key, std::max(1, std::min(o, 4))).first;
   }
   const int occ = found->second;
-  int bx = std::min((n_tasks + GEMV_WAVES - 1) / GEMV_WAVES, c->n_cu * occ);
-  dim3 grid(bx, (m_rows + mt - 1) / mt), block(GEMV_THREADS);
+  int bx = std::min((n_tasks + waves - 1) / waves, c->n_cu * occ);
+  dim3 grid(bx, (m_rows + mt - 1) / mt), block(threads);
   int rc = prof_begin(c, kclass);
   if (rc) return rc;
   kern<<<grid, block, lds, c->stream>>>(pro, epi, rows, m_rows, n_in, n_tasks, kc);
