@@ -21,7 +21,7 @@ class OraConfig(C.Structure):
                [("rope_base", C.c_float), ("rms_eps", C.c_float)] + \
                [(n, C.c_int32) for n in
                 ("dtype", "exit_layer", "period_k", "phase", "scope", "n_text", "n_speech",
-                 "max_seq_len", "kv_round_bf16")]
+                 "max_seq_len", "kv_round_bf16", "text_period_k", "text_phase")]
 
 
 WEIGHT_FIELDS = ("embed", "attn_norm", "wq", "wk", "wv", "wo", "mlp_norm", "wg", "wu", "wd",
@@ -59,6 +59,7 @@ def load(kind: str = "f32") -> C.CDLL:
     for f in ("ora_seq_len", "ora_seq_upper_valid", "ora_seq_pending"):
         getattr(lib, f).argtypes = [P]
     lib.ora_seq_stats.argtypes = [P, P]
+    lib.ora_pend_cap.argtypes = [C.POINTER(OraConfig)]
     lib.ora_get_kv.argtypes = [P, I, I, P, P]
     lib.ora_lens_logits.argtypes = [P, P, P]
     lib.ora_prim_matvec.argtypes = [P, I, I, I, P, P]
@@ -88,7 +89,7 @@ def make_config(shape, sched, max_seq_len: int, kv_round_bf16: bool = False) -> 
                      shape.head_dim, shape.d_ffn, shape.vocab_text, shape.vocab_speech,
                      shape.rope_base, shape.rms_eps, shape.dtype, sched.exit_layer,
                      sched.period_k, sched.phase, sched.scope, sched.n_text, sched.n_speech,
-                     max_seq_len, int(kv_round_bf16))
+                     max_seq_len, int(kv_round_bf16), sched.text_period_k, sched.text_phase)
 
 
 def schedule_run(shape, sched, n_steps: int, cycle_offset: int = 0, kind: str = "f32"):
@@ -186,11 +187,12 @@ class Seq:
         return self.lib.ora_seq_pending(self.handle)
 
     def stats(self) -> dict:
-        k = self.m.sched.period_k
-        out = np.zeros(3 + 2 * k, dtype=np.int64)
+        cap = self.lib.ora_pend_cap(C.byref(self.m.cfg))
+        out = np.zeros(3 + cap, dtype=np.int64)
         self.lib.ora_seq_stats(self.handle, _ptr(out))
         return {"text": int(out[0]), "speech_full": int(out[1]), "speech_ee": int(out[2]),
-                "flush_hist": {m: int(out[2 + m]) for m in range(1, 2 * k) if out[2 + m]}}
+                "text_ee": int(out[2 + cap]),
+                "flush_hist": {m: int(out[2 + m]) for m in range(1, cap) if out[2 + m]}}
 
     def kv(self, layer: int, pos: int):
         w = self.m.shape.n_kv_heads * self.m.shape.head_dim

@@ -57,6 +57,10 @@ typedef struct {
   int32_t n_text, n_speech;
   int32_t max_seq_len;
   int32_t kv_round_bf16;  /* diagnostic: round cached K/V to bf16 precision when stored */
+  /* the same periodic rule on text positions (Sec. V-C "Exploring Text Early Exit Policies",
+   * Table II row G10): K_text <= 1 keeps every text position at full depth */
+  int32_t text_period_k;
+  int32_t text_phase;     /* in [0, K_text) */
 } ora_config;
 
 typedef struct {
@@ -90,8 +94,8 @@ typedef struct {
   int *pend_pos;    /* [2K] */
   int next_input, has_input;
   real **K, **V;    /* [L] -> [max_seq_len][nkv*hd] */
-  int64_t n_text_steps, n_speech_full, n_speech_ee;
-  int64_t *flush_hist; /* [2K]: how many full-depth steps processed m rows, m in 1..2K-1 */
+  int64_t n_text_steps, n_speech_full, n_speech_ee, n_text_ee;
+  int64_t *flush_hist; /* [pend_cap]: how many full-depth steps processed m rows */
 } ora_seq;
 
 /* ------------------------------------------------------------------ element access */
@@ -302,15 +306,31 @@ static void head_lens(const ora_model *m, const real *h, ora_tmp *t) {
 /* Decide the step that emits generated token number g (0-based).  The interleave pattern is a
  * fixed cycle of n_text text slots followed by n_speech speech slots, entered at cycle_offset.
  * A speech chunk is cut into periods of K slots; the slot with index phase inside each period
- * runs full depth, the other K-1 exit at layer e.  Text always runs full depth. */
+ * runs full depth, the other K-1 exit at layer e.  Text runs full depth, unless a text period
+ * K_text > 1 is given: then text positions follow the same rule with (K_text, text_phase),
+ * indexed inside their chunk (scope 0) or over all text positions so far (scope 1: g - j_stream
+ * of them have been emitted). */
 static void sched_decide(const ora_config *c, int g, int cycle_offset, int j_stream, int *is_text,
                          int *full) {
   int cyc = c->n_text + c->n_speech;
   int slot = (int)(((int64_t)g + cycle_offset) % cyc);
   *is_text = slot < c->n_text;
-  int j = (c->scope == 0) ? slot - c->n_text : j_stream;
-  *full = *is_text || c->exit_layer == c->n_layers || c->period_k == 1 ||
-          (j % c->period_k == c->phase);
+  if (c->exit_layer == c->n_layers) {
+    *full = 1;
+  } else if (*is_text) {
+    int t = (c->scope == 0) ? slot : g - j_stream;
+    *full = c->text_period_k <= 1 || (t % c->text_period_k == c->text_phase);
+  } else {
+    int j = (c->scope == 0) ? slot - c->n_text : j_stream;
+    *full = c->period_k == 1 || (j % c->period_k == c->phase);
+  }
+}
+
+/* rows the pending buffer holds: between two full-depth steps at most K-1 speech positions exit
+ * early inside a chunk; with no full-depth slot between them a chunk's tail (<= K-1) and the next
+ * chunk's head (<= K-1) can join: 2K-1 rows with the current one.  Text periods add the same. */
+static int pend_cap(const ora_config *c) {
+  return 2 * c->period_k + (c->text_period_k > 1 ? 2 * c->text_period_k : 0);
 }
 
 static int config_ok(const ora_config *c) {
@@ -323,10 +343,21 @@ static int config_ok(const ora_config *c) {
   if (c->scope != 0 && c->scope != 1) return 0;
   if (c->n_text < 0 || c->n_speech < 0 || c->n_text + c->n_speech < 1) return 0;
   if (c->dtype != 0 && c->dtype != 1) return 0;
-  /* a pure-speech cycle whose chunks hold no full-depth slot would never complete its KV */
-  if (c->n_text == 0 && c->scope == 0 && c->exit_layer < c->n_layers && c->period_k > 1 &&
-      c->phase >= c->n_speech)
-    return 0;
+  if (c->text_period_k < 0) return 0;
+  if (c->text_period_k > 1 && (c->text_phase < 0 || c->text_phase >= c->text_period_k)) return 0;
+  /* With counters that restart per chunk the pattern repeats with the cycle: a cycle without a
+   * full-depth slot would never complete its KV, and the longest run of early exits must fit the
+   * pending buffer.  (Counters over the stream reach every phase: runs hold at most K-1 speech
+   * and K_text-1 text positions.) */
+  if (c->scope == 0 && c->exit_layer < c->n_layers) {
+    int cyc = c->n_text + c->n_speech, run = 0, longest = 0, any_full = 0;
+    for (int g = 0; g < 2 * cyc; ++g) {
+      int is_text, full;
+      sched_decide(c, g, 0, 0, &is_text, &full);
+      if (full) { any_full = 1; run = 0; } else if (++run > longest) longest = run;
+    }
+    if (!any_full || longest + 1 > pend_cap(c)) return 0;
+  }
   return 1;
 }
 
@@ -389,11 +420,9 @@ ora_seq *ora_seq_open(ora_model *m, int cycle_offset) {
     s->V[l] = calloc((size_t)c->max_seq_len * kvw, sizeof(real));
     if (!s->K[l] || !s->V[l]) return NULL;
   }
-  /* Between two full-depth steps at most K-1 positions exit early inside a chunk; with no text
-   * slots a chunk's tail (<= K-1) and the next chunk's head (<= K-1) can join: 2K-1 rows. */
-  s->pend_h = calloc((size_t)2 * c->period_k * c->d_model, sizeof(real));
-  s->pend_pos = calloc((size_t)2 * c->period_k, sizeof(int));
-  s->flush_hist = calloc((size_t)2 * c->period_k, sizeof(int64_t));
+  s->pend_h = calloc((size_t)pend_cap(c) * c->d_model, sizeof(real));
+  s->pend_pos = calloc((size_t)pend_cap(c), sizeof(int));
+  s->flush_hist = calloc((size_t)pend_cap(c), sizeof(int64_t));
   return s;
 }
 
@@ -489,7 +518,7 @@ int ora_step(ora_seq *s, int forced_next, int32_t *tok_out, int32_t *depth_out,
   sched_decide(c, s->g, s->cycle_offset, s->j_stream, &is_text, &full);
 
   ora_tmp t;
-  if (tmp_alloc(c, 2 * c->period_k, &t)) return ORA_ENOMEM;
+  if (tmp_alloc(c, pend_cap(c), &t)) return ORA_ENOMEM;
   int pos = s->len;
   /* the current position's hidden state lives in the slot after the pending ones */
   real *h = s->pend_h + (size_t)s->n_pending * d;
@@ -507,7 +536,7 @@ int ora_step(ora_seq *s, int forced_next, int32_t *tok_out, int32_t *depth_out,
     y = argmax_lowest(t.logits, V);
     s->n_pending += 1;
     *depth_out = e;
-    s->n_speech_ee += 1;
+    if (is_text) s->n_text_ee += 1; else s->n_speech_ee += 1;
   } else {
     /* full depth: pending positions and the current one go through layers e+1..L together;
      * each row keeps its own position, attention is causal inside the batch because row r only
@@ -547,14 +576,17 @@ int ora_seq_len(const ora_seq *s) { return s->len; }
 int ora_seq_upper_valid(const ora_seq *s) { return s->upper_valid; }
 int ora_seq_pending(const ora_seq *s) { return s->n_pending; }
 
-/* stats: [0] text steps, [1] full-depth speech steps, [2] early-exit steps,
- * then flush_hist[1..2K-1] */
+/* stats: [0] full-depth text steps, [1] full-depth speech steps, [2] early-exit speech steps,
+ * then flush_hist[1..pend_cap-1], then [2 + pend_cap] early-exit text steps */
 void ora_seq_stats(const ora_seq *s, int64_t *out) {
+  const int cap = pend_cap(&s->m->c);
   out[0] = s->n_text_steps;
   out[1] = s->n_speech_full;
   out[2] = s->n_speech_ee;
-  for (int i = 1; i < 2 * s->m->c.period_k; ++i) out[2 + i] = s->flush_hist[i];
+  for (int i = 1; i < cap; ++i) out[2 + i] = s->flush_hist[i];
+  out[2 + cap] = s->n_text_ee;
 }
+int ora_pend_cap(const ora_config *c) { return pend_cap(c); }
 
 int ora_get_kv(const ora_seq *s, int layer /*0-based*/, int pos, double *k_out, double *v_out) {
   const ora_config *c = &s->m->c;

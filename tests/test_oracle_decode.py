@@ -82,6 +82,12 @@ CASES = [
     (dict(period_k=4, phase=3, n_text=1, n_speech=2, scope=wl.SCOPE_STREAM), 0),
     (dict(period_k=3, phase=1, n_text=0, n_speech=5, exit_layer=1), 2),   # no text: joined runs
     (dict(period_k=5, phase=4, n_text=2, n_speech=4, exit_layer=3), 1),   # fixed-layer baseline
+    # the periodic rule on text positions (Sec. V-C, Table II row G10: text Even, speech full depth)
+    (dict(text_period_k=2, text_phase=0, period_k=1, phase=0, n_text=3, n_speech=2), 0),
+    # both modalities scheduled: early-exit runs cross the modality boundary
+    (dict(text_period_k=2, text_phase=1, period_k=4, phase=3, n_text=2, n_speech=4), 1),
+    (dict(text_period_k=3, text_phase=0, period_k=2, phase=1, n_text=2, n_speech=3,
+          scope=wl.SCOPE_STREAM), 0),
 ]
 
 
@@ -123,7 +129,7 @@ def test_teacher_forced_spark_equals_full_depth_pass(tiny, kind, over, offset):
                     assert np.max(np.abs(k1 - k2)) < TOL[kind]
                     assert np.max(np.abs(v1 - v2)) < TOL[kind]
         else:
-            assert depth == e and not want_text[i]
+            assert depth == e and (not want_text[i] or sched.text_period_k > 1)
             want = od.lens_logits(w.shape, weights, hs[e, pos])
             assert np.max(np.abs(logits - want)) < TOL[kind]
             assert np.max(np.abs(logits - m.lens_logits(h_e))) < TOL[kind]
@@ -133,14 +139,18 @@ def test_teacher_forced_spark_equals_full_depth_pass(tiny, kind, over, offset):
         assert tok == int(np.argmax(logits))
         # bookkeeping: lower frontier = upper frontier + pending, pending bounded
         assert s.upper_valid + s.pending == s.len
-        assert s.pending <= (K - 1 if sched.n_text > 0 or sched.scope == wl.SCOPE_STREAM
-                             else 2 * K - 2)
+        if sched.text_period_k > 1:
+            assert s.pending <= 2 * (K - 1) + 2 * (sched.text_period_k - 1)
+        else:
+            assert s.pending <= (K - 1 if sched.n_text > 0 or sched.scope == wl.SCOPE_STREAM
+                                 else 2 * K - 2)
     st = s.stats()
-    assert st["text"] == int(want_text.sum())
-    assert st["speech_ee"] == int((want_depth == e).sum()) if e < L else True
+    assert st["text"] + st["text_ee"] == int(want_text.sum())
+    assert st["text_ee"] == int(((want_depth == e) & (want_text == 1)).sum()) if e < L else True
+    assert st["speech_ee"] == int(((want_depth == e) & (want_text == 0)).sum()) if e < L else True
     assert st["text"] + st["speech_full"] == sum(st["flush_hist"].values())
     assert sum(mm * c for mm, c in st["flush_hist"].items()) <= n
-    if e < L and K > 1:
+    if e < L and (K > 1 or sched.text_period_k > 1):
         assert seen_pending >= 1
     s.close(); ref.close(); m.close()
 

@@ -45,6 +45,92 @@ def test_table2_exit_layer_column(row):
     assert abs(got_saving - saving) <= 0.5 + 1e-9 + 100 * tol / L, (name, got_saving)
 
 
+def test_table2_text_exit_layer_row():
+    """row G10: the periodic rule on text positions, speech at full depth"""
+    path = GOLDEN.parent / "table2_text_exit_layers.txt"
+    for line in path.read_text().splitlines():
+        if not line.strip() or line.startswith("#"):
+            continue
+        f = line.split()
+        L, e, kt, pt, nt, ns, scope = map(int, f[1:8])
+        want, tol = float(f[8]), float(f[9])
+        sched = wl.Schedule(e, 1, 0, scope, nt, ns, text_period_k=kt, text_phase=pt)
+        depth, is_text = ob.schedule_run(shape_with_layers(L), sched, 40 * (nt + ns))
+        assert np.all(depth[is_text == 0] == L)                 # speech column: 40
+        assert abs(depth[is_text == 1].mean() - want) <= tol, (f[0], depth[is_text == 1].mean())
+
+
+def brute_force_schedule(L, e, K, phase, kt, pt, scope, nt, ns, n, off):
+    """the rule of Sec. IV-B.1 written out slot by slot, for both modalities"""
+    pattern = ["t"] * nt + ["s"] * ns
+    depth, is_text = [], []
+    seen = {"t": 0, "s": 0}       # positions of each modality emitted so far
+    for g in range(n):
+        kind = pattern[(g + off) % len(pattern)]
+        # the index inside the chunk is the slot's own (a sequence may enter the cycle mid-chunk)
+        slot = (g + off) % len(pattern)
+        idx_chunk = slot if kind == "t" else slot - nt
+        idx = idx_chunk if scope == wl.SCOPE_CHUNK else seen[kind]
+        period, ph = (kt, pt) if kind == "t" else (K, phase)
+        if kind == "t" and kt <= 1:
+            full = True
+        else:
+            full = e == L or period == 1 or idx % period == ph
+        depth.append(L if full else e)
+        is_text.append(1 if kind == "t" else 0)
+        seen[kind] += 1
+    return np.array(depth), np.array(is_text)
+
+
+def test_schedule_against_brute_force_both_modalities():
+    rng = np.random.default_rng(7)
+    L = 12
+    checked = 0
+    for _ in range(300):
+        e = int(rng.integers(1, L + 1))
+        K, kt = int(rng.integers(1, 6)), int(rng.integers(0, 5))
+        phase = int(rng.integers(0, K))
+        pt = int(rng.integers(0, max(kt, 1)))
+        nt, ns = int(rng.integers(0, 6)), int(rng.integers(0, 8))
+        if nt + ns == 0:
+            continue
+        scope = int(rng.integers(0, 2))
+        off = int(rng.integers(0, nt + ns))
+        sched = wl.Schedule(e, K, phase, scope, nt, ns, text_period_k=kt, text_phase=pt)
+        res = ob.schedule_run(shape_with_layers(L), sched, 5 * (nt + ns) + 3, off)
+        want_d, want_t = brute_force_schedule(L, e, K, phase, kt, pt, scope, nt, ns,
+                                              5 * (nt + ns) + 3, off)
+        if res is None:
+            # refused: counters restart per chunk and the cycle has no full-depth slot, or its
+            # longest run of early exits does not fit the pending buffer
+            assert scope == wl.SCOPE_CHUNK and e < L
+            d0, _ = brute_force_schedule(L, e, K, phase, kt, pt, scope, nt, ns, 2 * (nt + ns), 0)
+            runs = "".join("f" if x == L else "e" for x in d0).split("f")
+            cap = 2 * K + (2 * kt if kt > 1 else 0)
+            assert not (d0 == L).any() or max(len(r) for r in runs) + 1 > cap
+            continue
+        assert list(res[0]) == list(want_d) and list(res[1]) == list(want_t)
+        checked += 1
+    assert checked > 150
+
+
+def test_text_policy_closed_forms():
+    L, e = 12, 5
+    for kt, nt, ns in itertools.product([2, 3, 4], [1, 3, 13], [2, 4]):
+        for pt in range(kt):
+            sched = wl.Schedule(e, 1, 0, wl.SCOPE_STREAM, nt, ns, text_period_k=kt, text_phase=pt)
+            depth, is_text = ob.schedule_run(shape_with_layers(L), sched, kt * 6 * (nt + ns))
+            text = depth[is_text == 1]
+            assert len(text) % kt == 0
+            assert text.mean() == pytest.approx(((kt - 1) * e + L) / kt, abs=1e-12)
+            assert np.all(depth[is_text == 0] == L)
+            sched = sched.replace(scope=wl.SCOPE_CHUNK)
+            res = ob.schedule_run(shape_with_layers(L), sched, 6 * (nt + ns))
+            depth, is_text = res
+            n_full = int(((is_text == 1) & (depth == L)).sum())
+            assert n_full == 6 * full_count_closed_form(nt, kt, pt)
+
+
 def test_named_schedules_patterns():
     """Even / Odd / Triple as spelled out in Sec. IV-B.1, on Step-Audio-2's 4-slot chunk:
     each has two full-depth and two early-exit positions (discussion of schedule variants)."""

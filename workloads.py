@@ -55,6 +55,10 @@ class Schedule:
     scope: int
     n_text: int
     n_speech: int
+    # the same periodic rule on text positions (Sec. V-C, Table II row G10); K_text <= 1: text
+    # always runs full depth
+    text_period_k: int = 0
+    text_phase: int = 0
 
     def replace(self, **kw) -> "Schedule":
         return dataclasses.replace(self, **kw)
