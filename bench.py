@@ -68,6 +68,8 @@ def main() -> int:
                          "random prompt lengths in 256..2048 and mixed cycle offsets")
     ap.add_argument("--exit-layer", type=int, default=None, help="override the workload's exit layer e")
     ap.add_argument("--period", type=int, default=None, help="override the refresh period K (phase becomes K-1)")
+    ap.add_argument("--text-period", type=int, default=None,
+                    help="apply the periodic rule to text positions too, with this period and phase 0")
     ap.add_argument("--aligned", action="store_true",
                     help="batch > 1: every sequence starts at cycle offset 0 (phase-aligned schedules)")
     args = ap.parse_args()
@@ -88,6 +90,8 @@ def main() -> int:
         sched = dataclasses.replace(sched, exit_layer=args.exit_layer)
     if args.period is not None:
         sched = dataclasses.replace(sched, period_k=args.period, phase=args.period - 1)
+    if args.text_period is not None:
+        sched = dataclasses.replace(sched, text_period_k=args.text_period, text_phase=0)
     prompt_len = args.prompt_len or w.prompt_len
     K, W = args.steps, args.warmup
     device = torch.device("cuda:0")
@@ -231,6 +235,7 @@ def main() -> int:
                                f"V={shape.vocab}; prompt {prompt_len if B == 1 else '256..2048'}, decode {K}, batch {B}, "
                                f"{sched.n_text}:{sched.n_speech} text:speech, e={sched.exit_layer}, "
                                f"K={sched.period_k}, phase={sched.phase}, "
+                               f"{'K_text=' + str(sched.text_period_k) + ', ' if sched.text_period_k > 1 else ''}"
                                f"scope={'chunk' if sched.scope == 0 else 'stream'}"
                                f"{', cycle offsets aligned' if args.aligned and B > 1 else ''}",
                    "weights": "random N(0,0.02), fp32 accumulation", "kv_cache": "paged, 64 tokens/page",

@@ -63,6 +63,15 @@ typedef struct spark_config {
   int32_t max_batch;     /* sequences that may be open / stepped together */
   int32_t max_seq_len;   /* longest context (prompt + generated) of one sequence */
   int32_t kv_page_tokens;/* tokens per KV page, multiple of 16 */
+  /* The same periodic rule on text positions (Sec. V-C "Exploring Text Early Exit Policies",
+   * Table II row G10).  text_period_k <= 1: every text position runs full depth (the default of
+   * Sec. IV-B.1).  Otherwise the text position with index t -- inside its chunk (SCOPE_CHUNK) or
+   * among all text positions of the sequence (SCOPE_STREAM) -- runs full depth iff
+   * t mod text_period_k == text_phase and exits at layer e otherwise; early-exited text
+   * positions are completed by the next full-depth step like speech ones.  The pending rows of
+   * both modalities must fit: 2*period_k + 2*text_period_k <= 2*SPARK_MAX_PERIOD. */
+  int32_t text_period_k;
+  int32_t text_phase;    /* in [0, text_period_k) when text_period_k > 1 */
 } spark_config;
 
 /* Weights [device].  Matrices are row-major [out][in] in `dtype`; gains and lens_b are fp32.
@@ -90,7 +99,7 @@ typedef struct spark_weights {
 
 /* Exit-layer log of one sequence (Sec. V-A "Metrics", Eq. 4). */
 typedef struct spark_stats {
-  int64_t text_steps;        /* text positions decoded (always depth L) */
+  int64_t text_steps;        /* text positions decoded at depth L */
   int64_t speech_full_steps; /* speech positions decoded at depth L */
   int64_t speech_ee_steps;   /* speech positions decoded at depth e */
   int64_t flush_rows[2 * SPARK_MAX_PERIOD]; /* [m]: full-depth steps that pushed m rows through
@@ -98,6 +107,7 @@ typedef struct spark_stats {
   double mean_text_depth;    /* average exit layer over text positions (0 if none) */
   double mean_speech_depth;  /* average exit layer over speech positions (0 if none) */
   double speech_layer_saving;/* (1 - mean_speech_depth / L) * 100, Eq. 4 (0 if none) */
+  int64_t text_ee_steps;     /* text positions decoded at depth e (0 unless text_period_k > 1) */
 } spark_stats;
 
 typedef struct spark_ctx spark_ctx;

@@ -33,7 +33,7 @@ class SparkConfig(C.Structure):
                [("rope_base", C.c_float), ("rms_eps", C.c_float)] + \
                [(n, C.c_int32) for n in ("dtype", "exit_layer", "period_k", "phase", "scope",
                                          "n_text", "n_speech", "max_batch", "max_seq_len",
-                                         "kv_page_tokens")]
+                                         "kv_page_tokens", "text_period_k", "text_phase")]
 
 
 WEIGHT_FIELDS = ("embed", "attn_norm", "wq", "wk", "wv", "wo", "mlp_norm", "wg", "wu", "wd",
@@ -48,7 +48,7 @@ class SparkStats(C.Structure):
     _fields_ = [("text_steps", C.c_int64), ("speech_full_steps", C.c_int64),
                 ("speech_ee_steps", C.c_int64), ("flush_rows", C.c_int64 * (2 * SPARK_MAX_PERIOD)),
                 ("mean_text_depth", C.c_double), ("mean_speech_depth", C.c_double),
-                ("speech_layer_saving", C.c_double)]
+                ("speech_layer_saving", C.c_double), ("text_ee_steps", C.c_int64)]
 
 
 class SparkError(RuntimeError):
@@ -97,7 +97,8 @@ def make_config(shape, sched, max_batch: int, max_seq_len: int, kv_page_tokens: 
                        shape.n_kv_heads, shape.head_dim, shape.d_ffn, shape.vocab_text,
                        shape.vocab_speech, shape.rope_base, shape.rms_eps, shape.dtype,
                        sched.exit_layer, sched.period_k, sched.phase, sched.scope, sched.n_text,
-                       sched.n_speech, max_batch, max_seq_len, kv_page_tokens)
+                       sched.n_speech, max_batch, max_seq_len, kv_page_tokens,
+                       getattr(sched, "text_period_k", 0), getattr(sched, "text_phase", 0))
 
 
 def _iptr(a: np.ndarray):
@@ -222,7 +223,7 @@ class Spark:
         st = SparkStats()
         self._check(self.lib.spark_get_stats(self.handle, seq_id, C.byref(st)))
         return {"text": st.text_steps, "speech_full": st.speech_full_steps,
-                "speech_ee": st.speech_ee_steps,
+                "speech_ee": st.speech_ee_steps, "text_ee": st.text_ee_steps,
                 "flush_hist": {m: int(st.flush_rows[m]) for m in range(2 * SPARK_MAX_PERIOD)
                                if st.flush_rows[m]},
                 "mean_text_depth": st.mean_text_depth, "mean_speech_depth": st.mean_speech_depth,

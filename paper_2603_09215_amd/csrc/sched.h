@@ -18,20 +18,25 @@ enum { ERR_NAN = 1, ERR_INACTIVE = 2, ERR_BARRIER = 4 };
 struct SchedParams {
   int n_layers, exit_layer, period_k, phase, scope, n_text, n_speech;
   int rmax;  // hidden-state slots per sequence (pending rows + the current one)
+  int text_period_k, text_phase;  // the same rule on text positions (Sec. V-C, row G10); <= 1: text is full depth
 };
 
 // The schedule as an integer function of the sequence counters.  Generated token g falls on slot
 // (g + offset) mod (n_text + n_speech) of the interleave cycle; slots [0, n_text) are text.  A
 // speech position has index j inside its chunk (scope 0) or among all speech positions (scope 1);
-// it runs full depth iff j mod K == phase.  Text, e == L and K == 1 always run full depth.
+// it runs full depth iff j mod K == phase; e == L and K == 1 always run full depth.  Text runs
+// full depth unless a text period is given: then the text position with index t (its slot inside
+// the chunk, or the count of text positions emitted so far, g - j_stream) follows the same rule
+// with (text_period_k, text_phase).
 __host__ __device__ inline void schedule_decide(const SchedParams &sp, int g, int offset,
                                                 int j_stream, int &is_text, int &full) {
-  int cyc = sp.n_text + sp.n_speech;
-  int slot = (int)(((long long)g + offset) % cyc);
+  const int cyc = sp.n_text + sp.n_speech;
+  const int slot = (int)(((long long)g + offset) % cyc);
   is_text = slot < sp.n_text;
-  int j = sp.scope == 0 ? slot - sp.n_text : j_stream;
-  full = is_text || sp.exit_layer == sp.n_layers || sp.period_k == 1 ||
-         (j % sp.period_k == sp.phase);
+  const int period = is_text ? sp.text_period_k : sp.period_k;
+  const int want = is_text ? sp.text_phase : sp.phase;
+  const int idx = sp.scope == 0 ? (is_text ? slot : slot - sp.n_text) : (is_text ? g - j_stream : j_stream);
+  full = sp.exit_layer == sp.n_layers || period <= 1 || idx % period == want;
 }
 
 constexpr int SCHED_THREADS = 256;  // >= max_batch

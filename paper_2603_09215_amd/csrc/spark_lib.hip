@@ -44,7 +44,7 @@ struct Seq {
   bool open = false, prefilled = false;
   int cycle_offset = 0, len = 0, g = 0, j_stream = 0, n_pending = 0, last_full = 0;
   std::vector<int> pages;
-  int64_t text_steps = 0, speech_full = 0, speech_ee = 0;
+  int64_t text_steps = 0, speech_full = 0, speech_ee = 0, text_ee = 0;
   int64_t flush_rows[2 * SPARK_MAX_PERIOD] = {0};
 };
 
@@ -101,6 +101,18 @@ int fail(spark_ctx *c, int code, const char *fmt, ...) {
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// hidden-state slots per sequence: between two full-depth steps at most K-1 speech positions exit
+// early inside a chunk; a chunk's tail and the next chunk's head can join when nothing between them
+// runs full depth: 2K-1 rows with the current one.  A text period adds the same.
+int pending_slots(const spark_config *c) {
+  return 2 * c->period_k + (c->text_period_k > 1 ? 2 * c->text_period_k : 0);
+}
+
+SchedParams sched_params(const spark_config *c) {
+  return SchedParams{c->n_layers, c->exit_layer, c->period_k, c->phase, c->scope, c->n_text,
+                     c->n_speech, pending_slots(c), c->text_period_k, c->text_phase};
+}
+
 bool config_ok(const spark_config *c, char *why, size_t n) {
 #define BAD(cond, msg) if (cond) { snprintf(why, n, "%s", msg); return false; }
   BAD(c->size != sizeof(spark_config), "spark_config.size does not match this library");
@@ -124,9 +136,25 @@ bool config_ok(const spark_config *c, char *why, size_t n) {
   BAD(c->phase < 0 || c->phase >= c->period_k, "phase outside [0, period_k)");
   BAD(c->scope != SPARK_SCOPE_CHUNK && c->scope != SPARK_SCOPE_STREAM, "unknown scope");
   BAD(c->n_text < 0 || c->n_speech < 0 || c->n_text + c->n_speech < 1, "empty interleave cycle");
-  BAD(c->n_text == 0 && c->scope == SPARK_SCOPE_CHUNK && c->exit_layer < c->n_layers &&
-          c->period_k > 1 && c->phase >= c->n_speech,
-      "a pure-speech cycle without a full-depth slot would never complete its KV");
+  BAD(c->text_period_k < 0 || c->text_period_k > SPARK_MAX_PERIOD, "text_period_k outside [0, 16]");
+  BAD(c->text_period_k > 1 && (c->text_phase < 0 || c->text_phase >= c->text_period_k),
+      "text_phase outside [0, text_period_k)");
+  BAD(pending_slots(c) > 2 * SPARK_MAX_PERIOD, "period_k + text_period_k > 16: too many pending rows");
+  if (c->scope == SPARK_SCOPE_CHUNK && c->exit_layer < c->n_layers) {
+    // the pattern repeats with the cycle: it needs a full-depth slot, and its longest run of early
+    // exits (which may wrap around the cycle and cross modalities) must fit the pending slots
+    const SchedParams sp = sched_params(c);
+    const int cyc = c->n_text + c->n_speech;
+    int run = 0, longest = 0;
+    bool any_full = false;
+    for (int g = 0; g < 2 * cyc; ++g) {
+      int is_text, full;
+      schedule_decide(sp, g, 0, 0, is_text, full);
+      if (full) { any_full = true; run = 0; } else { longest = std::max(longest, ++run); }
+    }
+    BAD(!any_full, "a cycle without a full-depth slot would never complete its KV");
+    BAD(longest + 1 > pending_slots(c), "a run of early exits is longer than the pending slots");
+  }
   BAD(c->max_batch < 1 || c->max_batch > SCHED_THREADS, "max_batch outside [1, 256]");
   BAD(c->max_seq_len < 1 || c->max_seq_len > MAX_SEQ_LEN, "max_seq_len outside [1, 16384]");
   BAD(c->kv_page_tokens < 16 || c->kv_page_tokens % 16, "kv_page_tokens must be a multiple of 16");
@@ -136,7 +164,7 @@ bool config_ok(const spark_config *c, char *why, size_t n) {
 
 void derive(const spark_config &c, Derived &d) {
   d.V = c.vocab_text + c.vocab_speech;
-  d.rmax = 2 * c.period_k;
+  d.rmax = pending_slots(&c);
   d.max_rows = std::max(c.max_batch * d.rmax, PREFILL_CHUNK);
   d.max_pages = (c.max_seq_len + c.kv_page_tokens - 1) / c.kv_page_tokens;
   d.n_pages_total = d.max_pages * c.max_batch;
@@ -777,6 +805,8 @@ int decode_chunk(spark_ctx *c, int steps, int n, const int32_t *seq_ids, const i
       if (want_rows[k]) {
         s.flush_rows[want_rows[k]] += 1;
         if (want_text[k]) s.text_steps += 1; else s.speech_full += 1;
+      } else if (want_text[k]) {
+        s.text_ee += 1;
       } else {
         s.speech_ee += 1;
       }
@@ -864,8 +894,7 @@ int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_p
   c->stream = (hipStream_t)hip_stream;
   c->scratch = (char *)scratch;
   c->kv_pool = kv_pool;
-  c->sp = SchedParams{cfg->n_layers, cfg->exit_layer, cfg->period_k, cfg->phase, cfg->scope,
-                      cfg->n_text, cfg->n_speech, c->dv.rmax};
+  c->sp = sched_params(cfg);
   c->seqs.resize(cfg->max_batch);
   for (int p = c->dv.n_pages_total - 1; p >= 0; --p) c->free_pages.push_back(p);
   c->h_in = c->h_out = nullptr;
@@ -1059,7 +1088,9 @@ int spark_get_stats(spark_ctx *c, int32_t seq_id, spark_stats *out) {
   out->speech_ee_steps = s->speech_ee;
   memcpy(out->flush_rows, s->flush_rows, sizeof(out->flush_rows));
   const double L = c->cfg.n_layers, e = c->cfg.exit_layer;
-  if (s->text_steps) out->mean_text_depth = L;
+  out->text_ee_steps = s->text_ee;
+  if (s->text_steps + s->text_ee)
+    out->mean_text_depth = (s->text_steps * L + s->text_ee * e) / (double)(s->text_steps + s->text_ee);
   const int64_t ns = s->speech_full + s->speech_ee;
   if (ns) {
     out->mean_speech_depth = (s->speech_full * L + s->speech_ee * e) / (double)ns;

@@ -84,6 +84,7 @@ def compare_run(spark, shape, sched, weights, prompts, offsets, n_steps, forced_
     for b in range(B):
         gs, os_ = spark.get_stats(sids[b]), oseqs[b].stats()
         assert gs["text"] == os_["text"] and gs["speech_full"] == os_["speech_full"]
+        assert gs["text_ee"] == os_["text_ee"]
         assert gs["speech_ee"] == os_["speech_ee"] and gs["flush_hist"] == os_["flush_hist"]
         stats.append(gs)
         spark.seq_close(sids[b])

@@ -61,6 +61,13 @@ SCHEDULES = [
     dict(exit_layer=4),                                                               # e = L
     dict(period_k=1, phase=0),                                                        # K = 1
     dict(period_k=8, phase=7, n_text=3, n_speech=9, scope=wl.SCOPE_STREAM, exit_layer=1),
+    # the periodic rule on text positions (Sec. V-C, row G10: text Even, speech at full depth)
+    dict(text_period_k=2, text_phase=0, period_k=1, phase=0, n_text=3, n_speech=2),
+    # both modalities scheduled: early-exit runs cross the modality boundary (up to 5 pending rows,
+    # so flushes of 5 and 6 rows take the MFMA-path row count on bf16 models, the vector tiles here)
+    dict(text_period_k=3, text_phase=0, period_k=4, phase=3, n_text=3, n_speech=4),
+    dict(text_period_k=3, text_phase=0, period_k=2, phase=1, n_text=2, n_speech=3,
+         scope=wl.SCOPE_STREAM),
 ]
 
 
@@ -73,8 +80,10 @@ def test_schedules_and_degenerate_cases(sb, tiny_weights, over):
     prompt = wl.make_prompt(w.shape, 9, seed=5)
     res = compare_run(sp, w.shape, sched, tiny_weights, [prompt], [2], 36, check_kv_every=3,
                       label=str(over))
-    if sched.exit_layer == w.shape.n_layers or sched.period_k == 1:
+    if sched.exit_layer == w.shape.n_layers or (sched.period_k == 1 and sched.text_period_k <= 1):
         assert np.all(res["depths"] == w.shape.n_layers)
+    if sched.text_period_k > 1:
+        assert res["stats"][0]["text_ee"] > 0
     sp.close()
 
 
@@ -229,6 +238,26 @@ def test_persistent_layer_pass_kernel(sb, tiny_weights, monkeypatch):
     sp = sb.Spark(shape, sched, weights, max_batch=1, max_seq_len=400, kv_page_tokens=32)
     compare_run(sp, shape, sched, weights, [wl.make_prompt(shape, 300, seed=5)], [1], 24,
                 check_kv_every=4, label="pass bf16-gqa7")
+    sp.close()
+
+
+def test_text_schedule_with_long_flushes_on_a_bf16_model(sb):
+    """text and speech both scheduled (Sec. V-C): runs of early exits cross the modality boundary,
+    so one sequence completes up to six rows in a full-depth step; on a bf16 model five or more
+    rows go through the MFMA kernels, fewer through the vector kernel"""
+    shape = wl.TINY.shape.replace(name="bf16-textsched", dtype=wl.DTYPE_BF16, n_layers=4, d_model=512,
+                                  n_q_heads=8, n_kv_heads=4, head_dim=64, d_ffn=1536 + 72,
+                                  vocab_text=1500, vocab_speech=701)
+    # text: full, early, early; speech: early, early, early, full -> five pending rows + the current
+    sched = wl.TINY.schedule.replace(text_period_k=3, text_phase=0, period_k=4, phase=3, n_text=3,
+                                     n_speech=4)
+    say("case text schedule bf16")
+    weights = wl.make_weights(shape, seed=8, gain_std=0.1)
+    sp = sb.Spark(shape, sched, weights, max_batch=1, max_seq_len=128, kv_page_tokens=16)
+    res = compare_run(sp, shape, sched, weights, [wl.make_prompt(shape, 21, seed=9)], [0], 42,
+                      check_kv_every=5, label="text schedule bf16")
+    hist = res["stats"][0]["flush_hist"]
+    assert max(hist) >= 5 and res["stats"][0]["text_ee"] > 0
     sp.close()
 
 
