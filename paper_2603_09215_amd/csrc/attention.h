@@ -47,7 +47,7 @@ __device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int 
                                           int split, const float *__restrict__ qbuf, const KVView &kv,
                                           int layer, int nq, int n_splits, float scale,
                                           float *__restrict__ part, int *__restrict__ cnt,
-                                          float *__restrict__ out, float *lds) {
+                                          float *__restrict__ out, const SplitOut &so, float *lds) {
   constexpr int VEC = Elem<KT>::VEC;
   constexpr int LPT = HD / VEC;                   // lanes per token
   constexpr int TPI = NT / LPT;                   // tokens per iteration of the workgroup
@@ -215,6 +215,9 @@ __device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int 
     float *dst = out + (size_t)r * nq * HD + (hq0 + g) * HD + c;
     store2_maybe_ds<DS>(dst, make_float2(acc4.x * inv, acc4.y * inv));
     store2_maybe_ds<DS>(dst + 2, make_float2(acc4.z * inv, acc4.w * inv));
+    // for the MFMA output projection: the same values as three bf16 parts
+    if (so.xs)
+      split_store4(so, r, (hq0 + g) * HD + c, make_float4(acc4.x * inv, acc4.y * inv, acc4.z * inv, acc4.w * inv));
   }
   if (DS) wait_memory_ops();   // the caller's next barrier arrival does not wait for these stores
 }
@@ -226,7 +229,7 @@ template <typename KT, int HD, int G>
 __global__ void __launch_bounds__(ATTN_THREADS)
 attn_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbuf, KVView kv,
             int layer, int nq, int group, int n_splits, float scale, float *__restrict__ part,
-            int *__restrict__ arrivals, float *__restrict__ out) {
+            int *__restrict__ arrivals, float *__restrict__ out, SplitOut so) {
   __shared__ float lds[attn_lds_floats<HD, G, ATTN_THREADS>()];
   const int n_groups = (group + G - 1) / G;
   const int split = blockIdx.x, hk = blockIdx.y / n_groups, gi = blockIdx.y - hk * n_groups, r = blockIdx.z;
@@ -234,7 +237,7 @@ attn_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbuf, KV
   if (split * ATTN_SLICE > rd.pos) return;        // slice beyond the row's context
   attn_task<KT, HD, G, ATTN_THREADS, false>(rd, r, hk, hk * group + gi * G, min(G, group - gi * G), split,
                                             qbuf, kv, layer, nq, n_splits, scale, part,
-                                            arrivals + r * gridDim.y + blockIdx.y, out, lds);
+                                            arrivals + r * gridDim.y + blockIdx.y, out, so, lds);
 }
 
 }  // namespace spark

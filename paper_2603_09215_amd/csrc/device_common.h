@@ -66,6 +66,55 @@ template <> struct Elem<bf16_t> {
   }
 };
 
+// x = hi + mid + lo exactly, each part a bf16 (3 x 8 mantissa bits cover the 24 of an fp32): the
+// form in which activations meet bf16 weights on the MFMA units without losing fp32 accuracy
+__device__ __forceinline__ void split3_bf16(float x, bf16_t &hi, bf16_t &mid, bf16_t &lo) {
+  hi = f32_to_bf16(x);
+  const float rem = x - bf16_to_f32(hi);      // exact
+  mid = f32_to_bf16(rem);
+  lo = f32_to_bf16(rem - bf16_to_f32(mid));   // the exact remainder has at most 8 bits left
+}
+
+// Where the three parts of pass row r's activations go for the MFMA kernels: part p of element k at
+// xs[p * part_stride + r * row_stride + k]; rows are zero beyond the `width` real elements.
+struct SplitOut {
+  bf16_t *xs;            // nullptr: not wanted
+  size_t part_stride;
+  int row_stride, width;
+};
+
+// four consecutive elements k..k+3 (k a multiple of 4) of row r; the thread that writes the row's
+// last elements also clears its padding
+__device__ __forceinline__ void split_store4(const SplitOut &so, int r, int k, float4 v) {
+  const float f[4] = {v.x, v.y, v.z, v.w};
+  bf16_t h[4], m[4], l[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) split3_bf16(f[e], h[e], m[e], l[e]);
+  bf16_t *dst = so.xs + (size_t)r * so.row_stride + k;
+  *(uint2 *)dst = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
+  *(uint2 *)(dst + so.part_stride) = make_uint2(m[0] | ((uint32_t)m[1] << 16), m[2] | ((uint32_t)m[3] << 16));
+  *(uint2 *)(dst + 2 * so.part_stride) = make_uint2(l[0] | ((uint32_t)l[1] << 16), l[2] | ((uint32_t)l[3] << 16));
+  if (k + 4 >= so.width)
+    for (int z = so.width; z < so.row_stride; z += 4)
+#pragma unroll
+      for (int p = 0; p < 3; ++p)
+        *(uint2 *)(so.xs + p * so.part_stride + (size_t)r * so.row_stride + z) = make_uint2(0, 0);
+}
+
+// one element
+__device__ __forceinline__ void split_store1(const SplitOut &so, int r, int k, float v) {
+  bf16_t h, m, l;
+  split3_bf16(v, h, m, l);
+  bf16_t *dst = so.xs + (size_t)r * so.row_stride + k;
+  dst[0] = h;
+  dst[so.part_stride] = m;
+  dst[2 * so.part_stride] = l;
+  if (k + 1 >= so.width)
+    for (int z = so.width; z < so.row_stride; ++z)
+#pragma unroll
+      for (int p = 0; p < 3; ++p) so.xs[p * so.part_stride + (size_t)r * so.row_stride + z] = 0;
+}
+
 // Data handed from one workgroup to another inside a kernel goes through device-scope relaxed
 // atomic accesses: they are served at the level where all XCDs agree, so neither side has to
 // flush or invalidate a whole L2 (each of the 8 XCDs has its own).

@@ -277,6 +277,24 @@ template <typename WT, bool DS = false> struct EpiSwiGLU {
   __device__ void end(int, const RowDesc &, State &) const {}
 };
 
+// the same, written as the three bf16 parts the down projection's MFMA kernel reads (no fp32 copy)
+template <typename WT> struct EpiSwiGLUSplit {
+  typedef NoState State;
+  const WT *wg, *wu;
+  int d, F;
+  SplitOut so;
+  __device__ void init(State &) const {}
+  __device__ void weight_rows(int task, const WT *&r0, const WT *&r1) const {
+    r0 = wg + (size_t)task * d;
+    r1 = wu + (size_t)task * d;
+  }
+  __device__ void finish(int task, int r, const RowDesc &, float y0, float y1, State &) const {
+    float s = y0 / (1.0f + expf(-y0));
+    split_store1(so, r, task, s * y1);
+  }
+  __device__ void end(int, const RowDesc &, State &) const {}
+};
+
 // u[r][i] = h[i] + (A h)[i] + b[i]   (translator of the layer-specific head)
 template <typename WT> struct EpiLensAffine {
   typedef NoState State;

@@ -82,12 +82,7 @@ prep_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ src, int
     const float f[4] = {v.x, v.y, v.z, v.w};
     bf16_t h[4], mid[4], l[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      h[e] = f32_to_bf16(f[e]);
-      const float rem = f[e] - bf16_to_f32(h[e]);      // exact
-      mid[e] = f32_to_bf16(rem);
-      l[e] = f32_to_bf16(rem - bf16_to_f32(mid[e]));   // exact remainder has at most 8 bits left
-    }
+    for (int e = 0; e < 4; ++e) split3_bf16(f[e], h[e], mid[e], l[e]);
     bf16_t *dst = xs + (size_t)r * n_pad + k;
     *(uint2 *)dst = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
     *(uint2 *)(dst + part_stride) = make_uint2(mid[0] | ((uint32_t)mid[1] << 16), mid[2] | ((uint32_t)mid[3] << 16));

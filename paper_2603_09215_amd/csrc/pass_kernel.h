@@ -467,7 +467,7 @@ spark_pass_k(PassParams<WT> p) {
           __syncthreads();  // LDS of the previous task is free
           attn_task<WT, HD, G, PASS_THREADS, true>(mine, r, hk, hk * G, G, split, p.qbuf, p.kv, l,
                                                    p.nq, p.n_splits, p.scale, p.part,
-                                                   p.arrivals + r * p.nkv + hk, p.attn_out, lds);
+                                                   p.arrivals + r * p.nkv + hk, p.attn_out, SplitOut{nullptr, 0, 0, 0}, lds);
         }
       }
     }

@@ -31,7 +31,7 @@ constexpr int MAX_SEQ_LEN = 16384;
 
 struct Layout {  // byte offsets into the scratch buffer
   size_t state, page_table, plan, lower, upper, ee, full, prefill_rows, prefill_tokens, seq_ids,
-      forced, step_flags, out_tokens, out_depth, best, arrivals, barrier, hidden, xsplit, mfma_part, qbuf, attn_out, part, act, lens_u,
+      forced, step_flags, out_tokens, out_depth, best, arrivals, barrier, hidden, xsplit, xsplit2, mfma_part, qbuf, attn_out, part, act, lens_u,
       logits, rope, inv_freq, total;
 };
 
@@ -206,6 +206,8 @@ void layout(const spark_config &c, const Derived &d, Layout &l) {
   {
     const size_t widest = align_up(std::max((size_t)c.d_ffn, std::max((size_t)c.d_model, qw)), 64);
     l.xsplit = take(sizeof(bf16_t) * 3 * (size_t)d.max_rows * widest);
+    // a second one for the MLP activations: the gate/up kernel writes them while it still reads its input
+    l.xsplit2 = take(c.dtype == SPARK_DTYPE_BF16 ? sizeof(bf16_t) * 3 * (size_t)d.max_rows * widest : 256);
     l.mfma_part = take(c.dtype == SPARK_DTYPE_BF16 ? MFMA_PARTIAL_BYTES : 256);
   }
   l.logits = take(sizeof(float) * (size_t)c.max_batch * d.V);
@@ -294,6 +296,14 @@ int launch_gemv(spark_ctx *c, const Pro &pro, const Epi &epi, const RowDesc *row
   return prof_end(c, kclass);
 }
 
+size_t xsplit_stride(spark_ctx *c);
+
+// a split-activation buffer seen as rows of `width` elements (padded to the MFMA chunk)
+SplitOut split_target(spark_ctx *c, int width, bool second = false) {
+  return SplitOut{at<bf16_t>(c, second ? c->lo.xsplit2 : c->lo.xsplit), xsplit_stride(c),
+                  (int)align_up(width, MG_KC), width};
+}
+
 KVView kv_view(spark_ctx *c) {
   KVView v;
   v.pool = c->kv_pool;
@@ -310,7 +320,7 @@ constexpr int ATTN_SPLIT_HEADS_MAX_ROWS = 4;
 
 // GT query heads per workgroup
 template <typename WT, int HD, int GT>
-void launch_attention_g(spark_ctx *c, const RowDesc *rows, int m, int layer) {
+void launch_attention_g(spark_ctx *c, const RowDesc *rows, int m, int layer, const SplitOut &so) {
   const spark_config &g = c->cfg;
   const Derived &d = c->dv;
   float *part = at<float>(c, c->lo.part);
@@ -318,31 +328,34 @@ void launch_attention_g(spark_ctx *c, const RowDesc *rows, int m, int layer) {
   const int splits = c->attn_splits_now > 0 ? std::min(d.n_splits, c->attn_splits_now) : d.n_splits;
   attn_rows_k<WT, HD, GT><<<dim3(splits, g.n_kv_heads * n_groups, m), ATTN_THREADS, 0, c->stream>>>(
       rows, at<float>(c, c->lo.qbuf), kv_view(c), layer, g.n_q_heads, d.group, d.n_splits,
-      1.0f / sqrtf((float)HD), part, at<int>(c, c->lo.arrivals), at<float>(c, c->lo.attn_out));
+      1.0f / sqrtf((float)HD), part, at<int>(c, c->lo.arrivals), at<float>(c, c->lo.attn_out), so);
 }
 
 template <typename WT, int HD>
-void launch_attention_hd(spark_ctx *c, const RowDesc *rows, int m, int layer) {
+void launch_attention_hd(spark_ctx *c, const RowDesc *rows, int m, int layer, const SplitOut &so) {
   // a handful of rows: four query heads per workgroup, so that even two KV heads make enough
   // workgroups; many rows: all heads of a KV head together, K and V are read once
   const int group = c->dv.group;
   const int gt = (m <= ATTN_SPLIT_HEADS_MAX_ROWS && group > 2) ? 2 : group;
   switch (gt) {
-    case 1: launch_attention_g<WT, HD, 1>(c, rows, m, layer); break;
-    case 2: launch_attention_g<WT, HD, 2>(c, rows, m, layer); break;
-    case 3: launch_attention_g<WT, HD, 4>(c, rows, m, layer); break;
-    case 4: launch_attention_g<WT, HD, 4>(c, rows, m, layer); break;
-    case 5: case 6: case 7: launch_attention_g<WT, HD, 7>(c, rows, m, layer); break;
-    case 8: launch_attention_g<WT, HD, 8>(c, rows, m, layer); break;
-    default: launch_attention_g<WT, HD, 16>(c, rows, m, layer); break;
+    case 1: launch_attention_g<WT, HD, 1>(c, rows, m, layer, so); break;
+    case 2: launch_attention_g<WT, HD, 2>(c, rows, m, layer, so); break;
+    case 3: launch_attention_g<WT, HD, 4>(c, rows, m, layer, so); break;
+    case 4: launch_attention_g<WT, HD, 4>(c, rows, m, layer, so); break;
+    case 5: case 6: case 7: launch_attention_g<WT, HD, 7>(c, rows, m, layer, so); break;
+    case 8: launch_attention_g<WT, HD, 8>(c, rows, m, layer, so); break;
+    default: launch_attention_g<WT, HD, 16>(c, rows, m, layer, so); break;
   }
 }
 
-template <typename WT> int launch_attention(spark_ctx *c, const RowDesc *rows, int m, int layer) {
+// split_out: also leave the output as the three bf16 parts the MFMA output projection reads
+template <typename WT> int launch_attention(spark_ctx *c, const RowDesc *rows, int m, int layer, bool split_out) {
   int rc = prof_begin(c, SPARK_KC_ATTN);
   if (rc) return rc;
-  if (c->cfg.head_dim == 128) launch_attention_hd<WT, 128>(c, rows, m, layer);
-  else launch_attention_hd<WT, 64>(c, rows, m, layer);
+  const int qw = c->cfg.n_q_heads * c->cfg.head_dim;
+  const SplitOut so = split_out ? split_target(c, qw) : SplitOut{nullptr, 0, 0, 0};
+  if (c->cfg.head_dim == 128) launch_attention_hd<WT, 128>(c, rows, m, layer, so);
+  else launch_attention_hd<WT, 64>(c, rows, m, layer, so);
   HIP_TRY(c, hipGetLastError());
   return prof_end(c, SPARK_KC_ATTN);
 }
@@ -468,7 +481,7 @@ int mfma_occupancy(spark_ctx *c) {
 
 template <int MTILES, typename Epi>
 int launch_mfma_tiles(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, int n_in, int n_tasks,
-                      bool may_split) {
+                      bool may_split, bool second_input = false) {
   if (n_in % 8) return fail(c, SPARK_EINVAL, "MFMA path needs an input width that is a multiple of 8, not %d", n_in);
   const int mrows = 32 * MTILES;
   const int z = (m + mrows - 1) / mrows;
@@ -494,7 +507,7 @@ int launch_mfma_tiles(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, 
   }
   const int cps = (n_chunks + split - 1) / split;
   split = (n_chunks + cps - 1) / cps;
-  const bf16_t *xs = at<bf16_t>(c, c->lo.xsplit);
+  const bf16_t *xs = at<bf16_t>(c, second_input ? c->lo.xsplit2 : c->lo.xsplit);
   const size_t xst = xsplit_stride(c);
   float *part = at<float>(c, c->lo.mfma_part);
   dim3 grid(bx, split, z);
@@ -517,16 +530,16 @@ int launch_mfma_tiles(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, 
 // y = W x for m rows whose hi/lo split sits in the xhi/xlo buffers
 template <typename Epi>
 int launch_mfma(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, int n_in, int n_tasks,
-                bool may_split, int kclass) {
+                bool may_split, int kclass, bool second_input = false) {
   int rc = prof_begin(c, kclass);
   if (rc) return rc;
-  if (m <= 32) rc = launch_mfma_tiles<1>(c, epi, rows, m, n_in, n_tasks, may_split);
-  else rc = launch_mfma_tiles<2>(c, epi, rows, m, n_in, n_tasks, may_split);   // tiles of 64 rows
+  if (m <= 32) rc = launch_mfma_tiles<1>(c, epi, rows, m, n_in, n_tasks, may_split, second_input);
+  else rc = launch_mfma_tiles<2>(c, epi, rows, m, n_in, n_tasks, may_split, second_input);   // tiles of 64 rows
   if (rc) return rc;
   return prof_end(c, kclass);
 }
 
-template <typename WT> int launch_attention(spark_ctx *c, const RowDesc *rows, int m, int layer);
+template <typename WT> int launch_attention(spark_ctx *c, const RowDesc *rows, int m, int layer, bool split_out);
 
 // layers [l0, l1) on m >= 16 rows, bf16 weights
 int run_layers_mfma(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
@@ -548,20 +561,19 @@ int run_layers_mfma(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
     eq.kv = kv_view(c);
     if ((rc = launch_mfma(c, eq, rows, m, d, (nq + 2 * nkv) * (hd / 2), true, SPARK_KC_QKV))) return rc;
 
-    if ((rc = launch_attention<WT>(c, rows, m, l))) return rc;
+    // attention leaves its output split for the MFMA kernel; so does the SwiGLU epilogue below
+    if ((rc = launch_attention<WT>(c, rows, m, l, true))) return rc;
 
-    if ((rc = launch_prep(c, rows, m, at<float>(c, c->lo.attn_out), (int)qw, 0, nullptr, (int)qw))) return rc;
     EpiResidual<WT> eo{(const WT *)c->w.wo + (size_t)l * d * qw, (int)qw, d, hidden, d};
     if ((rc = launch_mfma(c, eo, rows, m, (int)qw, d / 2, true, SPARK_KC_OPROJ))) return rc;
 
     if ((rc = launch_prep(c, rows, m, hidden, d, 1, c->w.mlp_norm + (size_t)l * d, d))) return rc;
-    EpiSwiGLU<WT> eg{(const WT *)c->w.wg + (size_t)l * F * d, (const WT *)c->w.wu + (size_t)l * F * d,
-                     d, F, at<float>(c, c->lo.act)};
+    EpiSwiGLUSplit<WT> eg{(const WT *)c->w.wg + (size_t)l * F * d, (const WT *)c->w.wu + (size_t)l * F * d,
+                          d, F, split_target(c, F, true)};
     if ((rc = launch_mfma(c, eg, rows, m, d, F, true, SPARK_KC_GATEUP))) return rc;
 
-    if ((rc = launch_prep(c, rows, m, at<float>(c, c->lo.act), F, 0, nullptr, F))) return rc;
     EpiResidual<WT> ed{(const WT *)c->w.wd + (size_t)l * d * F, F, d, hidden, d};
-    if ((rc = launch_mfma(c, ed, rows, m, F, d / 2, true, SPARK_KC_DOWN))) return rc;
+    if ((rc = launch_mfma(c, ed, rows, m, F, d / 2, true, SPARK_KC_DOWN, true))) return rc;
   }
   return SPARK_OK;
 }
@@ -593,7 +605,7 @@ int run_layers(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m, bool on
     eq.kv = kv_view(c);
     if ((rc = launch_gemv<WT>(c, n1, eq, rows, m, d, (nq + 2 * nkv) * (hd / 2), SPARK_KC_QKV))) return rc;
 
-    if ((rc = launch_attention<WT>(c, rows, m, l))) return rc;
+    if ((rc = launch_attention<WT>(c, rows, m, l, false))) return rc;
 
     ProPlain pa{at<float>(c, c->lo.attn_out), (int)qw, 0};
     EpiResidual<WT> eo{(const WT *)c->w.wo + (size_t)l * d * qw, (int)qw, d, hidden, d};
