@@ -497,7 +497,9 @@ int launch_mfma_tiles(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, 
   if (may_split) {
     const int slots = occ * c->n_cu, tiles = bx * z;
     const size_t per_split = sizeof(float) * (size_t)n_tasks * 2 * m_pad;
-    const int max_split = (int)std::min<size_t>(std::max(1, n_chunks / 8), std::max<size_t>(1, MFMA_PARTIAL_BYTES / per_split));
+    // (few tiles: shorter k ranges are worth the pipeline fill they cost)
+    const int min_chunks = tiles < 32 ? 4 : 8;
+    const int max_split = (int)std::min<size_t>(std::max(1, n_chunks / min_chunks), std::max<size_t>(1, MFMA_PARTIAL_BYTES / per_split));
     double best = 0.0;
     for (int s = 1; s <= std::min(max_split, 32); ++s) {
       const int blocks = tiles * s, rounds = (blocks + slots - 1) / slots;
