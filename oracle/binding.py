@@ -60,6 +60,8 @@ def load(kind: str = "f32") -> C.CDLL:
         getattr(lib, f).argtypes = [P]
     lib.ora_seq_stats.argtypes = [P, P]
     lib.ora_pend_cap.argtypes = [C.POINTER(OraConfig)]
+    lib.ora_sample.argtypes = [P, C.c_int, C.c_double, C.c_double, C.c_uint64, C.POINTER(C.c_int32),
+                               C.POINTER(C.c_double)]
     lib.ora_get_kv.argtypes = [P, I, I, P, P]
     lib.ora_lens_logits.argtypes = [P, P, P]
     lib.ora_prim_matvec.argtypes = [P, I, I, I, P, P]
@@ -90,6 +92,15 @@ def make_config(shape, sched, max_seq_len: int, kv_round_bf16: bool = False) -> 
                      shape.rope_base, shape.rms_eps, shape.dtype, sched.exit_layer,
                      sched.period_k, sched.phase, sched.scope, sched.n_text, sched.n_speech,
                      max_seq_len, int(kv_round_bf16), sched.text_period_k, sched.text_phase)
+
+
+def sample(logits, temperature: float, top_p: float, omega: int, kind: str = "f32"):
+    """(token, nucleus size, gap) of the oracle's nucleus sampler for one vector of logits"""
+    lib = load(kind)
+    lg = np.ascontiguousarray(logits, dtype=np.float64)
+    n, gap = C.c_int32(0), C.c_double(0.0)
+    tok = lib.ora_sample(_ptr(lg), len(lg), temperature, top_p, C.c_uint64(omega), C.byref(n), C.byref(gap))
+    return tok, n.value, gap.value
 
 
 def schedule_run(shape, sched, n_steps: int, cycle_offset: int = 0, kind: str = "f32"):

@@ -194,6 +194,75 @@ static int argmax_lowest(const real *x, int n) {
   return best;
 }
 
+/* ------------------------------------------------------------------ nucleus sampling */
+
+/* Temperature / nucleus (top-p) sampling from a vector of logits (Sec. V-A "Models": Step-Audio-2
+ * decodes with temperature 0.7 and top_p 0.9).  The paper fixes neither tie handling nor how the
+ * random draw is mapped to a token; the definition used here makes both exact:
+ *   w_i = exp((l_i - max l) / T);  q_i = floor(w_i * 2^32 + 1/2), at most 2^32 - 1  (integer masses)
+ *   order: larger q first, lower index first among equal q
+ *   nucleus: the shortest prefix of that order whose mass reaches ceil(top_p * sum q); M = its mass
+ *   x = floor(omega * M / 2^64) for the 64-bit random word omega of the step
+ *   token: the element of the prefix at which the running mass first exceeds x.
+ * Returns the token (-1 on a NaN logit or bad parameters).  nucleus_out: size of the nucleus;
+ * gap_out: how far, as a fraction of the total mass, the two decisions are from going the other
+ * way -- the smaller of (a) the distance of x to the edges of the chosen element's interval and
+ * (b) the distance of the nucleus' mass before and after its last element to the threshold. */
+typedef struct { uint64_t q; int32_t idx; } ora_mass;
+static int mass_order(const void *a, const void *b) {
+  const ora_mass *x = a, *y = b;
+  if (x->q != y->q) return x->q > y->q ? -1 : 1;
+  return x->idx < y->idx ? -1 : (x->idx > y->idx);
+}
+int ora_sample(const double *logits, int V, double temperature, double top_p, uint64_t omega,
+               int32_t *nucleus_out, double *gap_out) {
+  if (V < 1 || !(temperature > 0.0) || !(top_p > 0.0) || top_p > 1.0) return -1;
+  double mx = logits[0];
+  for (int i = 0; i < V; ++i) {
+    if (logits[i] != logits[i]) return -1;
+    if (logits[i] > mx) mx = logits[i];
+  }
+  ora_mass *e = malloc((size_t)V * sizeof(*e));
+  if (!e) return -1;
+  uint64_t total = 0;
+  for (int i = 0; i < V; ++i) {
+    double w = exp((logits[i] - mx) / temperature);
+    double scaled = floor(w * 4294967296.0 + 0.5);
+    e[i].q = scaled >= 4294967295.0 ? 4294967295ull : (uint64_t)scaled;
+    e[i].idx = i;
+    total += e[i].q;
+  }
+  qsort(e, (size_t)V, sizeof(*e), mass_order);
+  uint64_t target = (uint64_t)ceil(top_p * (double)total);
+  if (target < 1) target = 1;
+  if (target > total) target = total;
+  uint64_t run = 0;
+  int cut = 0;
+  for (int i = 0; i < V; ++i) {
+    run += e[i].q;
+    if (run >= target) { cut = i; break; }
+  }
+  const uint64_t M = run;
+  const uint64_t x = (uint64_t)(((__uint128_t)omega * M) >> 64);
+  /* (with the whole vocabulary in the nucleus there is no cut that could move) */
+  double gap = target == total ? 1.0
+                               : fmin((double)(M - target), (double)(target - (M - e[cut].q))) / (double)total;
+  run = 0;
+  int tok = e[cut].idx;
+  for (int i = 0; i <= cut; ++i) {
+    if (run + e[i].q > x) {
+      tok = e[i].idx;
+      gap = fmin(gap, fmin((double)(x - run), (double)(run + e[i].q - 1 - x)) / (double)total);
+      break;
+    }
+    run += e[i].q;
+  }
+  if (nucleus_out) *nucleus_out = cut + 1;
+  if (gap_out) *gap_out = gap;
+  free(e);
+  return tok;
+}
+
 /* ------------------------------------------------------------------ model pieces */
 
 static size_t lofs(const ora_model *m, int l, size_t rows, size_t cols) {
