@@ -72,6 +72,9 @@ def main() -> int:
                     help="apply the periodic rule to text positions too, with this period and phase 0")
     ap.add_argument("--aligned", action="store_true",
                     help="batch > 1: every sequence starts at cycle offset 0 (phase-aligned schedules)")
+    ap.add_argument("--temperature", type=float, default=0.0,
+                    help="> 0: draw tokens by temperature / nucleus sampling instead of the arg-max")
+    ap.add_argument("--top-p", type=float, default=0.9)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (no collectives, no "
@@ -95,7 +98,7 @@ def main() -> int:
     prompt_len = args.prompt_len or w.prompt_len
     K, W = args.steps, args.warmup
     device = torch.device("cuda:0")
-    max_seq = prompt_len + W + K + args.profile_steps + 64
+    max_seq = prompt_len + W + K + 4 * args.profile_steps + 64
     max_seq = min(16384, (max_seq + 63) // 64 * 64)
 
     t0 = time.time()
@@ -106,7 +109,7 @@ def main() -> int:
     B = args.batch
     if B > 1:
         plens = [int(x) for x in wl.make_prompt_lengths(B, 256, 2048, seed=3)]
-        max_seq = min(16384, (max(plens) + W + K + args.profile_steps + 64 + 63) // 64 * 64)
+        max_seq = min(16384, (max(plens) + W + K + 4 * args.profile_steps + 64 + 63) // 64 * 64)
     else:
         plens = [prompt_len]
     sp = Spark(shape, sched, dev_w, max_batch=B, max_seq_len=max_seq, kv_page_tokens=64, device="cuda:0")
@@ -137,10 +140,17 @@ def main() -> int:
                "frac_of_mfma_bf16_peak": round(pre_flops / prefill_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
 
     # ---- warm-up, then the timed region: exactly K steps, tokens fed back on the device
-    sp.decode(W, sids)
+    sampled = args.temperature > 0
+    if sampled:   # one 64-bit random word per step and sequence, drawn ahead of the timed region
+        sp.set_sampling(args.temperature, args.top_p)
+        words = np.random.Generator(np.random.Philox(7)).integers(0, 2 ** 64, size=(K + W, B), dtype=np.uint64)
+        decode = lambda n, first: sp.decode_sampled(n, sids, words[first:first + n])
+    else:
+        decode = lambda n, first: sp.decode(n, sids)
+    decode(W, 0)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    tok, dep = sp.decode(K, sids)
+    tok, dep = decode(K, W)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t1
     ms_per_step = elapsed * 1e3 / K
@@ -185,6 +195,15 @@ def main() -> int:
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": measured_traffic(shape), "bytes_per_launch": gateup_bytes, "avg_launch_ms": round(avg_ms, 5),
                 "launches_timed": int(n_launch)}
+
+    sampler = None
+    if sampled and args.profile_steps > 0:
+        sp.profile_select("sample")
+        decode(args.profile_steps, 0)
+        n_s, ms_s = sp.profile_read()
+        sp.profile_select(-1)
+        sampler = {"temperature": args.temperature, "top_p": args.top_p,
+                   "avg_launch_ms": round(ms_s / max(1, n_s), 5), "launches_timed": int(n_s)}
 
     depth_all = dep[:, 0]
     mix = {"full_steps": int((depth_all == shape.n_layers).sum()), "ee_steps": int((depth_all != shape.n_layers).sum())}
@@ -237,13 +256,16 @@ def main() -> int:
                                f"K={sched.period_k}, phase={sched.phase}, "
                                f"{'K_text=' + str(sched.text_period_k) + ', ' if sched.text_period_k > 1 else ''}"
                                f"scope={'chunk' if sched.scope == 0 else 'stream'}"
-                               f"{', cycle offsets aligned' if args.aligned and B > 1 else ''}",
+                               f"{', cycle offsets aligned' if args.aligned and B > 1 else ''}"
+                               f"{f', sampled T={args.temperature} top_p={args.top_p}' if sampled else ', greedy'}",
                    "weights": "random N(0,0.02), fp32 accumulation", "kv_cache": "paged, 64 tokens/page",
                    "step_mix": mix, "mean_speech_depth": stats["mean_speech_depth"],
                    "speech_layer_saving_pct": round(stats["speech_layer_saving"], 2),
                    "prefill": prefill},
         "roofline": roofline, "whole_step": whole, "step_classes": classes, "cpu_baseline": cpu,
     }
+    if sampler:
+        line["sampler"] = sampler
     print(json.dumps(line), flush=True)
     sp.close()
     return 0

@@ -150,6 +150,22 @@ int spark_step(spark_ctx *ctx, int32_t n, const int32_t *seq_ids, const int32_t 
 int spark_decode(spark_ctx *ctx, int32_t n_steps, int32_t n, const int32_t *seq_ids,
                  const int32_t *forced_next, int32_t *out_tokens, int32_t *out_depth);
 
+/* Temperature / nucleus (top-p) sampling in place of the arg-max (Sec. V-A "Models": Step-Audio-2
+ * decodes with temperature 0.7 and top_p 0.9; GLM-4-Voice greedily).  temperature > 0 and
+ * 0 < top_p <= 1 switch it on for spark_decode_sampled; temperature <= 0 switches it off.
+ * With w_i = exp((l_i - max l) / temperature) and integer masses q_i = floor(w_i * 2^32 + 1/2)
+ * (at most 2^32 - 1), the candidates are ordered by larger q, then lower id; the nucleus is the
+ * shortest prefix whose mass reaches ceil(top_p * sum q); with M its mass and omega the step's
+ * 64-bit random word, the token is the element of the prefix at which the running mass first
+ * exceeds floor(omega * M / 2^64).  Returns SPARK_EINVAL for parameters outside these ranges. */
+int spark_set_sampling(spark_ctx *ctx, float temperature, float top_p);
+
+/* spark_decode with one 64-bit random word per step and sequence: rand_words [host] is
+ * [n_steps][n].  With sampling switched off (or rand_words == NULL) it is spark_decode. */
+int spark_decode_sampled(spark_ctx *ctx, int32_t n_steps, int32_t n, const int32_t *seq_ids,
+                         const int32_t *forced_next, const uint64_t *rand_words,
+                         int32_t *out_tokens, int32_t *out_depth);
+
 /* Logits [host, V floats] of the head that decoded the sequence's latest position, and which head
  * it was (*head = e or L). */
 int spark_get_logits(spark_ctx *ctx, int32_t seq_id, float *out_logits, int32_t *head);
@@ -187,7 +203,8 @@ const char *spark_last_error(const spark_ctx *ctx);
 #define SPARK_KC_LENS 5
 #define SPARK_KC_HEAD 6
 #define SPARK_KC_PASS 7   /* the persistent kernel that runs a whole run of layers in one launch */
-#define SPARK_KC_COUNT 8
+#define SPARK_KC_SAMPLE 8 /* the temperature / nucleus sampler */
+#define SPARK_KC_COUNT 9
 int spark_profile_select(spark_ctx *ctx, int32_t kernel_class);
 int spark_profile_read(spark_ctx *ctx, int64_t *n_launches, double *total_ms);
 

@@ -15,7 +15,8 @@ HERE = pathlib.Path(__file__).resolve().parent
 LIB_PATH = HERE / "libspark.so"
 
 SPARK_MAX_PERIOD = 16
-KC = {"qkv": 0, "attn": 1, "oproj": 2, "gateup": 3, "down": 4, "lens": 5, "head": 6, "pass": 7}
+KC = {"qkv": 0, "attn": 1, "oproj": 2, "gateup": 3, "down": 4, "lens": 5, "head": 6, "pass": 7,
+      "sample": 8}
 
 ERRORS = {-1: "SPARK_EINVAL", -2: "SPARK_ENOSEQ", -3: "SPARK_ENOMEM", -4: "SPARK_ESTATE",
           -5: "SPARK_EHIP", -6: "SPARK_ENAN"}
@@ -23,7 +24,7 @@ ERRORS = {-1: "SPARK_EINVAL", -2: "SPARK_ENOSEQ", -3: "SPARK_ENOMEM", -4: "SPARK
 EXPORTS = ("spark_workspace_bytes", "spark_init", "spark_seq_open", "spark_prefill", "spark_step",
            "spark_decode", "spark_get_logits", "spark_get_kv", "spark_seq_state",
            "spark_get_stats", "spark_seq_close", "spark_destroy", "spark_last_error",
-           "spark_profile_select", "spark_profile_read")
+           "spark_profile_select", "spark_profile_read", "spark_set_sampling", "spark_decode_sampled")
 
 
 class SparkConfig(C.Structure):
@@ -77,6 +78,8 @@ def load_library() -> C.CDLL:
     lib.spark_prefill.argtypes = [P, I, P, I]
     lib.spark_step.argtypes = [P, I, P, P, P, P]
     lib.spark_decode.argtypes = [P, I, I, P, P, P, P]
+    lib.spark_set_sampling.argtypes = [P, C.c_float, C.c_float]
+    lib.spark_decode_sampled.argtypes = [P, I, I, P, P, P, P, P]
     lib.spark_get_logits.argtypes = [P, I, P, C.POINTER(I)]
     lib.spark_get_kv.argtypes = [P, I, I, I, P, P]
     lib.spark_seq_state.argtypes = [P, I, C.POINTER(I), C.POINTER(I), C.POINTER(I)]
@@ -199,6 +202,23 @@ class Spark:
         dep = np.empty((n_steps, n), dtype=np.int32)
         self._check(self.lib.spark_decode(self.handle, n_steps, n, _iptr(ids),
                                           _iptr(f) if f is not None else None, _iptr(tok), _iptr(dep)))
+        return tok, dep
+
+    def set_sampling(self, temperature: float, top_p: float) -> None:
+        self._check(self.lib.spark_set_sampling(self.handle, temperature, top_p))
+
+    def decode_sampled(self, n_steps: int, seq_ids, rand_words, forced_next=None):
+        ids = np.ascontiguousarray(seq_ids, dtype=np.int32)
+        n = len(ids)
+        f = None
+        if forced_next is not None:
+            f = np.ascontiguousarray(forced_next, dtype=np.int32).reshape(n_steps, n)
+        rw = np.ascontiguousarray(rand_words, dtype=np.uint64).reshape(n_steps, n)
+        tok = np.empty((n_steps, n), dtype=np.int32)
+        dep = np.empty((n_steps, n), dtype=np.int32)
+        self._check(self.lib.spark_decode_sampled(self.handle, n_steps, n, _iptr(ids),
+                                                  _iptr(f) if f is not None else None, _iptr(rw),
+                                                  _iptr(tok), _iptr(dep)))
         return tok, dep
 
     def get_logits(self, seq_id: int):

@@ -18,6 +18,7 @@
 #include "gemv.h"
 #include "mfma_gemm.h"
 #include "pass_launch.h"
+#include "sampling.h"
 #include "sched.h"
 
 using namespace spark;
@@ -31,7 +32,7 @@ constexpr int MAX_SEQ_LEN = 16384;
 
 struct Layout {  // byte offsets into the scratch buffer
   size_t state, page_table, plan, lower, upper, ee, full, prefill_rows, prefill_tokens, seq_ids,
-      forced, step_flags, out_tokens, out_depth, best, arrivals, barrier, hidden, xsplit, xsplit2, mfma_part, qbuf, attn_out, part, act, lens_u,
+      forced, step_flags, out_tokens, out_depth, best, arrivals, barrier, sample_hist, sample_arrive, sample_count, hidden, xsplit, xsplit2, mfma_part, sample_q, sample_cand, rand_words, qbuf, attn_out, part, act, lens_u,
       logits, rope, inv_freq, total;
 };
 
@@ -70,6 +71,7 @@ struct spark_ctx {
   bool use_mfma = true;        // SPARK_NO_MFMA=1 keeps every row count on the vector kernels
   unsigned bar_round = 0;      // grid barriers passed since the barrier words were zeroed
   unsigned long long *timeline_dev = nullptr;  // debugging aid, see SPARK_PASS_TIMELINE
+  float temperature = 0.f, top_p = 0.f;   // nucleus sampling, off while temperature <= 0
   int prefill_chunk = 128;   // prompt rows per pass, see spark_init
   int attn_splits_now = 0;   // context slices the rows of the passes being enqueued can reach (0: unknown, launch all)
   std::map<std::pair<const void *, size_t>, int> occ_cache;  // workgroups per CU of a (kernel, LDS bytes)
@@ -197,6 +199,9 @@ void layout(const spark_config &c, const Derived &d, Layout &l) {
   l.best = take(sizeof(unsigned long long) * c.max_batch);
   l.arrivals = take(sizeof(int) * (size_t)d.max_rows * c.n_q_heads);   // per (row, group of query heads)
   l.barrier = take(sizeof(unsigned) * (8 * 32 + 32));
+  l.sample_hist = take(sizeof(unsigned long long) * (size_t)SAMPLE_BINS * c.max_batch);   // zero between launches
+  l.sample_arrive = take(sizeof(unsigned) * c.max_batch);
+  l.sample_count = take(sizeof(unsigned) * c.max_batch);
   l.hidden = take(sizeof(float) * ((size_t)c.max_batch * d.rmax + PREFILL_CHUNK) * c.d_model);
   l.qbuf = take(sizeof(float) * d.max_rows * qw);
   l.attn_out = take(sizeof(float) * d.max_rows * qw);
@@ -211,6 +216,9 @@ void layout(const spark_config &c, const Derived &d, Layout &l) {
     l.mfma_part = take(c.dtype == SPARK_DTYPE_BF16 ? MFMA_PARTIAL_BYTES : 256);
   }
   l.logits = take(sizeof(float) * (size_t)c.max_batch * d.V);
+  l.sample_q = take(sizeof(unsigned) * (size_t)c.max_batch * d.V);   // integer masses of the sampler
+  l.sample_cand = take(sizeof(unsigned long long) * (size_t)SAMPLE_CAP * c.max_batch);
+  l.rand_words = take(sizeof(unsigned long long) * (size_t)MAX_STEPS_PER_CALL * c.max_batch);
   l.rope = take(sizeof(float2) * (size_t)c.max_seq_len * (c.head_dim / 2));
   l.inv_freq = take(sizeof(float) * (c.head_dim / 2));
   l.total = o;
@@ -705,7 +713,7 @@ int ensure_pages(spark_ctx *c, int id, int upto) {
 
 template <typename WT>
 int enqueue_step(spark_ctx *c, int n, int n_upper, int n_ee, int n_full, const int *forced_dev,
-                 int *out_tok_dev, int *out_depth_dev) {
+                 const unsigned long long *rand_dev, int *out_tok_dev, int *out_depth_dev) {
   const spark_config &g = c->cfg;
   RowDesc *lower = at<RowDesc>(c, c->lo.lower), *upper = at<RowDesc>(c, c->lo.upper);
   RowDesc *ee = at<RowDesc>(c, c->lo.ee), *full = at<RowDesc>(c, c->lo.full);
@@ -724,6 +732,20 @@ int enqueue_step(spark_ctx *c, int n, int n_upper, int n_ee, int n_full, const i
     if ((rc = run_layers<WT>(c, g.exit_layer, g.n_layers, upper, n_upper, n == 1))) return rc;
     if ((rc = run_final_head<WT>(c, full, n_full))) return rc;
   }
+  if (rand_dev && c->temperature > 0.f) {   // the drawn token takes the arg-max's place
+    if ((rc = prof_begin(c, SPARK_KC_SAMPLE))) return rc;
+    const dim3 grid((c->dv.V + SAMPLE_CHUNK - 1) / SAMPLE_CHUNK, n);
+    float *logits = at<float>(c, c->lo.logits);
+    unsigned *masses = at<unsigned>(c, c->lo.sample_q);
+    unsigned long long *class_mass = at<unsigned long long>(c, c->lo.sample_hist);
+    sample_mass_k<<<grid, SAMPLE_THREADS, 0, c->stream>>>(logits, c->dv.V, (double)c->temperature, masses,
+                                                          class_mass, best);
+    sample_pick_k<<<grid, SAMPLE_THREADS, 0, c->stream>>>(
+        logits, c->dv.V, (double)c->top_p, rand_dev, masses, class_mass,
+        at<unsigned long long>(c, c->lo.sample_cand), at<unsigned>(c, c->lo.sample_count),
+        at<unsigned>(c, c->lo.sample_arrive), best);
+    if ((rc = prof_end(c, SPARK_KC_SAMPLE))) return rc;
+  }
   emit_k<<<1, SCHED_THREADS, 0, c->stream>>>(n, seq_ids, forced_dev, flags, best, state, plan,
                                             out_tok_dev);
   HIP_TRY(c, hipGetLastError());
@@ -731,7 +753,7 @@ int enqueue_step(spark_ctx *c, int n, int n_upper, int n_ee, int n_full, const i
 }
 
 int decode_chunk(spark_ctx *c, int steps, int n, const int32_t *seq_ids, const int32_t *forced,
-                 int32_t *out_tokens, int32_t *out_depth) {
+                 const uint64_t *rand_words, int32_t *out_tokens, int32_t *out_depth) {
   const spark_config &g = c->cfg;
   int rc;
   // validation and page reservation
@@ -761,6 +783,10 @@ int decode_chunk(spark_ctx *c, int steps, int n, const int32_t *seq_ids, const i
                               hipMemcpyHostToDevice, c->stream));
   }
 
+  if (rand_words)   // (pageable source: the copy has completed on return)
+    HIP_TRY(c, hipMemcpyAsync(at<unsigned long long>(c, c->lo.rand_words), rand_words,
+                              sizeof(uint64_t) * (size_t)steps * n, hipMemcpyHostToDevice, c->stream));
+
   // host mirror of the schedule: decides the launch shapes, checked against the device's depths
   struct Mirror { int g, j, npend, len; };
   std::vector<Mirror> mir(n);
@@ -789,8 +815,10 @@ int decode_chunk(spark_ctx *c, int steps, int n, const int32_t *seq_ids, const i
     const int *f = forced ? at<int>(c, c->lo.forced) + (size_t)st * n : nullptr;
     int *ot = at<int>(c, c->lo.out_tokens) + (size_t)st * n;
     int *od = at<int>(c, c->lo.out_depth) + (size_t)st * n;
-    rc = g.dtype == SPARK_DTYPE_BF16 ? enqueue_step<bf16_t>(c, n, n_upper, n_ee, n_full, f, ot, od)
-                                     : enqueue_step<float>(c, n, n_upper, n_ee, n_full, f, ot, od);
+    const unsigned long long *rw =
+        rand_words ? at<unsigned long long>(c, c->lo.rand_words) + (size_t)st * n : nullptr;
+    rc = g.dtype == SPARK_DTYPE_BF16 ? enqueue_step<bf16_t>(c, n, n_upper, n_ee, n_full, f, rw, ot, od)
+                                     : enqueue_step<float>(c, n, n_upper, n_ee, n_full, f, rw, ot, od);
     if (rc) return rc;
   }
 
@@ -1004,17 +1032,36 @@ int spark_prefill(spark_ctx *c, int32_t seq_id, const int32_t *prompt, int32_t n
   return SPARK_OK;
 }
 
-int spark_decode(spark_ctx *c, int32_t n_steps, int32_t n, const int32_t *seq_ids,
-                 const int32_t *forced_next, int32_t *out_tokens, int32_t *out_depth) {
+int spark_decode_sampled(spark_ctx *c, int32_t n_steps, int32_t n, const int32_t *seq_ids,
+                         const int32_t *forced_next, const uint64_t *rand_words,
+                         int32_t *out_tokens, int32_t *out_depth) {
   if (!c) return SPARK_EINVAL;
   if (n < 1 || n > c->cfg.max_batch || n_steps < 1 || !seq_ids || !out_tokens || !out_depth)
     return fail(c, SPARK_EINVAL, "bad batch (n=%d, n_steps=%d)", n, n_steps);
   for (int s0 = 0; s0 < n_steps; s0 += MAX_STEPS_PER_CALL) {
     int steps = std::min(MAX_STEPS_PER_CALL, n_steps - s0);
     int rc = decode_chunk(c, steps, n, seq_ids, forced_next ? forced_next + (size_t)s0 * n : nullptr,
+                          rand_words ? rand_words + (size_t)s0 * n : nullptr,
                           out_tokens + (size_t)s0 * n, out_depth + (size_t)s0 * n);
     if (rc) return rc;
   }
+  return SPARK_OK;
+}
+
+int spark_decode(spark_ctx *c, int32_t n_steps, int32_t n, const int32_t *seq_ids,
+                 const int32_t *forced_next, int32_t *out_tokens, int32_t *out_depth) {
+  return spark_decode_sampled(c, n_steps, n, seq_ids, forced_next, nullptr, out_tokens, out_depth);
+}
+
+int spark_set_sampling(spark_ctx *c, float temperature, float top_p) {
+  if (!c) return SPARK_EINVAL;
+  if (!(temperature > 0.f)) {
+    c->temperature = c->top_p = 0.f;
+    return SPARK_OK;
+  }
+  if (!(top_p > 0.f) || top_p > 1.f) return fail(c, SPARK_EINVAL, "top_p outside (0, 1]");
+  c->temperature = temperature;
+  c->top_p = top_p;
   return SPARK_OK;
 }
 

@@ -12,6 +12,34 @@ from parity_util import compare_run, say
 pytestmark = pytest.mark.gpu
 
 
+def sampled_draws_match(sp, w, prompt, offset, n_steps=12, temperature=0.7, top_p=0.9):
+    """temperature / nucleus sampling (Sec. V-A "Models") over the whole 158k-entry vocabulary,
+    free running: each drawn token against the oracle's sampler on the GPU's logits of that step"""
+    from oracle import binding as ob
+    T, P = float(np.float32(temperature)), float(np.float32(top_p))
+    rng = np.random.default_rng(21)
+    sid = sp.seq_open(offset)
+    sp.prefill(sid, prompt)
+    sp.set_sampling(temperature, top_p)
+    sizes, moved, crowd = [], 0, []
+    for s in range(n_steps):
+        omega = int(rng.integers(0, 2 ** 64, dtype=np.uint64))
+        tok, _ = sp.decode_sampled(1, [sid], [omega])
+        lg, _ = sp.get_logits(sid)
+        otok, n, gap = ob.sample(lg, T, P, omega)
+        sizes.append(n)
+        moved += int(tok[0, 0] != int(np.argmax(lg)))
+        # how many masses lie within 1/64 (relative) below the nucleus' last one
+        m = np.sort(np.exp((lg.astype(np.float64) - float(lg.max())) / T))[::-1]
+        crowd.append(int(np.sum((m <= m[n - 1]) & (m > m[n - 1] * (1 - 1 / 64)))))
+        assert tok[0, 0] == otok or gap <= 4 * 2.0 ** -32, (s, int(tok[0, 0]), otok, gap)
+    say(f"  sampled T={temperature}: {n_steps} draws, nucleus sizes {min(sizes)}..{max(sizes)}, {moved} away from "
+        f"the arg-max, {min(crowd)}..{max(crowd)} masses within 1/64 below the nucleus' edge")
+    assert moved > 0
+    sp.set_sampling(0.0, 0.0)
+    sp.seq_close(sid)
+
+
 @pytest.mark.parametrize("name,n_steps,offset,n_prompt", [
     ("step_audio_2_mini", 36, 0, 32),    # 3 * (1 + 2) * 4 steps: flushes of 1, 2 and 3 rows
     ("glm_4_voice", 24, 10, 32),         # enters the cycle 3 text slots before a 26-slot speech chunk
@@ -44,6 +72,11 @@ def test_full_shape_short_run(name, n_steps, offset, n_prompt):
     depths = res["depths"][:, 0]
     assert set(np.unique(depths)) <= {w.schedule.exit_layer, w.shape.n_layers}
     assert n_steps < 12 or len(np.unique(depths)) == 2
+    if name == "step_audio_2_mini" and n_prompt == 32:
+        sampled_draws_match(sp, w, prompt, offset)
+        # a flat distribution: tens of thousands of masses within 1/64 of each other, more than
+        # the sampler's candidate list holds, so its general path decides
+        sampled_draws_match(sp, w, prompt, offset, n_steps=6, temperature=5.0, top_p=0.9)
     sp.close()
     del dev_w, host_w
     torch.cuda.empty_cache()
