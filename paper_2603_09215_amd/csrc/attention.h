@@ -38,6 +38,72 @@ template <int HD, int G, int NT> constexpr int attn_lds_floats() {
 
 // partial layout: part[((r*nq + hq)*n_splits + split)*(HD+4)] = {o[HD], m, l, pad, pad}
 //
+// Second half of a task, executed by all NT threads that produced the partial of one slice for
+// query heads hq0 .. hq0 + g_count - 1 of row r: count the slice as done; the workgroup that
+// arrives last for this (row, group of heads) merges the slices,
+// out = sum_s exp(m_s - M) o_s / sum_s exp(m_s - M) l_s.
+template <int HD, int NT, bool DS>
+__device__ __forceinline__ void attn_merge(const RowDesc &rd, int r, int hq0, int g_count, int nq,
+                                           int n_splits, const float *__restrict__ part,
+                                           int *__restrict__ cnt, float *__restrict__ out,
+                                           const SplitOut &so, int *s_last) {
+  constexpr int PS = HD + 4;
+  const int tid = threadIdx.x % NT;
+  // Partials are written through to memory (device-scope stores) and counted with a device-scope
+  // atomic; the merging workgroup drops its stale cache lines once and then reads them normally.
+  const int used = (rd.pos + ATTN_SLICE) / ATTN_SLICE;   // slices that intersect the context
+  wait_memory_ops();                                      // partials written before the count
+  task_sync<NT>();
+  if (tid == 0) {
+    const int prev = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *s_last = prev == used - 1;
+    if (*s_last) {
+      __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next layer
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // one cache invalidate for the workgroup
+    }
+  }
+  task_sync<NT>();
+  if (!*s_last) return;
+
+  // every thread merges four output elements of one head over all slices in one pass (running
+  // maximum, rescaled sums), eight slices' loads in flight at a time
+  for (int i = tid; i < g_count * (HD / 4); i += NT) {
+    const int g = i / (HD / 4), c = (i - g * (HD / 4)) * 4;
+    const float *p = part + (size_t)(r * nq + hq0 + g) * n_splits * PS;
+    float M = -INFINITY, L = 0.f;
+    float4 acc4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s0 = 0; s0 < used; s0 += 8) {
+      float2 ml8[8];
+      float4 o8[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int sl = min(s0 + k, used - 1);
+        ml8[k] = *(const float2 *)(p + (size_t)sl * PS + HD);
+        o8[k] = *(const float4 *)(p + (size_t)sl * PS + c);
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        if (s0 + k < used) {
+          const float Mn = fmaxf(M, ml8[k].x);
+          const float so = expf(M - Mn), sn = expf(ml8[k].x - Mn);   // exp(-inf) = 0 on the first slice
+          acc4.x = acc4.x * so + o8[k].x * sn; acc4.y = acc4.y * so + o8[k].y * sn;
+          acc4.z = acc4.z * so + o8[k].z * sn; acc4.w = acc4.w * so + o8[k].w * sn;
+          L = L * so + ml8[k].y * sn;
+          M = Mn;
+        }
+      }
+    }
+    const float inv = 1.0f / L;
+    float *dst = out + (size_t)r * nq * HD + (hq0 + g) * HD + c;
+    store2_maybe_ds<DS>(dst, make_float2(acc4.x * inv, acc4.y * inv));
+    store2_maybe_ds<DS>(dst + 2, make_float2(acc4.z * inv, acc4.w * inv));
+    // for the MFMA output projection: the same values as three bf16 parts
+    if (so.xs)
+      split_store4(so, r, (hq0 + g) * HD + c, make_float4(acc4.x * inv, acc4.y * inv, acc4.z * inv, acc4.w * inv));
+  }
+  if (DS) wait_memory_ops();   // the caller's next barrier arrival does not wait for these stores
+}
+
 // One task, executed by all NT threads of a workgroup: query heads hq0 .. hq0 + g_count - 1
 // (g_count <= G, all sharing KV head hk) of row r over one slice; `cnt` counts the slices of this
 // (row, group of heads) that are done.  DS: the queries were written, and the output will be
@@ -164,62 +230,7 @@ __device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int 
     store_device_scope(part + ((size_t)(r * nq + hq0 + g) * n_splits + split) * PS + HD + w,
                        ml[g * 2 + w]);
   }
-
-  // The workgroup that arrives last for this (row, kv head) merges the slices:
-  // out = sum_s exp(m_s - M) o_s / sum_s exp(m_s - M) l_s.
-  // Partials are written through to memory (device-scope stores) and counted with a device-scope
-  // atomic; the merging workgroup drops its stale cache lines once and then reads them normally.
-  const int used = (rd.pos + ATTN_SLICE) / ATTN_SLICE;   // slices that intersect the context
-  wait_memory_ops();                                      // partials written before the count
-  task_sync<NT>();
-  if (tid == 0) {
-    const int prev = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    *s_last = prev == used - 1;
-    if (*s_last) {
-      __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next layer
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // one cache invalidate for the workgroup
-    }
-  }
-  task_sync<NT>();
-  if (!*s_last) return;
-
-  // every thread merges four output elements of one head over all slices in one pass (running
-  // maximum, rescaled sums), eight slices' loads in flight at a time
-  for (int i = tid; i < g_count * (HD / 4); i += NT) {
-    const int g = i / (HD / 4), c = (i - g * (HD / 4)) * 4;
-    const float *p = part + (size_t)(r * nq + hq0 + g) * n_splits * PS;
-    float M = -INFINITY, L = 0.f;
-    float4 acc4 = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int s0 = 0; s0 < used; s0 += 8) {
-      float2 ml8[8];
-      float4 o8[8];
-#pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        const int sl = min(s0 + k, used - 1);
-        ml8[k] = *(const float2 *)(p + (size_t)sl * PS + HD);
-        o8[k] = *(const float4 *)(p + (size_t)sl * PS + c);
-      }
-#pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        if (s0 + k < used) {
-          const float Mn = fmaxf(M, ml8[k].x);
-          const float so = expf(M - Mn), sn = expf(ml8[k].x - Mn);   // exp(-inf) = 0 on the first slice
-          acc4.x = acc4.x * so + o8[k].x * sn; acc4.y = acc4.y * so + o8[k].y * sn;
-          acc4.z = acc4.z * so + o8[k].z * sn; acc4.w = acc4.w * so + o8[k].w * sn;
-          L = L * so + ml8[k].y * sn;
-          M = Mn;
-        }
-      }
-    }
-    const float inv = 1.0f / L;
-    float *dst = out + (size_t)r * nq * HD + (hq0 + g) * HD + c;
-    store2_maybe_ds<DS>(dst, make_float2(acc4.x * inv, acc4.y * inv));
-    store2_maybe_ds<DS>(dst + 2, make_float2(acc4.z * inv, acc4.w * inv));
-    // for the MFMA output projection: the same values as three bf16 parts
-    if (so.xs)
-      split_store4(so, r, (hq0 + g) * HD + c, make_float4(acc4.x * inv, acc4.y * inv, acc4.z * inv, acc4.w * inv));
-  }
-  if (DS) wait_memory_ops();   // the caller's next barrier arrival does not wait for these stores
+  attn_merge<HD, NT, DS>(rd, r, hq0, g_count, nq, n_splits, part, cnt, out, so, s_last);
 }
 
 // stand-alone launch: one workgroup per (slice, group of G query heads, row).  A KV head's `group`
@@ -238,6 +249,190 @@ attn_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbuf, KV
   attn_task<KT, HD, G, ATTN_THREADS, false>(rd, r, hk, hk * group + gi * G, min(G, group - gi * G), split,
                                             qbuf, kv, layer, nq, n_splits, scale, part,
                                             arrivals + r * gridDim.y + blockIdx.y, out, so, lds);
+}
+
+// ------------------------------------------------------------------ the same task on the MFMA units
+//
+// bf16 cache, head_dim 128, up to 16 query heads per KV head, one workgroup (4 waves) per
+// (slice, KV head, row), all query heads of the group together.  v_mfma_f32_16x16x32_bf16 twice:
+//   scores   S^T[token][head] = K[token][:] . Q[head][:]   wave w takes tokens 16w .. 16w+15; the K
+//            rows go from memory straight into the A operand (lane l: token l%16, eight
+//            consecutive elements at 8*(l/16) of each 32-wide step), the scaled queries, split into
+//            three bf16 parts that add up to the fp32 value, are the B operand;
+//   values   O[head][hd] = P[head][token] . V[token][hd]   wave w takes hd 32w .. 32w+31 over all
+//            64 tokens; P (two bf16 parts) crosses the waves through LDS in A-operand order, V is
+//            staged in LDS as it lies in the cache (token-major) and gathered column-wise, the
+//            only transposition the operation needs.
+// The partial it leaves and the merge are those of the vector task.
+typedef __attribute__((ext_vector_type(8))) __bf16 attn_bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float attn_f32x4_t;
+typedef unsigned int attn_u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int attn_u32x2_t __attribute__((ext_vector_type(2)));
+
+constexpr int AM_VPITCH = 130;   // bf16 elements per V row in LDS: 65 dwords, so the four token groups of a gather hit different banks
+constexpr int AM_PPITCH = 72;    // tokens per P row in LDS (16-byte aligned rows)
+
+__device__ __forceinline__ unsigned pack_bf16(bf16_t lo, bf16_t hi) { return (unsigned)lo | ((unsigned)hi << 16); }
+
+template <int HD>
+__global__ void __launch_bounds__(ATTN_THREADS)
+attn_rows_mfma_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbuf, KVView kv, int layer,
+                 int nq, int group, int n_splits, float scale, float *__restrict__ part,
+                 int *__restrict__ arrivals, float *__restrict__ out, SplitOut so) {
+  static_assert(HD == 128, "four 32-wide steps per key row, four waves of 32 value columns");
+  constexpr int PS = HD + 4;
+  __shared__ __align__(16) bf16_t s_v[ATTN_SLICE * AM_VPITCH];
+  __shared__ __align__(16) bf16_t s_p[2 * 16 * AM_PPITCH];
+  __shared__ float s_max[4 * 16], s_sum[4 * 16];
+  __shared__ int s_last;
+  const int split = blockIdx.x, hk = blockIdx.y, r = blockIdx.z;
+  const RowDesc rd = rows[r];
+  if (split * ATTN_SLICE > rd.pos) return;        // slice beyond the row's context
+  const int t0 = split * ATTN_SLICE;
+  const int n_tok = min(ATTN_SLICE, rd.pos + 1 - t0);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 15, quad = lane >> 4;    // operand column / row, and which eight of a 32-wide step
+  const int hq0 = hk * group;
+  const bf16_t *pool = (const bf16_t *)kv.pool;
+
+  // every load of the slice; tokens beyond the context read token t0 instead (it exists) and are
+  // masked below.  With pages of a multiple of 64 tokens the slice lies inside one page and its
+  // address is worked out once for the workgroup.
+  const bool one_page = (kv.page_tokens & (ATTN_SLICE - 1)) == 0;
+  const size_t slice_k = one_page ? kv_elem_offset(kv, rd.seq, t0, layer, 0, hk) : 0;
+  const size_t slice_v = one_page ? kv_elem_offset(kv, rd.seq, t0, layer, 1, hk) : 0;
+  attn_u32x4_t vraw[4];
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int t = it * 16 + (tid >> 4), tt = t < n_tok ? t : 0;
+    const size_t o = one_page ? slice_v + (size_t)tt * HD : kv_elem_offset(kv, rd.seq, t0 + tt, layer, 1, hk);
+    vraw[it] = *(const attn_u32x4_t *)(pool + o + (tid & 15) * 8);
+  }
+  attn_bf16x8_t ka[4];
+  {
+    const int t = 16 * wave + col, tt = t < n_tok ? t : 0;
+    const size_t o = one_page ? slice_k + (size_t)tt * HD : kv_elem_offset(kv, rd.seq, t0 + tt, layer, 0, hk);
+    const bf16_t *kp = pool + o + quad * 8;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) ka[s] = __builtin_bit_cast(attn_bf16x8_t, *(const attn_u32x4_t *)(kp + 32 * s));
+  }
+  // the scaled queries as three bf16 parts that add up to the fp32 value: each part keeps the
+  // upper 8 significant bits of what the parts before it left (truncation, exact remainders)
+  attn_bf16x8_t qb[3][4];
+  {
+    const float *qp = qbuf + ((size_t)r * nq + hq0 + min(col, group - 1)) * HD + quad * 8;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const float4 q0 = *(const float4 *)(qp + 32 * s), q1 = *(const float4 *)(qp + 32 * s + 4);
+      const float qf[8] = {q0.x * scale, q0.y * scale, q0.z * scale, q0.w * scale,
+                           q1.x * scale, q1.y * scale, q1.z * scale, q1.w * scale};
+      unsigned h[8], m[8], l[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        h[e] = __float_as_uint(qf[e]) & 0xffff0000u;
+        const float r1 = qf[e] - __uint_as_float(h[e]);
+        m[e] = __float_as_uint(r1) & 0xffff0000u;
+        l[e] = __float_as_uint(r1 - __uint_as_float(m[e]));   // at most 8 significant bits are left
+      }
+      attn_u32x4_t ph, pm, pl;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        ph[e] = (h[2 * e] >> 16) | h[2 * e + 1];
+        pm[e] = (m[2 * e] >> 16) | m[2 * e + 1];
+        pl[e] = (l[2 * e] >> 16) | (l[2 * e + 1] & 0xffff0000u);
+      }
+      qb[0][s] = __builtin_bit_cast(attn_bf16x8_t, ph);
+      qb[1][s] = __builtin_bit_cast(attn_bf16x8_t, pm);
+      qb[2][s] = __builtin_bit_cast(attn_bf16x8_t, pl);
+    }
+  }
+
+  // V into LDS as it lies in the cache (4-byte stores: the row pitch is an odd number of dwords)
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    unsigned *dst = (unsigned *)(s_v + (it * 16 + (tid >> 4)) * AM_VPITCH + (tid & 15) * 8);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) dst[e] = vraw[it][e];
+  }
+
+  // scores of this wave's 16 tokens: lane holds head `col`, tokens 16*wave + 4*quad + i
+  attn_f32x4_t sc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int s = 0; s < 4; ++s)
+#pragma unroll
+    for (int p = 0; p < 3; ++p) sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[s], qb[p][s], sc, 0, 0, 0);
+  const int tok0 = 16 * wave + 4 * quad;
+  float mw = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (tok0 + i >= n_tok) sc[i] = -INFINITY;
+    mw = fmaxf(mw, sc[i]);
+  }
+  mw = fmaxf(mw, __shfl_xor(mw, 16, 64));
+  mw = fmaxf(mw, __shfl_xor(mw, 32, 64));
+  if (quad == 0) s_max[wave * 16 + col] = mw;
+  __syncthreads();
+  const float mx = fmaxf(fmaxf(s_max[col], s_max[16 + col]), fmaxf(s_max[32 + col], s_max[48 + col]));
+  float pr[4], lw = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    pr[i] = tok0 + i < n_tok ? expf(sc[i] - mx) : 0.f;   // (token 0 of the slice is real, so mx is finite)
+    lw += pr[i];
+  }
+  lw += __shfl_xor(lw, 16, 64);
+  lw += __shfl_xor(lw, 32, 64);
+  if (quad == 0) s_sum[wave * 16 + col] = lw;
+  {
+    // probabilities as two bf16 parts (16 significant bits)
+    unsigned h[4], l[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      h[i] = __float_as_uint(pr[i]) & 0xffff0000u;
+      l[i] = __float_as_uint(pr[i] - __uint_as_float(h[i])) & 0xffff0000u;
+    }
+    attn_u32x2_t ph = {(h[0] >> 16) | h[1], (h[2] >> 16) | h[3]};
+    attn_u32x2_t pl = {(l[0] >> 16) | l[1], (l[2] >> 16) | l[3]};
+    *(attn_u32x2_t *)(s_p + col * AM_PPITCH + tok0) = ph;
+    *(attn_u32x2_t *)(s_p + 16 * AM_PPITCH + col * AM_PPITCH + tok0) = pl;
+  }
+  __syncthreads();
+
+  // weighted values: lane holds hd 32*wave + 16*t + col, heads 4*quad + i
+  attn_f32x4_t oacc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+    const attn_bf16x8_t pa0 = __builtin_bit_cast(
+        attn_bf16x8_t, *(const attn_u32x4_t *)(s_p + col * AM_PPITCH + 32 * ks + 8 * quad));
+    const attn_bf16x8_t pa1 = __builtin_bit_cast(
+        attn_bf16x8_t, *(const attn_u32x4_t *)(s_p + 16 * AM_PPITCH + col * AM_PPITCH + 32 * ks + 8 * quad));
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const bf16_t *vcol = s_v + (32 * ks + 8 * quad) * AM_VPITCH + 32 * wave + 16 * t + col;
+      attn_u32x4_t vb;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) vb[e] = pack_bf16(vcol[(2 * e) * AM_VPITCH], vcol[(2 * e + 1) * AM_VPITCH]);
+      const attn_bf16x8_t b = __builtin_bit_cast(attn_bf16x8_t, vb);
+      oacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa0, b, oacc[t], 0, 0, 0);
+      oacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa1, b, oacc[t], 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int g = 4 * quad + i;
+      if (g < group)
+        store_device_scope(part + ((size_t)(r * nq + hq0 + g) * n_splits + split) * PS + 32 * wave + 16 * t + col,
+                           oacc[t][i]);
+    }
+  if (tid < group * 2) {
+    const int g = tid >> 1;
+    const float v = (tid & 1) ? s_sum[g] + s_sum[16 + g] + s_sum[32 + g] + s_sum[48 + g]
+                              : fmaxf(fmaxf(s_max[g], s_max[16 + g]), fmaxf(s_max[32 + g], s_max[48 + g]));
+    store_device_scope(part + ((size_t)(r * nq + hq0 + g) * n_splits + split) * PS + HD + (tid & 1), v);
+  }
+  attn_merge<HD, ATTN_THREADS, false>(rd, r, hq0, group, nq, n_splits, part,
+                                      arrivals + r * gridDim.y + blockIdx.y, out, so, &s_last);
 }
 
 }  // namespace spark

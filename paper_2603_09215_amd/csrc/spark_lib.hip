@@ -71,6 +71,7 @@ struct spark_ctx {
   bool use_mfma = true;        // SPARK_NO_MFMA=1 keeps every row count on the vector kernels
   unsigned bar_round = 0;      // grid barriers passed since the barrier words were zeroed
   unsigned long long *timeline_dev = nullptr;  // debugging aid, see SPARK_PASS_TIMELINE
+  int attn_mfma_min_rows = 1;   // passes with at least this many rows run attention on the MFMA units (where the shape allows)
   float temperature = 0.f, top_p = 0.f;   // nucleus sampling, off while temperature <= 0
   int prefill_chunk = 128;   // prompt rows per pass, see spark_init
   int attn_splits_now = 0;   // context slices the rows of the passes being enqueued can reach (0: unknown, launch all)
@@ -362,7 +363,15 @@ template <typename WT> int launch_attention(spark_ctx *c, const RowDesc *rows, i
   if (rc) return rc;
   const int qw = c->cfg.n_q_heads * c->cfg.head_dim;
   const SplitOut so = split_out ? split_target(c, qw) : SplitOut{nullptr, 0, 0, 0};
-  if (c->cfg.head_dim == 128) launch_attention_hd<WT, 128>(c, rows, m, layer, so);
+  if (std::is_same<WT, bf16_t>::value && c->cfg.head_dim == 128 && c->dv.group <= 16 && c->use_mfma &&
+      m >= c->attn_mfma_min_rows) {
+    // many rows: the slice tasks on the MFMA units, all query heads of a KV head together
+    const int splits = c->attn_splits_now > 0 ? std::min(c->dv.n_splits, c->attn_splits_now) : c->dv.n_splits;
+    attn_rows_mfma_k<128><<<dim3(splits, c->cfg.n_kv_heads, m), ATTN_THREADS, 0, c->stream>>>(
+        rows, at<float>(c, c->lo.qbuf), kv_view(c), layer, c->cfg.n_q_heads, c->dv.group, c->dv.n_splits,
+        1.0f / sqrtf(128.0f), at<float>(c, c->lo.part), at<int>(c, c->lo.arrivals),
+        at<float>(c, c->lo.attn_out), so);
+  } else if (c->cfg.head_dim == 128) launch_attention_hd<WT, 128>(c, rows, m, layer, so);
   else launch_attention_hd<WT, 64>(c, rows, m, layer, so);
   HIP_TRY(c, hipGetLastError());
   return prof_end(c, SPARK_KC_ATTN);
@@ -950,6 +959,7 @@ int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_p
   // one kernel per operation yet; it is used when SPARK_PASS_KERNEL=1.
   const char *pass = getenv("SPARK_PASS_KERNEL");
   c->use_pass_kernel = pass && pass[0] == '1';
+  if (const char *v = getenv("SPARK_ATTN_MFMA_MIN_ROWS")) c->attn_mfma_min_rows = std::max(1, atoi(v));
   const char *no_mfma = getenv("SPARK_NO_MFMA");
   // the MFMA kernels load 16-byte vectors of 8 weights; other widths stay on the vector kernel
   c->use_mfma = !(no_mfma && no_mfma[0] == '1') && cfg->d_model % 8 == 0 &&
