@@ -41,12 +41,18 @@ constexpr int MG_ROWPAD = MG_KC + 8;   // bf16 per staged row (a 16-byte skew pe
 constexpr int MG_TASKS_PER_WAVE = 32;
 constexpr int MG_TASKS_PER_BLOCK = MG_WAVES * MG_TASKS_PER_WAVE;
 constexpr int MG_MAX_MTILES = 2;       // activation rows per workgroup: 32 or 64
+// bf16 parts of an activation that meet the weights: all three, so that every product is the
+// exact product of the fp32 activation and the bf16 weight, as in the vector kernel.  (Two parts,
+// 16 significant bits, would cut the MFMA and LDS work by a third at an error of 2^-17 per
+// product; tried: the 1e-5 perturbations change which cache entries round up or down to bf16,
+// and at the 40-layer shape that moved a logit by 0.022, past the 0.02 the parity tests allow.)
+constexpr int MG_PARTS = 3;
 // weight chunks a wave has in registers, on their way from HBM
 constexpr int MG_W_DEPTH = 2;
 // dynamic LDS of mfma_rows_k: per wave 64 padded weight rows of one chunk; two buffers of three
 // parts of 32*MTILES padded activation rows
 constexpr size_t mg_lds_bytes(int mtiles) {
-  return sizeof(bf16_t) * (MG_WAVES * 64 * MG_ROWPAD + 2 * 3 * 32 * mtiles * MG_ROWPAD);
+  return sizeof(bf16_t) * (MG_WAVES * 64 * MG_ROWPAD + 2 * MG_PARTS * 32 * mtiles * MG_ROWPAD);
 }
 
 // ------------------------------------------------------------------ activation preparation
@@ -169,14 +175,14 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
     x_src[i] = min(row0 + m, m_rows - 1) * x_stride + kv;    // rows past the end repeat the last one
     x_dst[i] = m * MG_ROWPAD + kv;
   }
-  u32x4_t xr[XV][3];
+  u32x4_t xr[XV][MG_PARTS];
 
   {
     const int k_ = c_begin * MG_KC;
 #pragma unroll
     for (int i = 0; i < XV; ++i) {
 #pragma unroll
-      for (int p = 0; p < 3; ++p) xr[i][p] = *(const u32x4_t *)(xs + p * part_stride + x_src[i] + k_);
+      for (int p = 0; p < MG_PARTS; ++p) xr[i][p] = *(const u32x4_t *)(xs + p * part_stride + x_src[i] + k_);
     }
   }
   __builtin_amdgcn_sched_barrier(0);
@@ -185,7 +191,7 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
     for (int i = 0; i < XV; ++i) {
       if ((int)threadIdx.x + i * MG_THREADS < XPOS) {
 #pragma unroll
-        for (int p = 0; p < 3; ++p) *(u32x4_t *)(s_x + p * PART_ELEMS + x_dst[i]) = xr[i][p];
+        for (int p = 0; p < MG_PARTS; ++p) *(u32x4_t *)(s_x + p * PART_ELEMS + x_dst[i]) = xr[i][p];
       }
     }
   }
@@ -195,7 +201,7 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
 #pragma unroll
     for (int i = 0; i < XV; ++i) {
 #pragma unroll
-      for (int p = 0; p < 3; ++p) xr[i][p] = *(const u32x4_t *)(xs + p * part_stride + x_src[i] + k_);
+      for (int p = 0; p < MG_PARTS; ++p) xr[i][p] = *(const u32x4_t *)(xs + p * part_stride + x_src[i] + k_);
     }
   }
   __builtin_amdgcn_sched_barrier(0);
@@ -224,8 +230,8 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
         for (int i = 0; i < XV; ++i) {
           if ((int)threadIdx.x + i * MG_THREADS < XPOS) {
 #pragma unroll
-            for (int p = 0; p < 3; ++p)
-              *(u32x4_t *)(s_x + ((buf ^ 1) * 3 + p) * PART_ELEMS + x_dst[i]) = xr[i][p];
+            for (int p = 0; p < MG_PARTS; ++p)
+              *(u32x4_t *)(s_x + ((buf ^ 1) * MG_PARTS + p) * PART_ELEMS + x_dst[i]) = xr[i][p];
           }
         }
       }
@@ -235,7 +241,7 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
 #pragma unroll
         for (int i = 0; i < XV; ++i) {
 #pragma unroll
-          for (int p = 0; p < 3; ++p) xr[i][p] = *(const u32x4_t *)(xs + p * part_stride + x_src[i] + k_);
+          for (int p = 0; p < MG_PARTS; ++p) xr[i][p] = *(const u32x4_t *)(xs + p * part_stride + x_src[i] + k_);
         }
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -247,7 +253,7 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
       }
       __builtin_amdgcn_sched_barrier(0);
       if (chunk < c_end) {
-        const bf16_t *xb = s_x + buf * 3 * PART_ELEMS + a_off;
+        const bf16_t *xb = s_x + buf * MG_PARTS * PART_ELEMS + a_off;
 #pragma unroll
         for (int s = 0; s < MG_KC / 16; ++s) {
           const bf16x8_t a0 = __builtin_bit_cast(bf16x8_t, *(const u32x4_t *)(s_w + a_off + s * 16));
@@ -255,7 +261,7 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
           // smallest part first, so that the large terms are added last; consecutive MFMAs go to
           // different accumulators
 #pragma unroll
-          for (int p = 2; p >= 0; --p) {
+          for (int p = MG_PARTS - 1; p >= 0; --p) {
 #pragma unroll
             for (int c = 0; c < MTILES; ++c) {
               const bf16x8_t b = __builtin_bit_cast(
