@@ -72,6 +72,9 @@ def main() -> int:
                     help="apply the periodic rule to text positions too, with this period and phase 0")
     ap.add_argument("--aligned", action="store_true",
                     help="batch > 1: every sequence starts at cycle offset 0 (phase-aligned schedules)")
+    ap.add_argument("--speech-share", type=float, default=0.0,
+                    help="e.g. 0.795: the text ends early, so that this share of the warm-up + timed tokens is "
+                         "speech (the interleave alone gives n_speech / (n_text + n_speech))")
     ap.add_argument("--temperature", type=float, default=0.0,
                     help="> 0: draw tokens by temperature / nucleus sampling instead of the arg-max")
     ap.add_argument("--top-p", type=float, default=0.9)
@@ -140,6 +143,11 @@ def main() -> int:
                "frac_of_mfma_bf16_peak": round(pre_flops / prefill_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
 
     # ---- warm-up, then the timed region: exactly K steps, tokens fed back on the device
+    text_budget = 0
+    if args.speech_share > 0:
+        text_budget = max(1, round((1.0 - args.speech_share) * (W + K)))
+        for s_ in sids:
+            sp.seq_text_budget(s_, text_budget)
     sampled = args.temperature > 0
     if sampled:   # one 64-bit random word per step and sequence, drawn ahead of the timed region
         sp.set_sampling(args.temperature, args.top_p)
@@ -257,6 +265,7 @@ def main() -> int:
                                f"{'K_text=' + str(sched.text_period_k) + ', ' if sched.text_period_k > 1 else ''}"
                                f"scope={'chunk' if sched.scope == 0 else 'stream'}"
                                f"{', cycle offsets aligned' if args.aligned and B > 1 else ''}"
+                               f"{f', text ends after {text_budget} tokens (speech share {args.speech_share})' if text_budget else ''}"
                                f"{f', sampled T={args.temperature} top_p={args.top_p}' if sampled else ', greedy'}",
                    "weights": "random N(0,0.02), fp32 accumulation", "kv_cache": "paged, 64 tokens/page",
                    "step_mix": mix, "mean_speech_depth": stats["mean_speech_depth"],

@@ -128,6 +128,15 @@ int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_p
  * generated token falls (0 = first text slot).  Writes the id to *seq_id. */
 int spark_seq_open(spark_ctx *ctx, int32_t cycle_offset, int32_t *seq_id);
 
+/* The text of an interleaved response ends before its speech does (Sec. IV-A: speech tokens are
+ * 79.5 % / 81.2 % of what the two models generate, more than the 2/3 their interleave ratios alone
+ * give).  After n_text_tokens text tokens in all, this sequence generates speech only: the slots
+ * of the cycle that would be text become speech, and the speech chunk running at that moment goes
+ * on, so a per-chunk index (SPARK_SCOPE_CHUNK) keeps counting from that chunk's start.  May be
+ * set once per sequence, before or between steps, and not below the number of text tokens the
+ * sequence has generated already (SPARK_EINVAL; SPARK_ESTATE if a budget is set). */
+int spark_seq_text_budget(spark_ctx *ctx, int32_t seq_id, int32_t n_text_tokens);
+
 /* Condition on a prompt [host] of n >= 1 ids: positions 0..n-2 are run at full depth and fill
  * the KV of every layer; the last id is held as the input of the first spark_step, so that every
  * generated token comes out of spark_step with its executed depth.  One prompt per sequence. */

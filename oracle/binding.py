@@ -54,6 +54,8 @@ def load(kind: str = "f32") -> C.CDLL:
     lib.ora_step.argtypes = [P, I, P, P, P]
     lib.ora_step_standard.argtypes = [P, I, P, P, I, P]
     lib.ora_schedule_run.argtypes = [C.POINTER(OraConfig), I, I, P, P]
+    lib.ora_schedule_run_budget.argtypes = [C.POINTER(OraConfig), I, I, I, P, P]
+    lib.ora_seq_text_budget.argtypes = [P, I]
     lib.ora_layer_saving.restype = C.c_double
     lib.ora_layer_saving.argtypes = [P, I, I]
     for f in ("ora_seq_len", "ora_seq_upper_valid", "ora_seq_pending"):
@@ -103,13 +105,13 @@ def sample(logits, temperature: float, top_p: float, omega: int, kind: str = "f3
     return tok, n.value, gap.value
 
 
-def schedule_run(shape, sched, n_steps: int, cycle_offset: int = 0, kind: str = "f32"):
+def schedule_run(shape, sched, n_steps: int, cycle_offset: int = 0, kind: str = "f32", text_budget: int = 0):
     """(depth[n], is_text[n]) from the oracle's scheduler alone; None if the config is refused."""
     lib = load(kind)
     cfg = make_config(shape, sched, 1)
     depth = np.zeros(n_steps, dtype=np.int32)
     is_text = np.zeros(n_steps, dtype=np.int32)
-    rc = lib.ora_schedule_run(C.byref(cfg), cycle_offset, n_steps, _ptr(depth), _ptr(is_text))
+    rc = lib.ora_schedule_run_budget(C.byref(cfg), cycle_offset, text_budget, n_steps, _ptr(depth), _ptr(is_text))
     if rc != 0:
         return None
     return depth, is_text
@@ -158,6 +160,10 @@ class Seq:
         self.handle = self.lib.ora_seq_open(model.handle, cycle_offset)
         if not self.handle:
             raise MemoryError("oracle sequence")
+
+    def text_budget(self, budget: int) -> int:
+        """after `budget` text tokens in all the sequence generates speech only"""
+        return self.lib.ora_seq_text_budget(self.handle, budget)
 
     def close(self):
         if self.handle:

@@ -24,7 +24,8 @@ ERRORS = {-1: "SPARK_EINVAL", -2: "SPARK_ENOSEQ", -3: "SPARK_ENOMEM", -4: "SPARK
 EXPORTS = ("spark_workspace_bytes", "spark_init", "spark_seq_open", "spark_prefill", "spark_step",
            "spark_decode", "spark_get_logits", "spark_get_kv", "spark_seq_state",
            "spark_get_stats", "spark_seq_close", "spark_destroy", "spark_last_error",
-           "spark_profile_select", "spark_profile_read", "spark_set_sampling", "spark_decode_sampled")
+           "spark_profile_select", "spark_profile_read", "spark_set_sampling", "spark_decode_sampled",
+           "spark_seq_text_budget")
 
 
 class SparkConfig(C.Structure):
@@ -79,6 +80,7 @@ def load_library() -> C.CDLL:
     lib.spark_step.argtypes = [P, I, P, P, P, P]
     lib.spark_decode.argtypes = [P, I, I, P, P, P, P]
     lib.spark_set_sampling.argtypes = [P, C.c_float, C.c_float]
+    lib.spark_seq_text_budget.argtypes = [P, I, I]
     lib.spark_decode_sampled.argtypes = [P, I, I, P, P, P, P, P]
     lib.spark_get_logits.argtypes = [P, I, P, C.POINTER(I)]
     lib.spark_get_kv.argtypes = [P, I, I, I, P, P]
@@ -203,6 +205,9 @@ class Spark:
         self._check(self.lib.spark_decode(self.handle, n_steps, n, _iptr(ids),
                                           _iptr(f) if f is not None else None, _iptr(tok), _iptr(dep)))
         return tok, dep
+
+    def seq_text_budget(self, seq_id: int, n_text_tokens: int) -> None:
+        self._check(self.lib.spark_seq_text_budget(self.handle, seq_id, n_text_tokens))
 
     def set_sampling(self, temperature: float, top_p: float) -> None:
         self._check(self.lib.spark_set_sampling(self.handle, temperature, top_p))

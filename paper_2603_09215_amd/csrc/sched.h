@@ -9,8 +9,8 @@
 
 namespace spark {
 
-// device-resident per-sequence state, 8 ints
-enum { ST_LEN = 0, ST_G, ST_JSTREAM, ST_NPENDING, ST_OFFSET, ST_NEXT, ST_ACTIVE, ST_LASTFULL, ST_WORDS };
+// device-resident per-sequence state, 9 ints
+enum { ST_LEN = 0, ST_G, ST_JSTREAM, ST_NPENDING, ST_OFFSET, ST_NEXT, ST_ACTIVE, ST_LASTFULL, ST_TEXTBUDGET, ST_WORDS };
 // plan words
 enum { PL_NLOWER = 0, PL_NUPPER, PL_NEE, PL_NFULL, PL_ERR, PL_BARRIER_ERR, PL_WORDS = 8 };
 enum { ERR_NAN = 1, ERR_INACTIVE = 2, ERR_BARRIER = 4 };
@@ -28,14 +28,33 @@ struct SchedParams {
 // full depth unless a text period is given: then the text position with index t (its slot inside
 // the chunk, or the count of text positions emitted so far, g - j_stream) follows the same rule
 // with (text_period_k, text_phase).
-__host__ __device__ inline void schedule_decide(const SchedParams &sp, int g, int offset,
-                                                int j_stream, int &is_text, int &full) {
+//
+// The text of a response ends before its speech (Sec. IV-A: speech is 79.5 % / 81.2 % of the
+// generated tokens, more than the 2/3 the interleave ratios alone give).  text_budget B > 0: once
+// B text tokens have been emitted every position is speech, and the chunk then running goes on,
+// so its index is the number of positions since the B-th text token.  That token's place in the
+// stream follows from the cycle alone, which keeps the schedule a function of the counters.
+__host__ __device__ inline int nth_text_position(const SchedParams &sp, int offset, int b /* 1-based */) {
+  const int cyc = sp.n_text + sp.n_speech, off = offset % cyc;
+  const int first = off < sp.n_text ? sp.n_text - off : 0;   // text slots left in the cycle entered
+  if (b <= first) return b - 1;
+  const int rest = b - first - 1;
+  return (cyc - off) + (rest / sp.n_text) * cyc + rest % sp.n_text;
+}
+
+__host__ __device__ inline void schedule_decide(const SchedParams &sp, int g, int offset, int j_stream,
+                                                int text_budget, int &is_text, int &full) {
   const int cyc = sp.n_text + sp.n_speech;
   const int slot = (int)(((long long)g + offset) % cyc);
-  is_text = slot < sp.n_text;
+  const int texts = g - j_stream;                 // text positions so far
+  const bool text_over = text_budget > 0 && texts >= text_budget;
+  is_text = slot < sp.n_text && !text_over;
   const int period = is_text ? sp.text_period_k : sp.period_k;
   const int want = is_text ? sp.text_phase : sp.phase;
-  const int idx = sp.scope == 0 ? (is_text ? slot : slot - sp.n_text) : (is_text ? g - j_stream : j_stream);
+  int idx;
+  if (is_text) idx = sp.scope == 0 ? slot : texts;
+  else if (sp.scope != 0) idx = j_stream;
+  else idx = text_over ? g - nth_text_position(sp, offset, text_budget) - 1 : slot - sp.n_text;
   full = sp.exit_layer == sp.n_layers || period <= 1 || idx % period == want;
 }
 
@@ -54,7 +73,7 @@ sched_dispatch_k(SchedParams sp, int n, const int *__restrict__ seq_ids, const i
     const int *st = state + seq * ST_WORDS;
     len = st[ST_LEN];
     npend = st[ST_NPENDING];
-    schedule_decide(sp, st[ST_G], st[ST_OFFSET], st[ST_JSTREAM], is_text, full);
+    schedule_decide(sp, st[ST_G], st[ST_OFFSET], st[ST_JSTREAM], st[ST_TEXTBUDGET], is_text, full);
     lower[i] = RowDesc{seq * sp.rmax + npend, seq, len, i};
     out_depth[i] = full ? sp.n_layers : sp.exit_layer;
     step_flags[i] = full | (is_text << 1);

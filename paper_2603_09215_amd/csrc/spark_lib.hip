@@ -44,6 +44,7 @@ struct Derived {
 struct Seq {
   bool open = false, prefilled = false;
   int cycle_offset = 0, len = 0, g = 0, j_stream = 0, n_pending = 0, last_full = 0;
+  int text_budget = 0;   // > 0: speech only after this many text tokens
   std::vector<int> pages;
   int64_t text_steps = 0, speech_full = 0, speech_ee = 0, text_ee = 0;
   int64_t flush_rows[2 * SPARK_MAX_PERIOD] = {0};
@@ -152,7 +153,7 @@ bool config_ok(const spark_config *c, char *why, size_t n) {
     bool any_full = false;
     for (int g = 0; g < 2 * cyc; ++g) {
       int is_text, full;
-      schedule_decide(sp, g, 0, 0, is_text, full);
+      schedule_decide(sp, g, 0, 0, 0, is_text, full);
       if (full) { any_full = true; run = 0; } else { longest = std::max(longest, ++run); }
     }
     BAD(!any_full, "a cycle without a full-depth slot would never complete its KV");
@@ -811,7 +812,8 @@ int decode_chunk(spark_ctx *c, int steps, int n, const int32_t *seq_ids, const i
     c->attn_splits_now = max_pos / ATTN_SLICE + 1;
     for (int i = 0; i < n; ++i) {
       int is_text, full;
-      schedule_decide(c->sp, mir[i].g, c->seqs[seq_ids[i]].cycle_offset, mir[i].j, is_text, full);
+      const Seq &sq = c->seqs[seq_ids[i]];
+      schedule_decide(c->sp, mir[i].g, sq.cycle_offset, mir[i].j, sq.text_budget, is_text, full);
       want_depth[st * n + i] = full ? g.n_layers : g.exit_layer;
       want_text[st * n + i] = is_text;
       want_rows[st * n + i] = full ? mir[i].npend + 1 : 0;
@@ -1034,6 +1036,7 @@ int spark_prefill(spark_ctx *c, int32_t seq_id, const int32_t *prompt, int32_t n
   st[ST_OFFSET] = s->cycle_offset;
   st[ST_NEXT] = prompt[n - 1];
   st[ST_ACTIVE] = 1;
+  st[ST_TEXTBUDGET] = s->text_budget;
   HIP_TRY(c, hipMemcpyAsync(at<int>(c, c->lo.state) + (size_t)seq_id * ST_WORDS, st, sizeof(st),
                             hipMemcpyHostToDevice, c->stream));
   HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -1128,6 +1131,24 @@ int spark_get_kv(spark_ctx *c, int32_t seq_id, int32_t layer, int32_t pos, float
         }
       }
     }
+  return SPARK_OK;
+}
+
+int spark_seq_text_budget(spark_ctx *c, int32_t seq_id, int32_t n_text_tokens) {
+  if (!c) return SPARK_EINVAL;
+  Seq *s = find_seq(c, seq_id);
+  if (!s) return fail(c, SPARK_ENOSEQ, "unknown sequence id %d", seq_id);
+  if (n_text_tokens < 1) return fail(c, SPARK_EINVAL, "text budget < 1");
+  if (s->text_budget > 0) return fail(c, SPARK_ESTATE, "sequence %d already has a text budget", seq_id);
+  if (n_text_tokens < s->g - s->j_stream)
+    return fail(c, SPARK_EINVAL, "sequence %d has generated more text tokens already", seq_id);
+  if (c->cfg.n_text < 1) return fail(c, SPARK_EINVAL, "the interleave has no text slots");
+  s->text_budget = n_text_tokens;
+  if (s->prefilled) {   // the state is on the device already
+    HIP_TRY(c, hipMemcpyAsync(at<int>(c, c->lo.state) + (size_t)seq_id * ST_WORDS + ST_TEXTBUDGET,
+                              &s->text_budget, sizeof(int), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+  }
   return SPARK_OK;
 }
 

@@ -18,10 +18,13 @@ def say(msg: str) -> None:
 
 
 def compare_run(spark, shape, sched, weights, prompts, offsets, n_steps, forced_seed=2,
-                check_kv_every=0, chunk=1, oracle_kind="f32", label="", kv_round_bf16=None):
+                check_kv_every=0, chunk=1, oracle_kind="f32", label="", kv_round_bf16=None,
+                text_budgets=None):
     """Run len(prompts) sequences for n_steps teacher-forced steps on both sides.
 
-    chunk > 1 uses spark_decode with that many steps per call.  Returns a dict of what was seen.
+    chunk > 1 uses spark_decode with that many steps per call.  text_budgets: per sequence, the
+    number of text tokens after which it generates speech only (0: none).  Returns a dict of what
+    was seen.
     Asserts: depths bit-exact; logits within tolerance of the oracle's; tokens equal except at
     logged near-ties (oracle gap between its own argmax and the GPU's token <= 2 * tol)."""
     tol = TOL[shape.dtype]
@@ -39,6 +42,9 @@ def compare_run(spark, shape, sched, weights, prompts, offsets, n_steps, forced_
     for b in range(B):
         assert oseqs[b].prefill(prompts[b]) == 0
         spark.prefill(sids[b], prompts[b])
+        if text_budgets is not None and text_budgets[b] > 0:
+            assert oseqs[b].text_budget(text_budgets[b]) == 0
+            spark.seq_text_budget(sids[b], text_budgets[b])
     worst, near_ties, depths = 0.0, [], []
     step = 0
     while step < n_steps:

@@ -280,3 +280,42 @@ def test_batched_decode_on_the_mfma_path(sb):
                     label="batch24 bf16")
     assert len(np.unique(a["depths"], axis=1)) > 1
     sp.close()
+
+
+def test_text_ends_before_the_speech(sb, tiny_weights):
+    """Sec. IV-A: after a sequence's text budget every position is speech.  Per-chunk and stream
+    counters, several sequences with different budgets and cycle offsets in one batch, multi-step
+    calls; and a budget that is set between two steps."""
+    w = wl.TINY
+    say("case text budget")
+    for scope in (wl.SCOPE_CHUNK, wl.SCOPE_STREAM):
+        sched = w.schedule.replace(scope=scope)
+        sp = sb.Spark(w.shape, sched, tiny_weights, max_batch=4, max_seq_len=160, kv_page_tokens=16)
+        prompts = [wl.make_prompt(w.shape, 10 + 3 * b, seed=20 + b) for b in range(4)]
+        res = compare_run(sp, w.shape, sched, tiny_weights, prompts, [0, 1, 4, 5], 60, chunk=5,
+                          text_budgets=[3, 7, 0, 1], label=f"text budget scope {scope}")
+        texts = [st["text"] for st in res["stats"]]
+        assert texts[0] == 3 and texts[1] == 7 and texts[3] == 1 and texts[2] >= 20
+        sp.close()
+    # set between steps: "the text has just ended"
+    from oracle import binding as ob
+    sp = sb.Spark(w.shape, w.schedule, tiny_weights, max_batch=1, max_seq_len=96, kv_page_tokens=16)
+    om = ob.Model(w.shape, w.schedule, tiny_weights, max_seq_len=96)
+    sid, os_ = sp.seq_open(0), om.open(0)
+    prompt = wl.make_prompt(w.shape, 8, seed=3)
+    sp.prefill(sid, prompt)
+    assert os_.prefill(prompt) == 0
+    forced = wl.make_forced_stream(w.shape, 40, 2, 4, 0, seed=5)
+    for i in range(40):
+        if i == 8:      # two text tokens of the first cycle and two of the second are out
+            with pytest.raises(sb.SparkError):
+                sp.seq_text_budget(sid, 3)                   # fewer than already generated
+            sp.seq_text_budget(sid, 4)
+            assert os_.text_budget(4) == 0
+            with pytest.raises(sb.SparkError):
+                sp.seq_text_budget(sid, 9)                   # only once
+        tok, dep = sp.step([sid], [forced[i]])
+        rc, otok, odep, _ = os_.step(forced_next=int(forced[i]))
+        assert rc == 0 and dep[0] == odep, (i, dep[0], odep)
+    assert sp.get_stats(sid)["text"] == 4 == os_.stats()["text"]
+    os_.close(); om.close(); sp.close()

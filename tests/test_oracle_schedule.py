@@ -223,3 +223,91 @@ def test_refused_configs():
     for kw in bad:
         s = wl.TINY.schedule.replace(**kw)
         assert ob.schedule_run(wl.TINY.shape, s, 8) is None, kw
+
+
+# ---------------------------------------------------------------- the text ends before the speech
+
+def brute_force_with_text_budget(L, e, K, phase, scope, nt, ns, n, off, budget):
+    """Sec. IV-A: speech is most of a response because the text ends first.  Written out position
+    by position from a list of what has been generated: a slot of the cycle is text while fewer
+    than `budget` text tokens exist; a speech position's index is its place among all speech
+    (stream) or the number of speech positions since the last text one (chunk: the chunk that runs
+    when the text ends goes on)."""
+    kinds, depth = [], []
+    cyc = nt + ns
+    for g in range(n):
+        slot = (g + off) % cyc
+        kind = "t" if slot < nt and kinds.count("t") < budget else "s"
+        if kind == "t":
+            full = True
+        else:
+            if scope == wl.SCOPE_STREAM:
+                idx = kinds.count("s")
+            elif "t" in kinds:
+                idx = g - 1 - max(i for i, k in enumerate(kinds) if k == "t")
+            else:           # no text yet: the sequence entered the cycle inside a speech chunk
+                idx = g + (off % cyc) - nt if (off % cyc) >= nt else g
+                # (entered on a text slot with a spent budget cannot happen: budget >= 1)
+            full = e == L or K == 1 or idx % K == phase
+        kinds.append(kind)
+        depth.append(L if full else e)
+    return np.array(depth), np.array([1 if k == "t" else 0 for k in kinds])
+
+
+def test_text_budget_against_brute_force():
+    rng = np.random.default_rng(17)
+    L, checked, tails = 12, 0, 0
+    for _ in range(300):
+        e = int(rng.integers(1, L))
+        K = int(rng.integers(1, 6))
+        phase = int(rng.integers(0, K))
+        nt, ns = int(rng.integers(1, 5)), int(rng.integers(1, 8))
+        scope = int(rng.integers(0, 2))
+        off = int(rng.integers(0, nt + ns))
+        budget = int(rng.integers(1, 4 * nt + 2))
+        n = 8 * (nt + ns)
+        sched = wl.Schedule(e, K, phase, scope, nt, ns)
+        res = ob.schedule_run(shape_with_layers(L), sched, n, off, text_budget=budget)
+        if res is None:
+            continue
+        want_d, want_t = brute_force_with_text_budget(L, e, K, phase, scope, nt, ns, n, off, budget)
+        assert list(res[1]) == list(want_t), (nt, ns, off, budget)
+        assert list(res[0]) == list(want_d), (e, K, phase, scope, nt, ns, off, budget)
+        assert res[1].sum() == min(budget, want_t.sum()) == budget      # exactly the budget, then none
+        last_text = int(np.flatnonzero(res[1])[-1])
+        assert not res[1][last_text + 1:].any()
+        tails += int(n - last_text > nt + ns)
+        checked += 1
+    assert checked > 150 and tails > 100
+
+
+def test_text_budget_reproduces_the_speech_share_of_the_paper():
+    """Sec. IV-A: 79.5 % (Step-Audio-2, 1:2) and 81.2 % (GLM-4-Voice, 13:26) of the generated
+    tokens are speech.  The budget that gives that share over a response, and the closed forms of
+    the tail: one full-depth position every K in it, mean speech depth from the counts."""
+    for (nt, ns, L, e, share, n) in [(1, 2, 28, 20, 0.795, 1024), (13, 26, 40, 32, 0.812, 1024)]:
+        budget = round((1.0 - share) * n)
+        K, phase = 4, 3
+        for scope in (wl.SCOPE_STREAM, wl.SCOPE_CHUNK):
+            sched = wl.Schedule(e, K, phase, scope, nt, ns)
+            depth, is_text = ob.schedule_run(shape_with_layers(L), sched, n, 0, text_budget=budget)
+            assert is_text.sum() == budget
+            assert abs((1 - is_text.mean()) - share) < 0.5 / n + 1e-12
+            speech = depth[is_text == 0]
+            last_text = int(np.flatnonzero(is_text)[-1])
+            tail = depth[last_text + 1:]
+            full_at = np.flatnonzero(tail == L)
+            assert len(full_at) >= 3 and np.all(np.diff(full_at) == K)      # periodic refresh goes on
+            if scope == wl.SCOPE_STREAM:
+                S = len(speech)
+                n_full = (S - 1 - phase) // K + 1                             # j = phase, phase + K, ...
+                assert (speech == L).sum() == n_full
+                assert speech.mean() == pytest.approx((n_full * L + (S - n_full) * e) / S, abs=1e-12)
+            else:
+                assert full_at[0] == phase                                    # the tail's chunk index starts at 0
+    # an unlimited budget is the plain cycle
+    sched = wl.Schedule(20, 4, 3, wl.SCOPE_CHUNK, 1, 2)
+    a = ob.schedule_run(shape_with_layers(28), sched, 60, 1)
+    b = ob.schedule_run(shape_with_layers(28), sched, 60, 1, text_budget=0)
+    c = ob.schedule_run(shape_with_layers(28), sched, 60, 1, text_budget=10 ** 6)
+    assert list(a[0]) == list(b[0]) == list(c[0]) and list(a[1]) == list(c[1])
