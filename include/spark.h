@@ -117,6 +117,13 @@ typedef struct spark_ctx spark_ctx;
  * Returns SPARK_EINVAL for a configuration the library refuses. */
 int spark_workspace_bytes(const spark_config *cfg, size_t *kv_pool_bytes, size_t *scratch_bytes);
 
+/* The schedule alone (Sec. IV-B.1), no device needed: executed depth (exit_layer or n_layers) and
+ * modality (1 = text) of the first n_steps generated tokens of a sequence opened at cycle_offset
+ * with the given text budget (<= 0: none; see spark_seq_text_budget).  depth_out, is_text_out
+ * [host], n_steps entries each.  It evaluates the same function the dispatch kernel evaluates. */
+int spark_schedule_preview(const spark_config *cfg, int32_t cycle_offset, int32_t text_budget,
+                           int32_t n_steps, int32_t *depth_out, int32_t *is_text_out);
+
 /* Create a context.  kv_pool and scratch [device] must be at least the sizes reported above and
  * 256-byte aligned; hip_stream is a hipStream_t (NULL = the default stream) on which every kernel
  * of this context is launched.  The weights struct is copied; the tensors are not. */

@@ -25,7 +25,7 @@ EXPORTS = ("spark_workspace_bytes", "spark_init", "spark_seq_open", "spark_prefi
            "spark_decode", "spark_get_logits", "spark_get_kv", "spark_seq_state",
            "spark_get_stats", "spark_seq_close", "spark_destroy", "spark_last_error",
            "spark_profile_select", "spark_profile_read", "spark_set_sampling", "spark_decode_sampled",
-           "spark_seq_text_budget")
+           "spark_seq_text_budget", "spark_schedule_preview")
 
 
 class SparkConfig(C.Structure):
@@ -81,6 +81,7 @@ def load_library() -> C.CDLL:
     lib.spark_decode.argtypes = [P, I, I, P, P, P, P]
     lib.spark_set_sampling.argtypes = [P, C.c_float, C.c_float]
     lib.spark_seq_text_budget.argtypes = [P, I, I]
+    lib.spark_schedule_preview.argtypes = [C.POINTER(SparkConfig), I, I, I, P, P]
     lib.spark_decode_sampled.argtypes = [P, I, I, P, P, P, P, P]
     lib.spark_get_logits.argtypes = [P, I, P, C.POINTER(I)]
     lib.spark_get_kv.argtypes = [P, I, I, I, P, P]
@@ -104,6 +105,18 @@ def make_config(shape, sched, max_batch: int, max_seq_len: int, kv_page_tokens: 
                        sched.exit_layer, sched.period_k, sched.phase, sched.scope, sched.n_text,
                        sched.n_speech, max_batch, max_seq_len, kv_page_tokens,
                        getattr(sched, "text_period_k", 0), getattr(sched, "text_phase", 0))
+
+
+def schedule_preview(shape, sched, n_steps: int, cycle_offset: int = 0, text_budget: int = 0):
+    """(depth[n], is_text[n]) from the library's own schedule function, on the host; None if the
+    configuration is refused"""
+    lib = load_library()
+    cfg = make_config(shape, sched, 1, 64, 16)
+    depth = np.zeros(n_steps, dtype=np.int32)
+    is_text = np.zeros(n_steps, dtype=np.int32)
+    rc = lib.spark_schedule_preview(C.byref(cfg), cycle_offset, text_budget, n_steps,
+                                    C.c_void_p(depth.ctypes.data), C.c_void_p(is_text.ctypes.data))
+    return (depth, is_text) if rc == 0 else None
 
 
 def _iptr(a: np.ndarray):

@@ -923,6 +923,24 @@ int spark_workspace_bytes(const spark_config *cfg, size_t *kv_pool_bytes, size_t
   return SPARK_OK;
 }
 
+int spark_schedule_preview(const spark_config *cfg, int32_t cycle_offset, int32_t text_budget,
+                           int32_t n_steps, int32_t *depth_out, int32_t *is_text_out) {
+  char why[128];
+  if (!cfg || !config_ok(cfg, why, sizeof(why)) || cycle_offset < 0 || n_steps < 0 || !depth_out ||
+      !is_text_out || (text_budget > 0 && cfg->n_text < 1))
+    return SPARK_EINVAL;
+  const SchedParams sp = sched_params(cfg);
+  int j_stream = 0;
+  for (int g = 0; g < n_steps; ++g) {
+    int is_text, full;
+    schedule_decide(sp, g, cycle_offset, j_stream, text_budget, is_text, full);   // the function the device runs
+    depth_out[g] = full ? cfg->n_layers : cfg->exit_layer;
+    is_text_out[g] = is_text;
+    if (!is_text) ++j_stream;
+  }
+  return SPARK_OK;
+}
+
 int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_pool,
                size_t kv_pool_bytes, void *scratch, size_t scratch_bytes, void *hip_stream,
                spark_ctx **out) {
