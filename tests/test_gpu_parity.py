@@ -319,3 +319,27 @@ def test_text_ends_before_the_speech(sb, tiny_weights):
         assert rc == 0 and dep[0] == odep, (i, dep[0], odep)
     assert sp.get_stats(sid)["text"] == 4 == os_.stats()["text"]
     os_.close(); om.close(); sp.close()
+
+
+@pytest.mark.parametrize("name,shape_kw,page,long_prompt", [
+    # MFMA attention (bf16 cache, head_dim 128): 36 slices, a slice inside one 64-token page
+    ("bf16-hd128-long", dict(dtype=wl.DTYPE_BF16, n_layers=3, d_model=512, n_q_heads=4, n_kv_heads=2,
+                             head_dim=128, d_ffn=1024), 64, 2300),
+    # the same kernel with slices that span four 16-token pages
+    ("bf16-hd128-small-pages", dict(dtype=wl.DTYPE_BF16, n_layers=3, d_model=512, n_q_heads=4, n_kv_heads=2,
+                                    head_dim=128, d_ffn=1024), 16, 900),
+    # vector attention (fp32), 19 slices
+    ("fp32-long", dict(), 64, 1200),
+])
+def test_long_contexts(sb, name, shape_kw, page, long_prompt):
+    """contexts of many attention slices: the merge runs several rounds of eight partials, the
+    prompt passes see rows whose contexts differ by a whole pass, a short sequence shares the batch"""
+    shape = wl.TINY.shape.replace(name=name, **shape_kw)
+    sched = wl.TINY.schedule.replace(exit_layer=2, n_text=1, n_speech=2, scope=wl.SCOPE_STREAM)
+    say(f"case long context {name}")
+    weights = wl.make_weights(shape, seed=6, gain_std=0.1)
+    sp = sb.Spark(shape, sched, weights, max_batch=2, max_seq_len=long_prompt + 64, kv_page_tokens=page)
+    prompts = [wl.make_prompt(shape, long_prompt, seed=7), wl.make_prompt(shape, 70, seed=8)]
+    res = compare_run(sp, shape, sched, weights, prompts, [0, 2], 24, check_kv_every=8, chunk=3, label=name)
+    assert len(np.unique(res["depths"])) == 2
+    sp.close()
