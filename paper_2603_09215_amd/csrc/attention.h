@@ -44,14 +44,14 @@ template <int HD, int G, int NT> constexpr int attn_lds_floats() {
 // out = sum_s exp(m_s - M) o_s / sum_s exp(m_s - M) l_s.
 template <int HD, int NT, bool DS>
 __device__ __forceinline__ void attn_merge(const RowDesc &rd, int r, int hq0, int g_count, int nq,
-                                           int n_splits, const float *__restrict__ part,
+                                           int n_splits, int slice_tokens, const float *__restrict__ part,
                                            int *__restrict__ cnt, float *__restrict__ out,
                                            const SplitOut &so, int *s_last) {
   constexpr int PS = HD + 4;
   const int tid = threadIdx.x % NT;
   // Partials are written through to memory (device-scope stores) and counted with a device-scope
   // atomic; the merging workgroup drops its stale cache lines once and then reads them normally.
-  const int used = (rd.pos + ATTN_SLICE) / ATTN_SLICE;   // slices that intersect the context
+  const int used = rd.pos / slice_tokens + 1;   // slices that intersect the context
   wait_memory_ops();                                      // partials written before the count
   task_sync<NT>();
   if (tid == 0) {
@@ -230,7 +230,7 @@ __device__ __forceinline__ void attn_task(const RowDesc &rd, int r, int hk, int 
     store_device_scope(part + ((size_t)(r * nq + hq0 + g) * n_splits + split) * PS + HD + w,
                        ml[g * 2 + w]);
   }
-  attn_merge<HD, NT, DS>(rd, r, hq0, g_count, nq, n_splits, part, cnt, out, so, s_last);
+  attn_merge<HD, NT, DS>(rd, r, hq0, g_count, nq, n_splits, ATTN_SLICE, part, cnt, out, so, s_last);
 }
 
 // stand-alone launch: one workgroup per (slice, group of G query heads, row).  A KV head's `group`
@@ -271,151 +271,202 @@ typedef unsigned int attn_u32x2_t __attribute__((ext_vector_type(2)));
 
 constexpr int AM_VPITCH = 130;   // bf16 elements per V row in LDS: 65 dwords, so the four token groups of a gather hit different banks
 constexpr int AM_PPITCH = 72;    // tokens per P row in LDS (16-byte aligned rows)
+constexpr int AM_QPITCH = 136;   // elements per Q row in LDS (16-byte aligned rows, 4 dwords of skew)
 
 __device__ __forceinline__ unsigned pack_bf16(bf16_t lo, bf16_t hi) { return (unsigned)lo | ((unsigned)hi << 16); }
 
+// loads of one 64-token piece: V as the workgroup stages it, K as this wave's A operand
+struct AttnPiece {
+  attn_u32x4_t v[4];
+  attn_bf16x8_t k[4];
+};
+
+template <int HD>
+__device__ __forceinline__ void attn_piece_load(AttnPiece &pc, const KVView &kv, const bf16_t *pool, int seq,
+                                                int layer, int hk, int t0, int n_tok, bool one_page,
+                                                int tid, int wave, int col, int quad) {
+  // tokens beyond the context read token t0 instead (it exists) and are masked later.  With pages
+  // of a multiple of 64 tokens the piece lies inside one page: one address for the workgroup.
+  const size_t piece_k = one_page ? kv_elem_offset(kv, seq, t0, layer, 0, hk) : 0;
+  const size_t piece_v = one_page ? kv_elem_offset(kv, seq, t0, layer, 1, hk) : 0;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int t = it * 16 + (tid >> 4), tt = t < n_tok ? t : 0;
+    const size_t o = one_page ? piece_v + (size_t)tt * HD : kv_elem_offset(kv, seq, t0 + tt, layer, 1, hk);
+    pc.v[it] = *(const attn_u32x4_t *)(pool + o + (tid & 15) * 8);
+  }
+  const int t = 16 * wave + col, tt = t < n_tok ? t : 0;
+  const size_t o = one_page ? piece_k + (size_t)tt * HD : kv_elem_offset(kv, seq, t0 + tt, layer, 0, hk);
+  const bf16_t *kp = pool + o + quad * 8;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) pc.k[s] = __builtin_bit_cast(attn_bf16x8_t, *(const attn_u32x4_t *)(kp + 32 * s));
+}
+
+// `pieces` 64-token pieces per workgroup (slice = 64 * pieces tokens): a workgroup's life is mostly
+// dependent round trips (row descriptor, page table, K/V, partial, arrival), so with many rows it
+// pays to put several pieces behind one such chain; the pieces are folded with a running maximum.
 template <int HD>
 __global__ void __launch_bounds__(ATTN_THREADS)
 attn_rows_mfma_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbuf, KVView kv, int layer,
-                 int nq, int group, int n_splits, float scale, float *__restrict__ part,
+                 int nq, int group, int n_splits, int pieces, float scale, float *__restrict__ part,
                  int *__restrict__ arrivals, float *__restrict__ out, SplitOut so) {
   static_assert(HD == 128, "four 32-wide steps per key row, four waves of 32 value columns");
   constexpr int PS = HD + 4;
   __shared__ __align__(16) bf16_t s_v[ATTN_SLICE * AM_VPITCH];
   __shared__ __align__(16) bf16_t s_p[2 * 16 * AM_PPITCH];
-  __shared__ float s_max[4 * 16], s_sum[4 * 16];
+  __shared__ __align__(16) bf16_t s_q[3 * 16 * AM_QPITCH];
+  __shared__ float s_max[4 * 16], s_sum[4 * 16], s_alpha[16];
   __shared__ int s_last;
   const int split = blockIdx.x, hk = blockIdx.y, r = blockIdx.z;
   const RowDesc rd = rows[r];
-  if (split * ATTN_SLICE > rd.pos) return;        // slice beyond the row's context
-  const int t0 = split * ATTN_SLICE;
-  const int n_tok = min(ATTN_SLICE, rd.pos + 1 - t0);
+  const int span = ATTN_SLICE * pieces;
+  if (split * span > rd.pos) return;              // slice beyond the row's context
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 15, quad = lane >> 4;    // operand column / row, and which eight of a 32-wide step
   const int hq0 = hk * group;
   const bf16_t *pool = (const bf16_t *)kv.pool;
-
-  // every load of the slice; tokens beyond the context read token t0 instead (it exists) and are
-  // masked below.  With pages of a multiple of 64 tokens the slice lies inside one page and its
-  // address is worked out once for the workgroup.
   const bool one_page = (kv.page_tokens & (ATTN_SLICE - 1)) == 0;
-  const size_t slice_k = one_page ? kv_elem_offset(kv, rd.seq, t0, layer, 0, hk) : 0;
-  const size_t slice_v = one_page ? kv_elem_offset(kv, rd.seq, t0, layer, 1, hk) : 0;
-  attn_u32x4_t vraw[4];
-#pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int t = it * 16 + (tid >> 4), tt = t < n_tok ? t : 0;
-    const size_t o = one_page ? slice_v + (size_t)tt * HD : kv_elem_offset(kv, rd.seq, t0 + tt, layer, 1, hk);
-    vraw[it] = *(const attn_u32x4_t *)(pool + o + (tid & 15) * 8);
-  }
-  attn_bf16x8_t ka[4];
+  const int n_pieces = min(pieces, (rd.pos - split * span) / ATTN_SLICE + 1);   // pieces the context reaches
+
+  AttnPiece cur;
+  attn_piece_load<HD>(cur, kv, pool, rd.seq, layer, hk, split * span, min(ATTN_SLICE, rd.pos + 1 - split * span),
+                      one_page, tid, wave, col, quad);
+
+  // the scaled queries as three bf16 parts that add up to the fp32 value (each part keeps the
+  // upper 8 significant bits of what the parts before it left: truncation, exact remainders):
+  // split once by the workgroup, eight elements per thread, and handed to the waves through LDS
   {
-    const int t = 16 * wave + col, tt = t < n_tok ? t : 0;
-    const size_t o = one_page ? slice_k + (size_t)tt * HD : kv_elem_offset(kv, rd.seq, t0 + tt, layer, 0, hk);
-    const bf16_t *kp = pool + o + quad * 8;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) ka[s] = __builtin_bit_cast(attn_bf16x8_t, *(const attn_u32x4_t *)(kp + 32 * s));
-  }
-  // the scaled queries as three bf16 parts that add up to the fp32 value: each part keeps the
-  // upper 8 significant bits of what the parts before it left (truncation, exact remainders)
-  attn_bf16x8_t qb[3][4];
-  {
-    const float *qp = qbuf + ((size_t)r * nq + hq0 + min(col, group - 1)) * HD + quad * 8;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const float4 q0 = *(const float4 *)(qp + 32 * s), q1 = *(const float4 *)(qp + 32 * s + 4);
+    const int h = tid >> 4, e0 = (tid & 15) * 8;
+    attn_u32x4_t ph = {0u, 0u, 0u, 0u}, pm = ph, pl = ph;
+    if (h < group) {
+      const float *qp = qbuf + ((size_t)r * nq + hq0 + h) * HD + e0;
+      const float4 q0 = *(const float4 *)qp, q1 = *(const float4 *)(qp + 4);
       const float qf[8] = {q0.x * scale, q0.y * scale, q0.z * scale, q0.w * scale,
                            q1.x * scale, q1.y * scale, q1.z * scale, q1.w * scale};
-      unsigned h[8], m[8], l[8];
+      unsigned hi[8], mi[8], lo[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        h[e] = __float_as_uint(qf[e]) & 0xffff0000u;
-        const float r1 = qf[e] - __uint_as_float(h[e]);
-        m[e] = __float_as_uint(r1) & 0xffff0000u;
-        l[e] = __float_as_uint(r1 - __uint_as_float(m[e]));   // at most 8 significant bits are left
+        hi[e] = __float_as_uint(qf[e]) & 0xffff0000u;
+        const float r1 = qf[e] - __uint_as_float(hi[e]);
+        mi[e] = __float_as_uint(r1) & 0xffff0000u;
+        lo[e] = __float_as_uint(r1 - __uint_as_float(mi[e]));   // at most 8 significant bits are left
       }
-      attn_u32x4_t ph, pm, pl;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        ph[e] = (h[2 * e] >> 16) | h[2 * e + 1];
-        pm[e] = (m[2 * e] >> 16) | m[2 * e + 1];
-        pl[e] = (l[2 * e] >> 16) | (l[2 * e + 1] & 0xffff0000u);
+        ph[e] = (hi[2 * e] >> 16) | hi[2 * e + 1];
+        pm[e] = (mi[2 * e] >> 16) | mi[2 * e + 1];
+        pl[e] = (lo[2 * e] >> 16) | (lo[2 * e + 1] & 0xffff0000u);
       }
-      qb[0][s] = __builtin_bit_cast(attn_bf16x8_t, ph);
-      qb[1][s] = __builtin_bit_cast(attn_bf16x8_t, pm);
-      qb[2][s] = __builtin_bit_cast(attn_bf16x8_t, pl);
     }
+    *(attn_u32x4_t *)(s_q + (0 * 16 + h) * AM_QPITCH + e0) = ph;
+    *(attn_u32x4_t *)(s_q + (1 * 16 + h) * AM_QPITCH + e0) = pm;
+    *(attn_u32x4_t *)(s_q + (2 * 16 + h) * AM_QPITCH + e0) = pl;
   }
 
-  // V into LDS as it lies in the cache (4-byte stores: the row pitch is an odd number of dwords)
-#pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    unsigned *dst = (unsigned *)(s_v + (it * 16 + (tid >> 4)) * AM_VPITCH + (tid & 15) * 8);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) dst[e] = vraw[it][e];
-  }
+  // running state.  Score layout: lane = (head col, tokens 4*quad + i of the wave's 16);
+  // output layout: lane = (hd 32*wave + 16*t + col, heads 4*quad + i).
+  float run_max = -INFINITY, run_sum = 0.f;       // of head `col`; the sum is this wave's share
+  attn_f32x4_t oacc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 
-  // scores of this wave's 16 tokens: lane holds head `col`, tokens 16*wave + 4*quad + i
-  attn_f32x4_t sc = {0.f, 0.f, 0.f, 0.f};
+  for (int j = 0; j < n_pieces; ++j) {
+    const int t0 = split * span + j * ATTN_SLICE;
+    const int n_tok = min(ATTN_SLICE, rd.pos + 1 - t0);
+    if (j > 0) __syncthreads();                   // the last piece's V and P have been consumed
+    // V into LDS as it lies in the cache (4-byte stores: the row pitch is an odd number of dwords)
 #pragma unroll
-  for (int s = 0; s < 4; ++s)
+    for (int it = 0; it < 4; ++it) {
+      unsigned *dst = (unsigned *)(s_v + (it * 16 + (tid >> 4)) * AM_VPITCH + (tid & 15) * 8);
 #pragma unroll
-    for (int p = 0; p < 3; ++p) sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[s], qb[p][s], sc, 0, 0, 0);
-  const int tok0 = 16 * wave + 4 * quad;
-  float mw = -INFINITY;
+      for (int e = 0; e < 4; ++e) dst[e] = cur.v[it][e];
+    }
+    attn_bf16x8_t ka[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    if (tok0 + i >= n_tok) sc[i] = -INFINITY;
-    mw = fmaxf(mw, sc[i]);
-  }
-  mw = fmaxf(mw, __shfl_xor(mw, 16, 64));
-  mw = fmaxf(mw, __shfl_xor(mw, 32, 64));
-  if (quad == 0) s_max[wave * 16 + col] = mw;
-  __syncthreads();
-  const float mx = fmaxf(fmaxf(s_max[col], s_max[16 + col]), fmaxf(s_max[32 + col], s_max[48 + col]));
-  float pr[4], lw = 0.f;
+    for (int s = 0; s < 4; ++s) ka[s] = cur.k[s];
+    if (j + 1 < n_pieces)                          // the next piece's loads fly during this one's arithmetic
+      attn_piece_load<HD>(cur, kv, pool, rd.seq, layer, hk, t0 + ATTN_SLICE,
+                          min(ATTN_SLICE, rd.pos + 1 - t0 - ATTN_SLICE), one_page, tid, wave, col, quad);
+    __syncthreads();
+
+    // scores of this wave's 16 tokens
+    attn_f32x4_t sc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    pr[i] = tok0 + i < n_tok ? expf(sc[i] - mx) : 0.f;   // (token 0 of the slice is real, so mx is finite)
-    lw += pr[i];
-  }
-  lw += __shfl_xor(lw, 16, 64);
-  lw += __shfl_xor(lw, 32, 64);
-  if (quad == 0) s_sum[wave * 16 + col] = lw;
-  {
-    // probabilities as two bf16 parts (16 significant bits)
-    unsigned h[4], l[4];
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+      for (int p = 0; p < 3; ++p) {
+        const attn_bf16x8_t qb = __builtin_bit_cast(
+            attn_bf16x8_t, *(const attn_u32x4_t *)(s_q + (p * 16 + col) * AM_QPITCH + 32 * s + 8 * quad));
+        sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[s], qb, sc, 0, 0, 0);
+      }
+    const int tok0 = 16 * wave + 4 * quad;
+    float mw = -INFINITY;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      h[i] = __float_as_uint(pr[i]) & 0xffff0000u;
-      l[i] = __float_as_uint(pr[i] - __uint_as_float(h[i])) & 0xffff0000u;
+      if (tok0 + i >= n_tok) sc[i] = -INFINITY;
+      mw = fmaxf(mw, sc[i]);
     }
-    attn_u32x2_t ph = {(h[0] >> 16) | h[1], (h[2] >> 16) | h[3]};
-    attn_u32x2_t pl = {(l[0] >> 16) | l[1], (l[2] >> 16) | l[3]};
-    *(attn_u32x2_t *)(s_p + col * AM_PPITCH + tok0) = ph;
-    *(attn_u32x2_t *)(s_p + 16 * AM_PPITCH + col * AM_PPITCH + tok0) = pl;
-  }
-  __syncthreads();
+    mw = fmaxf(mw, __shfl_xor(mw, 16, 64));
+    mw = fmaxf(mw, __shfl_xor(mw, 32, 64));
+    if (quad == 0) s_max[wave * 16 + col] = mw;
+    __syncthreads();
+    const float piece_max = fmaxf(fmaxf(s_max[col], s_max[16 + col]), fmaxf(s_max[32 + col], s_max[48 + col]));
+    const float new_max = fmaxf(run_max, piece_max);   // finite: token 0 of every piece is real
+    const float alpha = expf(run_max - new_max);       // exp(-inf) = 0 on the first piece
+    run_max = new_max;
+    float pr[4], lw = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      pr[i] = tok0 + i < n_tok ? expf(sc[i] - new_max) : 0.f;
+      lw += pr[i];
+    }
+    lw += __shfl_xor(lw, 16, 64);
+    lw += __shfl_xor(lw, 32, 64);
+    run_sum = run_sum * alpha + lw;
+    if (wave == 0 && quad == 0) s_alpha[col] = alpha;
+    {
+      // probabilities as two bf16 parts (16 significant bits)
+      unsigned h[4], l[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        h[i] = __float_as_uint(pr[i]) & 0xffff0000u;
+        l[i] = __float_as_uint(pr[i] - __uint_as_float(h[i])) & 0xffff0000u;
+      }
+      attn_u32x2_t ph = {(h[0] >> 16) | h[1], (h[2] >> 16) | h[3]};
+      attn_u32x2_t pl = {(l[0] >> 16) | l[1], (l[2] >> 16) | l[3]};
+      *(attn_u32x2_t *)(s_p + col * AM_PPITCH + tok0) = ph;
+      *(attn_u32x2_t *)(s_p + 16 * AM_PPITCH + col * AM_PPITCH + tok0) = pl;
+    }
+    __syncthreads();
 
-  // weighted values: lane holds hd 32*wave + 16*t + col, heads 4*quad + i
-  attn_f32x4_t oacc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    // weighted values on top of the rescaled sums of the earlier pieces
+    if (j > 0) {
 #pragma unroll
-  for (int ks = 0; ks < 2; ++ks) {
-    const attn_bf16x8_t pa0 = __builtin_bit_cast(
-        attn_bf16x8_t, *(const attn_u32x4_t *)(s_p + col * AM_PPITCH + 32 * ks + 8 * quad));
-    const attn_bf16x8_t pa1 = __builtin_bit_cast(
-        attn_bf16x8_t, *(const attn_u32x4_t *)(s_p + 16 * AM_PPITCH + col * AM_PPITCH + 32 * ks + 8 * quad));
+      for (int i = 0; i < 4; ++i) {
+        const float a = s_alpha[4 * quad + i];
+        oacc[0][i] *= a;
+        oacc[1][i] *= a;
+      }
+    }
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const bf16_t *vcol = s_v + (32 * ks + 8 * quad) * AM_VPITCH + 32 * wave + 16 * t + col;
-      attn_u32x4_t vb;
+    for (int ks = 0; ks < 2; ++ks) {
+      const attn_bf16x8_t pa0 = __builtin_bit_cast(
+          attn_bf16x8_t, *(const attn_u32x4_t *)(s_p + col * AM_PPITCH + 32 * ks + 8 * quad));
+      const attn_bf16x8_t pa1 = __builtin_bit_cast(
+          attn_bf16x8_t, *(const attn_u32x4_t *)(s_p + 16 * AM_PPITCH + col * AM_PPITCH + 32 * ks + 8 * quad));
 #pragma unroll
-      for (int e = 0; e < 4; ++e) vb[e] = pack_bf16(vcol[(2 * e) * AM_VPITCH], vcol[(2 * e + 1) * AM_VPITCH]);
-      const attn_bf16x8_t b = __builtin_bit_cast(attn_bf16x8_t, vb);
-      oacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa0, b, oacc[t], 0, 0, 0);
-      oacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa1, b, oacc[t], 0, 0, 0);
+      for (int t = 0; t < 2; ++t) {
+        const bf16_t *vcol = s_v + (32 * ks + 8 * quad) * AM_VPITCH + 32 * wave + 16 * t + col;
+        attn_u32x4_t vb;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) vb[e] = pack_bf16(vcol[(2 * e) * AM_VPITCH], vcol[(2 * e + 1) * AM_VPITCH]);
+        const attn_bf16x8_t b = __builtin_bit_cast(attn_bf16x8_t, vb);
+        oacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa0, b, oacc[t], 0, 0, 0);
+        oacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa1, b, oacc[t], 0, 0, 0);
+      }
     }
   }
+
+  // the slice's partial: weighted values, maximum, sum over the waves
+  if (quad == 0) { s_sum[wave * 16 + col] = run_sum; s_max[col] = run_max; }
 #pragma unroll
   for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -425,13 +476,13 @@ attn_rows_mfma_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbu
         store_device_scope(part + ((size_t)(r * nq + hq0 + g) * n_splits + split) * PS + 32 * wave + 16 * t + col,
                            oacc[t][i]);
     }
+  __syncthreads();
   if (tid < group * 2) {
     const int g = tid >> 1;
-    const float v = (tid & 1) ? s_sum[g] + s_sum[16 + g] + s_sum[32 + g] + s_sum[48 + g]
-                              : fmaxf(fmaxf(s_max[g], s_max[16 + g]), fmaxf(s_max[32 + g], s_max[48 + g]));
+    const float v = (tid & 1) ? s_sum[g] + s_sum[16 + g] + s_sum[32 + g] + s_sum[48 + g] : s_max[g];
     store_device_scope(part + ((size_t)(r * nq + hq0 + g) * n_splits + split) * PS + HD + (tid & 1), v);
   }
-  attn_merge<HD, ATTN_THREADS, false>(rd, r, hq0, group, nq, n_splits, part,
+  attn_merge<HD, ATTN_THREADS, false>(rd, r, hq0, group, nq, n_splits, span, part,
                                       arrivals + r * gridDim.y + blockIdx.y, out, so, &s_last);
 }
 

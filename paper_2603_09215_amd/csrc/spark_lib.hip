@@ -72,6 +72,7 @@ struct spark_ctx {
   bool use_mfma = true;        // SPARK_NO_MFMA=1 keeps every row count on the vector kernels
   unsigned bar_round = 0;      // grid barriers passed since the barrier words were zeroed
   unsigned long long *timeline_dev = nullptr;  // debugging aid, see SPARK_PASS_TIMELINE
+  int attn_pieces = 0;   // SPARK_ATTN_PIECES: 64-token pieces per attention workgroup (0: by the launch's size)
   int attn_mfma_min_rows = 1;   // passes with at least this many rows run attention on the MFMA units (where the shape allows)
   float temperature = 0.f, top_p = 0.f;   // nucleus sampling, off while temperature <= 0
   int prefill_chunk = 128;   // prompt rows per pass, see spark_init
@@ -366,11 +367,14 @@ template <typename WT> int launch_attention(spark_ctx *c, const RowDesc *rows, i
   const SplitOut so = split_out ? split_target(c, qw) : SplitOut{nullptr, 0, 0, 0};
   if (std::is_same<WT, bf16_t>::value && c->cfg.head_dim == 128 && c->dv.group <= 16 && c->use_mfma &&
       m >= c->attn_mfma_min_rows) {
-    // many rows: the slice tasks on the MFMA units, all query heads of a KV head together
+    // the slice tasks on the MFMA units, all query heads of a KV head together; with many
+    // workgroups to run, several 64-token pieces per workgroup
     const int splits = c->attn_splits_now > 0 ? std::min(c->dv.n_splits, c->attn_splits_now) : c->dv.n_splits;
-    attn_rows_mfma_k<128><<<dim3(splits, c->cfg.n_kv_heads, m), ATTN_THREADS, 0, c->stream>>>(
+    const long tasks = (long)splits * c->cfg.n_kv_heads * m;
+    int pieces = c->attn_pieces > 0 ? c->attn_pieces : (tasks >= 8L * c->n_cu ? 4 : tasks >= 4L * c->n_cu ? 2 : 1);
+    attn_rows_mfma_k<128><<<dim3((splits + pieces - 1) / pieces, c->cfg.n_kv_heads, m), ATTN_THREADS, 0, c->stream>>>(
         rows, at<float>(c, c->lo.qbuf), kv_view(c), layer, c->cfg.n_q_heads, c->dv.group, c->dv.n_splits,
-        1.0f / sqrtf(128.0f), at<float>(c, c->lo.part), at<int>(c, c->lo.arrivals),
+        pieces, 1.0f / sqrtf(128.0f), at<float>(c, c->lo.part), at<int>(c, c->lo.arrivals),
         at<float>(c, c->lo.attn_out), so);
   } else if (c->cfg.head_dim == 128) launch_attention_hd<WT, 128>(c, rows, m, layer, so);
   else launch_attention_hd<WT, 64>(c, rows, m, layer, so);
@@ -980,6 +984,7 @@ int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_p
   const char *pass = getenv("SPARK_PASS_KERNEL");
   c->use_pass_kernel = pass && pass[0] == '1';
   if (const char *v = getenv("SPARK_ATTN_MFMA_MIN_ROWS")) c->attn_mfma_min_rows = std::max(1, atoi(v));
+  if (const char *v = getenv("SPARK_ATTN_PIECES")) c->attn_pieces = std::max(0, std::min(8, atoi(v)));
   const char *no_mfma = getenv("SPARK_NO_MFMA");
   // the MFMA kernels load 16-byte vectors of 8 weights; other widths stay on the vector kernel
   c->use_mfma = !(no_mfma && no_mfma[0] == '1') && cfg->d_model % 8 == 0 &&
