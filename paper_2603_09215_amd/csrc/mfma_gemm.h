@@ -51,8 +51,8 @@ constexpr int MG_PARTS = 3;
 constexpr int MG_W_DEPTH = 2;
 // dynamic LDS of mfma_rows_k: per wave 64 padded weight rows of one chunk; two buffers of three
 // parts of 32*MTILES padded activation rows
-constexpr size_t mg_lds_bytes(int mtiles) {
-  return sizeof(bf16_t) * (MG_WAVES * 64 * MG_ROWPAD + 2 * MG_PARTS * 32 * mtiles * MG_ROWPAD);
+constexpr size_t mg_lds_bytes(int mtiles, int waves = MG_WAVES) {
+  return sizeof(bf16_t) * (waves * 64 * MG_ROWPAD + 2 * MG_PARTS * 32 * mtiles * MG_ROWPAD);
 }
 
 // ------------------------------------------------------------------ activation preparation
@@ -118,8 +118,9 @@ prep_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ src, int
 // products skipped or discarded), which lets the compiler wait for exactly the loads a step needs;
 // loads return in issue order, so inside an iteration the activation loads are issued before the
 // weight loads and the order of the steps is pinned.
-template <int MTILES, typename Epi, bool SPLIT>
-__global__ void __launch_bounds__(MG_THREADS)
+// WAVES: 8, or 4 for matrices of few rows, whose launches then have twice as many workgroups
+template <int MTILES, typename Epi, bool SPLIT, int WAVES = MG_WAVES>
+__global__ void __launch_bounds__(64 * WAVES)
 mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t *__restrict__ xs,
             size_t part_stride, int n_in, int n_tasks, int chunks_per_split,
             float *__restrict__ part, int m_pad) {
@@ -127,15 +128,15 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
   constexpr int MROWS = 32 * MTILES;
   constexpr int WD = MG_W_DEPTH;
   constexpr int XPOS = MROWS * (MG_KC / 8);                  // 16-byte vectors of one part of a chunk
-  constexpr int XV = (XPOS + MG_THREADS - 1) / MG_THREADS;   // of them per thread
+  constexpr int XV = (XPOS + (64 * WAVES) - 1) / (64 * WAVES);   // of them per thread
   constexpr int PART_ELEMS = MROWS * MG_ROWPAD;
   constexpr int WI = 8;                                      // load instructions per chunk: 8 rows x 128 bytes each
   extern __shared__ uint4 mg_smem[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   bf16_t *s_w = (bf16_t *)mg_smem + wave * 64 * MG_ROWPAD;             // this wave's [64][MG_ROWPAD]
-  bf16_t *s_x = (bf16_t *)mg_smem + MG_WAVES * 64 * MG_ROWPAD;         // [2][3][MROWS * MG_ROWPAD]
+  bf16_t *s_x = (bf16_t *)mg_smem + WAVES * 64 * MG_ROWPAD;         // [2][3][MROWS * MG_ROWPAD]
   const int row0 = blockIdx.z * MROWS;
-  const int task0 = blockIdx.x * MG_TASKS_PER_BLOCK + wave * MG_TASKS_PER_WAVE;
+  const int task0 = blockIdx.x * (WAVES * MG_TASKS_PER_WAVE) + wave * MG_TASKS_PER_WAVE;
   const int n_chunks = (n_in + MG_KC - 1) / MG_KC;   // the last one may be short: activations are zero-padded
   const int x_stride = n_chunks * MG_KC;
   const int c_begin = blockIdx.y * chunks_per_split;
@@ -170,7 +171,7 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
   int x_src[XV], x_dst[XV];
 #pragma unroll
   for (int i = 0; i < XV; ++i) {
-    const int pos = min((int)threadIdx.x + i * MG_THREADS, XPOS - 1);
+    const int pos = min((int)threadIdx.x + i * (64 * WAVES), XPOS - 1);
     const int m = pos / (MG_KC / 8), kv = (pos - m * (MG_KC / 8)) * 8;
     x_src[i] = min(row0 + m, m_rows - 1) * x_stride + kv;    // rows past the end repeat the last one
     x_dst[i] = m * MG_ROWPAD + kv;
@@ -189,7 +190,7 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
   {
 #pragma unroll
     for (int i = 0; i < XV; ++i) {
-      if ((int)threadIdx.x + i * MG_THREADS < XPOS) {
+      if ((int)threadIdx.x + i * (64 * WAVES) < XPOS) {
 #pragma unroll
         for (int p = 0; p < MG_PARTS; ++p) *(u32x4_t *)(s_x + p * PART_ELEMS + x_dst[i]) = xr[i][p];
       }
@@ -228,7 +229,7 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
       {
 #pragma unroll
         for (int i = 0; i < XV; ++i) {
-          if ((int)threadIdx.x + i * MG_THREADS < XPOS) {
+          if ((int)threadIdx.x + i * (64 * WAVES) < XPOS) {
 #pragma unroll
             for (int p = 0; p < MG_PARTS; ++p)
               *(u32x4_t *)(s_x + ((buf ^ 1) * MG_PARTS + p) * PART_ELEMS + x_dst[i]) = xr[i][p];

@@ -72,6 +72,7 @@ struct spark_ctx {
   bool use_mfma = true;        // SPARK_NO_MFMA=1 keeps every row count on the vector kernels
   unsigned bar_round = 0;      // grid barriers passed since the barrier words were zeroed
   unsigned long long *timeline_dev = nullptr;  // debugging aid, see SPARK_PASS_TIMELINE
+  int mfma_small_tiles = 32;   // launches with fewer 8-wave tiles use 4-wave workgroups (SPARK_MFMA_SMALL_TILES)
   int attn_pieces = 0;   // SPARK_ATTN_PIECES: 64-token pieces per attention workgroup (0: by the launch's size)
   int attn_mfma_min_rows = 1;   // passes with at least this many rows run attention on the MFMA units (where the shape allows)
   float temperature = 0.f, top_p = 0.f;   // nucleus sampling, off while temperature <= 0
@@ -484,34 +485,34 @@ int launch_prep(spark_ctx *c, const RowDesc *rows, int m, const float *src, int 
 template <typename Epi> int finish_tasks_per_thread(const Epi &) { return 1; }
 template <typename WT> int finish_tasks_per_thread(const EpiVocab<WT> &) { return 64; }
 
-template <int MTILES, typename Epi, bool SPLIT>
+template <int MTILES, typename Epi, bool SPLIT, int WAVES>
 int mfma_occupancy(spark_ctx *c) {
-  auto kern = mfma_rows_k<MTILES, Epi, SPLIT>;
-  const auto key = std::make_pair((const void *)kern, mg_lds_bytes(MTILES));
+  auto kern = mfma_rows_k<MTILES, Epi, SPLIT, WAVES>;
+  const size_t lds = mg_lds_bytes(MTILES, WAVES);
+  const auto key = std::make_pair((const void *)kern, lds);
   auto found = c->occ_cache.find(key);
   if (found == c->occ_cache.end()) {
-    if (mg_lds_bytes(MTILES) > 65536)
-      HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)mg_lds_bytes(MTILES)));
+    if (lds > 65536)
+      HIP_TRY(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     int o = 0;
-    HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, kern, MG_THREADS, mg_lds_bytes(MTILES)));
+    HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, kern, 64 * WAVES, lds));
     if (o < 1) return fail(c, SPARK_EHIP, "the MFMA kernel for %d rows does not fit on a CU", 32 * MTILES);
     found = c->occ_cache.emplace(key, o).first;
   }
   return found->second;
 }
 
-template <int MTILES, typename Epi>
-int launch_mfma_tiles(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, int n_in, int n_tasks,
-                      bool may_split, bool second_input = false) {
-  if (n_in % 8) return fail(c, SPARK_EINVAL, "MFMA path needs an input width that is a multiple of 8, not %d", n_in);
+template <int MTILES, typename Epi, int WAVES>
+int launch_mfma_shape(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, int n_in, int n_tasks,
+                      bool may_split, bool second_input) {
+  constexpr int TASKS_PER_BLOCK = WAVES * MG_TASKS_PER_WAVE;
   const int mrows = 32 * MTILES;
   const int z = (m + mrows - 1) / mrows;
-  const int bx = (n_tasks + MG_TASKS_PER_BLOCK - 1) / MG_TASKS_PER_BLOCK;
+  const int bx = (n_tasks + TASKS_PER_BLOCK - 1) / TASKS_PER_BLOCK;
   const int n_chunks = (n_in + MG_KC - 1) / MG_KC;
   const int m_pad = (int)align_up(m, 32);
   // resident workgroups on the chip: the k range is split until one round of them has work
-  int occ = mfma_occupancy<MTILES, Epi, true>(c);
+  int occ = mfma_occupancy<MTILES, Epi, true, WAVES>(c);
   if (occ < 0) return occ;
   // k splits: the count that keeps most of the chip busy over whole rounds of resident
   // workgroups, with at least eight chunks each (the pipeline needs a few to fill)
@@ -535,20 +536,35 @@ int launch_mfma_tiles(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, 
   const size_t xst = xsplit_stride(c);
   float *part = at<float>(c, c->lo.mfma_part);
   dim3 grid(bx, split, z);
+  const size_t lds = mg_lds_bytes(MTILES, WAVES);
   if (split > 1) {
-    mfma_rows_k<MTILES, Epi, true><<<grid, MG_THREADS, mg_lds_bytes(MTILES), c->stream>>>(
+    mfma_rows_k<MTILES, Epi, true, WAVES><<<grid, 64 * WAVES, lds, c->stream>>>(
         epi, rows, m, xs, xst, n_in, n_tasks, cps, part, m_pad);
     const int tpt = finish_tasks_per_thread(epi);
     const int total = ((n_tasks + tpt - 1) / tpt) * m_pad;
     mfma_finish_k<Epi><<<(total + 255) / 256, 256, 0, c->stream>>>(epi, rows, m, n_tasks, split, part, m_pad, tpt);
   } else {
-    occ = mfma_occupancy<MTILES, Epi, false>(c);
+    occ = mfma_occupancy<MTILES, Epi, false, WAVES>(c);
     if (occ < 0) return occ;
-    mfma_rows_k<MTILES, Epi, false><<<grid, MG_THREADS, mg_lds_bytes(MTILES), c->stream>>>(
+    mfma_rows_k<MTILES, Epi, false, WAVES><<<grid, 64 * WAVES, lds, c->stream>>>(
         epi, rows, m, xs, xst, n_in, n_tasks, cps, part, m_pad);
   }
   HIP_TRY(c, hipGetLastError());
   return SPARK_OK;
+}
+
+template <int MTILES, typename Epi>
+int launch_mfma_tiles(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, int n_in, int n_tasks,
+                      bool may_split, bool second_input = false) {
+  if (n_in % 8) return fail(c, SPARK_EINVAL, "MFMA path needs an input width that is a multiple of 8, not %d", n_in);
+  // matrices of few rows and a short k (q/k/v, o, the lens translator): four waves per workgroup,
+  // so that the launch has enough workgroups without cutting k into ranges too short to stream
+  // (measured at 32 rows: q/k/v 23.5 -> 20.8 us, o 20.2 -> 16.0 us; down, with its long k, and
+  // gate/up, with its many tiles, are better off with eight)
+  const int tiles8 = ((n_tasks + MG_TASKS_PER_BLOCK - 1) / MG_TASKS_PER_BLOCK) * ((m + 32 * MTILES - 1) / (32 * MTILES));
+  if (tiles8 < c->mfma_small_tiles && n_in <= 8192)
+    return launch_mfma_shape<MTILES, Epi, 4>(c, epi, rows, m, n_in, n_tasks, may_split, second_input);
+  return launch_mfma_shape<MTILES, Epi, 8>(c, epi, rows, m, n_in, n_tasks, may_split, second_input);
 }
 
 // y = W x for m rows whose hi/lo split sits in the xhi/xlo buffers
@@ -985,6 +1001,7 @@ int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_p
   c->use_pass_kernel = pass && pass[0] == '1';
   if (const char *v = getenv("SPARK_ATTN_MFMA_MIN_ROWS")) c->attn_mfma_min_rows = std::max(1, atoi(v));
   if (const char *v = getenv("SPARK_ATTN_PIECES")) c->attn_pieces = std::max(0, std::min(8, atoi(v)));
+  if (const char *v = getenv("SPARK_MFMA_SMALL_TILES")) c->mfma_small_tiles = atoi(v);
   const char *no_mfma = getenv("SPARK_NO_MFMA");
   // the MFMA kernels load 16-byte vectors of 8 weights; other widths stay on the vector kernel
   c->use_mfma = !(no_mfma && no_mfma[0] == '1') && cfg->d_model % 8 == 0 &&
