@@ -308,8 +308,8 @@ __device__ __forceinline__ void attn_piece_load(AttnPiece &pc, const KVView &kv,
 template <int HD>
 __global__ void __launch_bounds__(ATTN_THREADS)
 attn_rows_mfma_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbuf, KVView kv, int layer,
-                 int nq, int group, int n_splits, int pieces, float scale, float *__restrict__ part,
-                 int *__restrict__ arrivals, float *__restrict__ out, SplitOut so) {
+                 int nq, int kv_group, int heads_per_wg, int n_splits, int pieces, float scale,
+                 float *__restrict__ part, int *__restrict__ arrivals, float *__restrict__ out, SplitOut so) {
   static_assert(HD == 128, "four 32-wide steps per key row, four waves of 32 value columns");
   constexpr int PS = HD + 4;
   __shared__ __align__(16) bf16_t s_v[ATTN_SLICE * AM_VPITCH];
@@ -317,13 +317,18 @@ attn_rows_mfma_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbu
   __shared__ __align__(16) bf16_t s_q[3 * 16 * AM_QPITCH];
   __shared__ float s_max[4 * 16], s_sum[4 * 16], s_alpha[16];
   __shared__ int s_last;
-  const int split = blockIdx.x, hk = blockIdx.y, r = blockIdx.z;
+  // blockIdx.y = (KV head, part of its query heads): with few rows and few KV heads the query
+  // heads of a KV head are dealt to several workgroups, which shortens each one's merge
+  const int wg_per_kv = (kv_group + heads_per_wg - 1) / heads_per_wg;
+  const int split = blockIdx.x, hk = blockIdx.y / wg_per_kv, r = blockIdx.z;
+  const int h_first = (blockIdx.y - hk * wg_per_kv) * heads_per_wg;
+  const int group = min(heads_per_wg, kv_group - h_first);   // query heads of this workgroup
   const RowDesc rd = rows[r];
   const int span = ATTN_SLICE * pieces;
   if (split * span > rd.pos) return;              // slice beyond the row's context
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 15, quad = lane >> 4;    // operand column / row, and which eight of a 32-wide step
-  const int hq0 = hk * group;
+  const int hq0 = hk * kv_group + h_first;
   const bf16_t *pool = (const bf16_t *)kv.pool;
   const bool one_page = (kv.page_tokens & (ATTN_SLICE - 1)) == 0;
   const int n_pieces = min(pieces, (rd.pos - split * span) / ATTN_SLICE + 1);   // pieces the context reaches

@@ -373,9 +373,13 @@ template <typename WT> int launch_attention(spark_ctx *c, const RowDesc *rows, i
     const int splits = c->attn_splits_now > 0 ? std::min(c->dv.n_splits, c->attn_splits_now) : c->dv.n_splits;
     const long tasks = (long)splits * c->cfg.n_kv_heads * m;
     int pieces = c->attn_pieces > 0 ? c->attn_pieces : (tasks >= 8L * c->n_cu ? 4 : tasks >= 4L * c->n_cu ? 2 : 1);
-    attn_rows_mfma_k<128><<<dim3((splits + pieces - 1) / pieces, c->cfg.n_kv_heads, m), ATTN_THREADS, 0, c->stream>>>(
-        rows, at<float>(c, c->lo.qbuf), kv_view(c), layer, c->cfg.n_q_heads, c->dv.group, c->dv.n_splits,
-        pieces, 1.0f / sqrtf(128.0f), at<float>(c, c->lo.part), at<int>(c, c->lo.arrivals),
+    // few workgroups (a handful of rows, two KV heads): eight query heads per workgroup
+    const int heads_per_wg = (tasks < c->n_cu / 2 && c->dv.group > 8) ? 8 : c->dv.group;
+    const int wg_per_kv = (c->dv.group + heads_per_wg - 1) / heads_per_wg;
+    attn_rows_mfma_k<128><<<dim3((splits + pieces - 1) / pieces, c->cfg.n_kv_heads * wg_per_kv, m), ATTN_THREADS, 0,
+                            c->stream>>>(
+        rows, at<float>(c, c->lo.qbuf), kv_view(c), layer, c->cfg.n_q_heads, c->dv.group, heads_per_wg,
+        c->dv.n_splits, pieces, 1.0f / sqrtf(128.0f), at<float>(c, c->lo.part), at<int>(c, c->lo.arrivals),
         at<float>(c, c->lo.attn_out), so);
   } else if (c->cfg.head_dim == 128) launch_attention_hd<WT, 128>(c, rows, m, layer, so);
   else launch_attention_hd<WT, 64>(c, rows, m, layer, so);
