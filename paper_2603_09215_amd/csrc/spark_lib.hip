@@ -28,6 +28,9 @@ namespace {
 constexpr int PREFILL_CHUNK = 256;   // most prompt rows pushed through the layers together (buffers are sized for it)
 constexpr size_t MFMA_PARTIAL_BYTES = 48u << 20;  // k-split partial sums of one projection
 constexpr int MAX_STEPS_PER_CALL = 256;
+// rows from which the MFMA projections run (measured: four rows 4 % faster on them than in one
+// pass of the vector kernel, three rows 5 % slower)
+constexpr int MFMA_MIN_ROWS = 4;
 constexpr int MAX_SEQ_LEN = 16384;
 
 struct Layout {  // byte offsets into the scratch buffer
@@ -73,6 +76,7 @@ struct spark_ctx {
   unsigned bar_round = 0;      // grid barriers passed since the barrier words were zeroed
   unsigned long long *timeline_dev = nullptr;  // debugging aid, see SPARK_PASS_TIMELINE
   int mfma_small_tiles = 32;   // launches with fewer 8-wave tiles use 4-wave workgroups (SPARK_MFMA_SMALL_TILES)
+  int mfma_min_rows = MFMA_MIN_ROWS;   // SPARK_MFMA_MIN_ROWS
   int attn_pieces = 0;   // SPARK_ATTN_PIECES: 64-token pieces per attention workgroup (0: by the launch's size)
   int attn_mfma_min_rows = 1;   // passes with at least this many rows run attention on the MFMA units (where the shape allows)
   float temperature = 0.f, top_p = 0.f;   // nucleus sampling, off while temperature <= 0
@@ -468,7 +472,6 @@ template <typename WT> int launch_pass(spark_ctx *c, int l0, int l1, const RowDe
 
 // ------------------------------------------------------------------ MFMA path (16..128+ rows, bf16)
 
-constexpr int MFMA_MIN_ROWS = 5;   // up to four rows share one pass of the vector kernel; more would take several
 
 // the three bf16 parts of the split activations are stored one after the other
 size_t xsplit_stride(spark_ctx *c) {
@@ -631,7 +634,7 @@ int run_layers(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m, bool on
   if (one_sequence && m <= 4 && c->use_pass_kernel && pass_supported<WT>(g.head_dim, c->dv.group))
     return launch_pass<WT>(c, l0, l1, rows, m);
   // many rows: the projections are dense contractions for the MFMA units
-  if (std::is_same<WT, bf16_t>::value && m >= MFMA_MIN_ROWS && c->use_mfma)
+  if (std::is_same<WT, bf16_t>::value && m >= c->mfma_min_rows && c->use_mfma)
     return run_layers_mfma(c, l0, l1, rows, m);
   const int d = g.d_model, hd = g.head_dim, nq = g.n_q_heads, nkv = g.n_kv_heads, F = g.d_ffn;
   const size_t qw = (size_t)nq * hd, kvw = (size_t)nkv * hd;
@@ -672,7 +675,7 @@ template <typename WT> int run_lens_head(spark_ctx *c, const RowDesc *rows, int 
   const int d = g.d_model, V = c->dv.V;
   float *hidden = at<float>(c, c->lo.hidden), *u = at<float>(c, c->lo.lens_u);
   int rc;
-  if (std::is_same<WT, bf16_t>::value && m >= MFMA_MIN_ROWS && c->use_mfma) {
+  if (std::is_same<WT, bf16_t>::value && m >= c->mfma_min_rows && c->use_mfma) {
     if ((rc = launch_prep(c, rows, m, hidden, d, 1, nullptr, d))) return rc;
     EpiLensAffine<bf16_t> ea{(const bf16_t *)c->w.lens_a, c->w.lens_b, hidden, u, d};
     if ((rc = launch_mfma(c, ea, rows, m, d, d / 2, true, SPARK_KC_LENS))) return rc;
@@ -697,7 +700,7 @@ template <typename WT> int run_lens_head(spark_ctx *c, const RowDesc *rows, int 
 template <typename WT> int run_final_head(spark_ctx *c, const RowDesc *rows, int m) {
   const spark_config &g = c->cfg;
   const int d = g.d_model, V = c->dv.V;
-  if (std::is_same<WT, bf16_t>::value && m >= MFMA_MIN_ROWS && c->use_mfma) {
+  if (std::is_same<WT, bf16_t>::value && m >= c->mfma_min_rows && c->use_mfma) {
     int rc;
     if ((rc = launch_prep(c, rows, m, at<float>(c, c->lo.hidden), d, 1, c->w.final_norm, d))) return rc;
     EpiVocab<bf16_t> ev{(const bf16_t *)c->w.lm_head, d, V, at<float>(c, c->lo.logits),
@@ -1006,6 +1009,7 @@ int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_p
   if (const char *v = getenv("SPARK_ATTN_MFMA_MIN_ROWS")) c->attn_mfma_min_rows = std::max(1, atoi(v));
   if (const char *v = getenv("SPARK_ATTN_PIECES")) c->attn_pieces = std::max(0, std::min(8, atoi(v)));
   if (const char *v = getenv("SPARK_MFMA_SMALL_TILES")) c->mfma_small_tiles = atoi(v);
+  if (const char *v = getenv("SPARK_MFMA_MIN_ROWS")) c->mfma_min_rows = std::max(1, atoi(v));
   const char *no_mfma = getenv("SPARK_NO_MFMA");
   // the MFMA kernels load 16-byte vectors of 8 weights; other widths stay on the vector kernel
   c->use_mfma = !(no_mfma && no_mfma[0] == '1') && cfg->d_model % 8 == 0 &&

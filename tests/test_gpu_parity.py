@@ -243,7 +243,7 @@ def test_persistent_layer_pass_kernel(sb, tiny_weights, monkeypatch):
 
 def test_text_schedule_with_long_flushes_on_a_bf16_model(sb):
     """text and speech both scheduled (Sec. V-C): runs of early exits cross the modality boundary,
-    so one sequence completes up to six rows in a full-depth step; on a bf16 model five or more
+    so one sequence completes up to six rows in a full-depth step; on a bf16 model four or more
     rows go through the MFMA kernels, fewer through the vector kernel"""
     shape = wl.TINY.shape.replace(name="bf16-textsched", dtype=wl.DTYPE_BF16, n_layers=4, d_model=512,
                                   n_q_heads=8, n_kv_heads=4, head_dim=64, d_ffn=1536 + 72,
