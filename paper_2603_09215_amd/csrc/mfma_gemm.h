@@ -328,4 +328,37 @@ mfma_finish_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, int n_tasks
   epi.end(m, rd, st);
 }
 
+// The same for epilogues without a running state, with the stores in mind: a workgroup of 1024
+// threads takes 32 tasks x 32 activation rows, one pair per thread.  It sums the k ranges with the
+// rows fastest across threads (the order in which the partials lie), turns the tile in LDS, and
+// runs the epilogue with the tasks fastest, so that what the epilogue writes (consecutive
+// elements of a row of the hidden state, of q, of the cache, of the split activations) leaves a
+// wave as whole segments instead of single words 7 KB apart.  grid (tasks / 32, m_pad / 32).
+template <typename Epi>
+__global__ void __launch_bounds__(1024)
+mfma_finish_tile_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, int n_tasks, int n_split,
+                   const float *__restrict__ part, int m_pad) {
+  __shared__ float s_y[2][32][33];
+  const int task0 = blockIdx.x * 32, row0 = blockIdx.y * 32;
+  {
+    const int ml = threadIdx.x & 31, tl = threadIdx.x >> 5, task = min(task0 + tl, n_tasks - 1);
+    float y0 = 0.f, y1 = 0.f;
+    for (int s = 0; s < n_split; ++s) {
+      const float *p = part + (((size_t)s * n_tasks + task) * 2) * m_pad + row0 + ml;
+      y0 += p[0];
+      y1 += p[m_pad];
+    }
+    s_y[0][tl][ml] = y0;
+    s_y[1][tl][ml] = y1;
+  }
+  __syncthreads();
+  const int tl = threadIdx.x & 31, ml = threadIdx.x >> 5, task = task0 + tl, m = row0 + ml;
+  if (task >= n_tasks || m >= m_rows) return;
+  const RowDesc rd = rows[m];
+  typename Epi::State st;
+  epi.init(st);
+  epi.finish(task, m, rd, s_y[0][tl][ml], s_y[1][tl][ml], st);
+  epi.end(m, rd, st);
+}
+
 }  // namespace spark

@@ -549,7 +549,11 @@ int launch_mfma_shape(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, 
         epi, rows, m, xs, xst, n_in, n_tasks, cps, part, m_pad);
     const int tpt = finish_tasks_per_thread(epi);
     const int total = ((n_tasks + tpt - 1) / tpt) * m_pad;
-    mfma_finish_k<Epi><<<(total + 255) / 256, 256, 0, c->stream>>>(epi, rows, m, n_tasks, split, part, m_pad, tpt);
+    if (tpt == 1)   // epilogues without a running state: stores coalesced over tasks
+      mfma_finish_tile_k<Epi><<<dim3((n_tasks + 31) / 32, m_pad / 32), 1024, 0, c->stream>>>(epi, rows, m, n_tasks, split,
+                                                                                              part, m_pad);
+    else
+      mfma_finish_k<Epi><<<(total + 255) / 256, 256, 0, c->stream>>>(epi, rows, m, n_tasks, split, part, m_pad, tpt);
   } else {
     occ = mfma_occupancy<MTILES, Epi, false, WAVES>(c);
     if (occ < 0) return occ;
