@@ -80,3 +80,82 @@ def test_full_shape_short_run(name, n_steps, offset, n_prompt):
     sp.close()
     del dev_w, host_w
     torch.cuda.empty_cache()
+
+
+def test_bench_configuration_properties():
+    """The configuration bench.py times (Step-Audio-2-mini shape, 512-token prompt, 1024 decoded
+    tokens in multi-step calls, 64-token pages, free running): too long for the oracle's model, so
+    what holds at any size is checked: the depth of every step against the oracle's scheduler, the
+    counters, the two validity frontiers of the cache, and that a second, identical run reproduces
+    the tokens bit for bit (nothing in the path depends on timing or on atomics' order)."""
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from oracle import binding as ob
+    from paper_2603_09215_amd import binding as sb
+    w = wl.WORKLOADS["step_audio_2_mini"]
+    say("case bench configuration")
+    dev_w = wl.make_weights_on_device(w.shape, seed=0)
+    n = w.decode_len
+    want_depth, want_text = ob.schedule_run(w.shape, w.schedule, n, 0)
+    prompt = wl.make_prompt(w.shape, w.prompt_len, seed=1, ids=w.prompt_ids)
+    runs = []
+    for rep in range(2):
+        sp = sb.Spark(w.shape, w.schedule, dev_w, max_batch=1, max_seq_len=w.prompt_len + n + 64, kv_page_tokens=64)
+        sid = sp.seq_open(0)
+        sp.prefill(sid, prompt)
+        tok, dep = sp.decode(n, [sid])
+        assert np.array_equal(dep[:, 0], want_depth)
+        assert tok.min() >= 0 and tok.max() < w.shape.vocab
+        st = sp.get_stats(sid)
+        assert st["text"] == int(want_text.sum())
+        assert st["speech_full"] == int(((want_text == 0) & (want_depth == w.shape.n_layers)).sum())
+        assert st["speech_ee"] == int((want_depth != w.shape.n_layers).sum())
+        state = sp.seq_state(sid)
+        trailing_ee = 0
+        while want_depth[n - 1 - trailing_ee] != w.shape.n_layers:
+            trailing_ee += 1
+        assert state["len"] == w.prompt_len - 1 + n and state["pending"] == trailing_ee
+        assert state["upper_valid"] == state["len"] - trailing_ee
+        logits, head = sp.get_logits(sid)
+        assert np.all(np.isfinite(logits)) and int(np.argmax(logits)) == tok[-1, 0]
+        runs.append(tok.copy())
+        sp.close()
+    assert np.array_equal(runs[0], runs[1])
+    del dev_w
+    torch.cuda.empty_cache()
+
+
+def test_batched_bench_configuration_properties():
+    """bench.py --batch at the Step-Audio-2-mini shape (prompts of 256..2048 tokens, mixed cycle
+    offsets, MFMA projections and attention with several pieces per workgroup): every sequence's
+    depths against the oracle's scheduler, and a second run reproduces the tokens bit for bit"""
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from oracle import binding as ob
+    from paper_2603_09215_amd import binding as sb
+    w = wl.WORKLOADS["step_audio_2_mini"]
+    say("case batched bench configuration")
+    dev_w = wl.make_weights_on_device(w.shape, seed=0)
+    B, n = 12, 48
+    cyc = w.schedule.n_text + w.schedule.n_speech
+    plens = [int(x) for x in wl.make_prompt_lengths(B, 256, 2048, seed=3)]
+    prompts = [wl.make_prompt(w.shape, p, seed=1 + i, ids=w.prompt_ids) for i, p in enumerate(plens)]
+    runs = []
+    for rep in range(2):
+        sp = sb.Spark(w.shape, w.schedule, dev_w, max_batch=B, max_seq_len=2048 + n + 64, kv_page_tokens=64)
+        sids = [sp.seq_open(i % cyc) for i in range(B)]
+        for s_, p_ in zip(sids, prompts):
+            sp.prefill(s_, p_)
+        tok, dep = sp.decode(n, sids)
+        for i in range(B):
+            want_depth, _ = ob.schedule_run(w.shape, w.schedule, n, i % cyc)
+            assert np.array_equal(dep[:, i], want_depth), i
+            assert sp.seq_state(sids[i])["len"] == plens[i] - 1 + n
+        assert tok.min() >= 0 and tok.max() < w.shape.vocab
+        runs.append(tok.copy())
+        sp.close()
+    assert np.array_equal(runs[0], runs[1])
+    del dev_w
+    torch.cuda.empty_cache()
