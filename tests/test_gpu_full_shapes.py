@@ -82,6 +82,38 @@ def test_full_shape_short_run(name, n_steps, offset, n_prompt):
     torch.cuda.empty_cache()
 
 
+def first_layer_cache_entries_match(sp, sid, w, dev_w, prompt, generated):
+    """Sampled outputs the oracle can compute one by one at any context length: a position's key
+    and value in the first layer depend on its token alone (embedding, RMSNorm, k/v projection,
+    RoPE at the position, rounding to the cache's bf16), so entries written by the prompt passes
+    (MFMA kernels), by early-exit and full-depth steps and at the far end of the context are
+    checked against the oracle's primitives."""
+    from oracle import binding as ob
+    import torch
+    shape = w.shape
+    n_prompt = len(prompt)
+    bits = lambda t: t.cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+    gamma = dev_w["attn_norm"][0].cpu().numpy()
+    wk, wv = bits(dev_w["wk"][0]), bits(dev_w["wv"][0])
+    last = n_prompt - 1 + len(generated) - 1          # the last position whose token has been processed
+    for pos in (0, 191, 192, n_prompt - 2, n_prompt - 1, n_prompt, n_prompt + 2, n_prompt + 3, 1000, last):
+        token = int(prompt[pos]) if pos < n_prompt else int(generated[pos - n_prompt])
+        x = wl.bf16_bits_to_f32(bits(dev_w["embed"][token])).astype(np.float64)
+        xn = ob.prim_rmsnorm(x, gamma, shape.rms_eps, kind="f64")
+        k = ob.prim_matvec(wk, xn, kind="f64").reshape(shape.n_kv_heads, shape.head_dim)
+        v = ob.prim_matvec(wv, xn, kind="f64")
+        k = np.concatenate([ob.prim_rope(kh, pos, shape.rope_base, kind="f64") for kh in k])
+        gk, gv = sp.get_kv(sid, 0, pos)
+        for got, want, name in ((gk, k, "K"), (gv, v, "V")):
+            # the cache holds bf16: one unit in the last place; the rotation angle is formed in
+            # fp32 on the device (position x frequency: 2^-24 relative, i.e. up to 1e-4 rad at
+            # these positions), which moves an element by that fraction of its partner
+            tol = 2.0 ** -7 * np.abs(want) + 2e-4 * np.max(np.abs(want))
+            bad = int(np.argmax(np.abs(got - want) - tol))
+            assert np.all(np.abs(got - want) <= tol), (name, pos, bad, float(got[bad]), float(want[bad]))
+    say(f"  first-layer K/V of 10 positions up to {last} match the oracle's primitives")
+
+
 def test_bench_configuration_properties():
     """The configuration bench.py times (Step-Audio-2-mini shape, 512-token prompt, 1024 decoded
     tokens in multi-step calls, 64-token pages, free running): too long for the oracle's model, so
@@ -119,6 +151,8 @@ def test_bench_configuration_properties():
         assert state["upper_valid"] == state["len"] - trailing_ee
         logits, head = sp.get_logits(sid)
         assert np.all(np.isfinite(logits)) and int(np.argmax(logits)) == tok[-1, 0]
+        if rep == 0:
+            first_layer_cache_entries_match(sp, sid, w, dev_w, prompt, tok[:, 0])
         runs.append(tok.copy())
         sp.close()
     assert np.array_equal(runs[0], runs[1])
