@@ -104,7 +104,7 @@ prep_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ src, int
 
 // ------------------------------------------------------------------ the contraction
 
-// grid.x: blocks of 256 tasks; grid.y: k splits; grid.z: tiles of 32*MTILES activation rows.
+// A workgroup takes one tile of 256 (or 128) tasks, one k range and one tile of 32*MTILES activation rows.
 // SPLIT: write partial sums part[split][task][2][m_pad] instead of running the epilogue.
 //
 // The loop over 64-wide chunks of k is software-pipelined.  Weights: a wave has MG_W_DEPTH chunks
@@ -123,8 +123,32 @@ template <int MTILES, typename Epi, bool SPLIT, int WAVES = MG_WAVES>
 __global__ void __launch_bounds__(64 * WAVES)
 mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t *__restrict__ xs,
             size_t part_stride, int n_in, int n_tasks, int chunks_per_split,
-            float *__restrict__ part, int m_pad) {
+            float *__restrict__ part, int m_pad, int n_task_tiles, int n_splits, int n_row_tiles,
+            int xcd_groups) {
   static_assert(MTILES <= MG_MAX_MTILES, "accumulators and LDS are sized for 64 rows");
+  // Workgroup -> (task tile, k range, row tile).  Consecutive workgroup ids go to consecutive
+  // XCDs, each with its own L2: the row tiles of one (task tile, k range) read the same weights,
+  // so they get ids 8 apart (same XCD, launched together) and the weights cross HBM once for them.
+  // Ids are dealt in groups of 8 * n_row_tiles: 8 tiles, one per XCD, times their row tiles.
+  // (xcd_groups: chosen by the launch; measured to pay for few, long k ranges: gate/up of a prompt
+  // pass 191 -> 169 us, while down with its many short ranges lost, 101 -> 116 us.)
+  int bx, by, bz;
+  if (!xcd_groups) {   // task tiles fastest, then k ranges, then row tiles
+    const int tiles = n_task_tiles * n_splits;
+    bz = blockIdx.x / tiles;
+    const int tile = blockIdx.x - bz * tiles;
+    if (bz >= n_row_tiles) return;
+    by = tile / n_task_tiles;
+    bx = tile - by * n_task_tiles;
+  } else {
+    const int per_group = 8 * n_row_tiles;
+    const int group = blockIdx.x / per_group, r = blockIdx.x - group * per_group;
+    const int tile = group * 8 + (r & 7);
+    if (tile >= n_task_tiles * n_splits) return;
+    bz = r >> 3;
+    by = tile / n_task_tiles;
+    bx = tile - by * n_task_tiles;
+  }
   constexpr int MROWS = 32 * MTILES;
   constexpr int WD = MG_W_DEPTH;
   constexpr int XPOS = MROWS * (MG_KC / 8);                  // 16-byte vectors of one part of a chunk
@@ -135,11 +159,11 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   bf16_t *s_w = (bf16_t *)mg_smem + wave * 64 * MG_ROWPAD;             // this wave's [64][MG_ROWPAD]
   bf16_t *s_x = (bf16_t *)mg_smem + WAVES * 64 * MG_ROWPAD;         // [2][3][MROWS * MG_ROWPAD]
-  const int row0 = blockIdx.z * MROWS;
-  const int task0 = blockIdx.x * (WAVES * MG_TASKS_PER_WAVE) + wave * MG_TASKS_PER_WAVE;
+  const int row0 = bz * MROWS;
+  const int task0 = bx * (WAVES * MG_TASKS_PER_WAVE) + wave * MG_TASKS_PER_WAVE;
   const int n_chunks = (n_in + MG_KC - 1) / MG_KC;   // the last one may be short: activations are zero-padded
   const int x_stride = n_chunks * MG_KC;
-  const int c_begin = blockIdx.y * chunks_per_split;
+  const int c_begin = by * chunks_per_split;
   const int c_end = min(n_chunks, c_begin + chunks_per_split);
   if (c_begin >= c_end) return;
 
@@ -290,7 +314,7 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
       const int task = task0 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
       if (task < n_tasks) {
         if (SPLIT) {
-          float *p = part + (((size_t)blockIdx.y * n_tasks + task) * 2) * m_pad + m;
+          float *p = part + (((size_t)by * n_tasks + task) * 2) * m_pad + m;
           if (m < m_pad) { p[0] = acc0[c][r]; p[m_pad] = acc1[c][r]; }
         } else if (m_ok) {
           epi.finish(task, m, rd, acc0[c][r], acc1[c][r], st);

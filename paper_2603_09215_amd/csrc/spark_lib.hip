@@ -75,6 +75,7 @@ struct spark_ctx {
   bool use_mfma = true;        // SPARK_NO_MFMA=1 keeps every row count on the vector kernels
   unsigned bar_round = 0;      // grid barriers passed since the barrier words were zeroed
   unsigned long long *timeline_dev = nullptr;  // debugging aid, see SPARK_PASS_TIMELINE
+  int mfma_xcd_max_split = 4;   // SPARK_MFMA_XCD_MAX_SPLIT: row tiles share an XCD when k has at most this many ranges
   int mfma_small_tiles = 32;   // launches with fewer 8-wave tiles use 4-wave workgroups (SPARK_MFMA_SMALL_TILES)
   int mfma_min_rows = MFMA_MIN_ROWS;   // SPARK_MFMA_MIN_ROWS
   int attn_pieces = 0;   // SPARK_ATTN_PIECES: 64-token pieces per attention workgroup (0: by the launch's size)
@@ -542,11 +543,14 @@ int launch_mfma_shape(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, 
   const bf16_t *xs = at<bf16_t>(c, second_input ? c->lo.xsplit2 : c->lo.xsplit);
   const size_t xst = xsplit_stride(c);
   float *part = at<float>(c, c->lo.mfma_part);
-  dim3 grid(bx, split, z);
+  // one-dimensional grid: the kernel deals its ids so that the row tiles of a weight tile share an XCD
+  const int xcd_groups = z > 1 && split <= c->mfma_xcd_max_split;
+  const int tiles_padded = xcd_groups ? (bx * split + 7) / 8 * 8 : bx * split;
+  dim3 grid(tiles_padded * z);
   const size_t lds = mg_lds_bytes(MTILES, WAVES);
   if (split > 1) {
     mfma_rows_k<MTILES, Epi, true, WAVES><<<grid, 64 * WAVES, lds, c->stream>>>(
-        epi, rows, m, xs, xst, n_in, n_tasks, cps, part, m_pad);
+        epi, rows, m, xs, xst, n_in, n_tasks, cps, part, m_pad, bx, split, z, xcd_groups);
     const int tpt = finish_tasks_per_thread(epi);
     const int total = ((n_tasks + tpt - 1) / tpt) * m_pad;
     if (tpt == 1)   // epilogues without a running state: stores coalesced over tasks
@@ -558,7 +562,7 @@ int launch_mfma_shape(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, 
     occ = mfma_occupancy<MTILES, Epi, false, WAVES>(c);
     if (occ < 0) return occ;
     mfma_rows_k<MTILES, Epi, false, WAVES><<<grid, 64 * WAVES, lds, c->stream>>>(
-        epi, rows, m, xs, xst, n_in, n_tasks, cps, part, m_pad);
+        epi, rows, m, xs, xst, n_in, n_tasks, cps, part, m_pad, bx, split, z, xcd_groups);
   }
   HIP_TRY(c, hipGetLastError());
   return SPARK_OK;
@@ -1014,6 +1018,7 @@ int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_p
   if (const char *v = getenv("SPARK_ATTN_PIECES")) c->attn_pieces = std::max(0, std::min(8, atoi(v)));
   if (const char *v = getenv("SPARK_MFMA_SMALL_TILES")) c->mfma_small_tiles = atoi(v);
   if (const char *v = getenv("SPARK_MFMA_MIN_ROWS")) c->mfma_min_rows = std::max(1, atoi(v));
+  if (const char *v = getenv("SPARK_MFMA_XCD_MAX_SPLIT")) c->mfma_xcd_max_split = atoi(v);
   const char *no_mfma = getenv("SPARK_NO_MFMA");
   // the MFMA kernels load 16-byte vectors of 8 weights; other widths stay on the vector kernel
   c->use_mfma = !(no_mfma && no_mfma[0] == '1') && cfg->d_model % 8 == 0 &&
