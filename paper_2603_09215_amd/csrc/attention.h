@@ -254,11 +254,13 @@ attn_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ qbuf, KV
 // ------------------------------------------------------------------ the same task on the MFMA units
 //
 // bf16 cache, head_dim 128, up to 16 query heads per KV head, one workgroup (4 waves) per
-// (slice, KV head, row), all query heads of the group together.  v_mfma_f32_16x16x32_bf16 twice:
+// (slice, KV head or half of its query heads, row); a slice is one or several 64-token pieces,
+// taken one after the other.  Per piece, v_mfma_f32_16x16x32_bf16 twice:
 //   scores   S^T[token][head] = K[token][:] . Q[head][:]   wave w takes tokens 16w .. 16w+15; the K
 //            rows go from memory straight into the A operand (lane l: token l%16, eight
 //            consecutive elements at 8*(l/16) of each 32-wide step), the scaled queries, split into
-//            three bf16 parts that add up to the fp32 value, are the B operand;
+//            three bf16 parts that add up to the fp32 value (once per workgroup, handed to the
+//            waves through LDS), are the B operand;
 //   values   O[head][hd] = P[head][token] . V[token][hd]   wave w takes hd 32w .. 32w+31 over all
 //            64 tokens; P (two bf16 parts) crosses the waves through LDS in A-operand order, V is
 //            staged in LDS as it lies in the cache (token-major) and gathered column-wise, the
