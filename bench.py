@@ -75,6 +75,9 @@ def main() -> int:
     ap.add_argument("--speech-share", type=float, default=0.0,
                     help="e.g. 0.795: the text ends early, so that this share of the warm-up + timed tokens is "
                          "speech (the interleave alone gives n_speech / (n_text + n_speech))")
+    ap.add_argument("--align-phases", action="store_true",
+                    help="batch > 1 with --speech-share: once every sequence is in its speech tail (after the "
+                         "warm-up), move the phases so that the full-depth steps of the batch coincide")
     ap.add_argument("--temperature", type=float, default=0.0,
                     help="> 0: draw tokens by temperature / nucleus sampling instead of the arg-max")
     ap.add_argument("--top-p", type=float, default=0.9)
@@ -146,8 +149,8 @@ def main() -> int:
     text_budget = 0
     if args.speech_share > 0:
         text_budget = max(1, round((1.0 - args.speech_share) * (W + K)))
-        for s_ in sids:
-            sp.seq_text_budget(s_, text_budget)
+        for i_, s_ in enumerate(sids):   # a batch: the responses' texts differ in length (+- a third, seeded)
+            sp.seq_text_budget(s_, text_budget if B == 1 else max(1, round(text_budget * (2 / 3 + 2 / 3 * i_ / (B - 1)))))
     sampled = args.temperature > 0
     if sampled:   # one 64-bit random word per step and sequence, drawn ahead of the timed region
         sp.set_sampling(args.temperature, args.top_p)
@@ -156,6 +159,8 @@ def main() -> int:
     else:
         decode = lambda n, first: sp.decode(n, sids)
     decode(W, 0)
+    if args.align_phases:
+        sp.align_phases(sids)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     tok, dep = decode(K, W)
@@ -266,6 +271,7 @@ def main() -> int:
                                f"scope={'chunk' if sched.scope == 0 else 'stream'}"
                                f"{', cycle offsets aligned' if args.aligned and B > 1 else ''}"
                                f"{f', text ends after {text_budget} tokens (speech share {args.speech_share})' if text_budget else ''}"
+                               f"{', phases aligned after the warm-up' if args.align_phases else ''}"
                                f"{f', sampled T={args.temperature} top_p={args.top_p}' if sampled else ', greedy'}",
                    "weights": "random N(0,0.02), fp32 accumulation", "kv_cache": "paged, 64 tokens/page",
                    "step_mix": mix, "mean_speech_depth": stats["mean_speech_depth"],

@@ -144,6 +144,18 @@ int spark_seq_open(spark_ctx *ctx, int32_t cycle_offset, int32_t *seq_id);
  * sequence has generated already (SPARK_EINVAL; SPARK_ESTATE if a budget is set). */
 int spark_seq_text_budget(spark_ctx *ctx, int32_t seq_id, int32_t n_text_tokens);
 
+/* The phase of the schedule on speech positions is a free choice (Table II: the Even, Odd and
+ * Triple variants differ in little else), and in a batch it decides whether the sequences'
+ * full-depth steps fall on the same steps: only then does an early-exit step skip the upper layers
+ * for the whole batch (Sec. IV-B.3).  spark_seq_set_phase moves one sequence's phase (0 <= phase <
+ * period_k) for its future speech positions; spark_align_phases moves the phases of n sequences
+ * [host ids] so that, counted in their own speech positions, each runs full depth at its K-th
+ * speech position from now and every K-th after it (SPARK_SCOPE_STREAM only).  The move can join
+ * two runs of early exits (at most 2K-2 pending positions, which the pending slots hold).  Not
+ * available with a schedule on text positions (SPARK_EINVAL). */
+int spark_seq_set_phase(spark_ctx *ctx, int32_t seq_id, int32_t phase);
+int spark_align_phases(spark_ctx *ctx, int32_t n, const int32_t *seq_ids);
+
 /* Condition on a prompt [host] of n >= 1 ids: positions 0..n-2 are run at full depth and fill
  * the KV of every layer; the last id is held as the input of the first spark_step, so that every
  * generated token comes out of spark_step with its executed depth.  One prompt per sequence. */

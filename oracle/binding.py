@@ -56,6 +56,9 @@ def load(kind: str = "f32") -> C.CDLL:
     lib.ora_schedule_run.argtypes = [C.POINTER(OraConfig), I, I, P, P]
     lib.ora_schedule_run_budget.argtypes = [C.POINTER(OraConfig), I, I, I, P, P]
     lib.ora_seq_text_budget.argtypes = [P, I]
+    lib.ora_seq_set_phase.argtypes = [P, I]
+    lib.ora_schedule_run_moves.argtypes = [C.POINTER(OraConfig), I, I, I, I, P, P, P, P]
+    lib.ora_seq_j_stream.argtypes = [P]
     lib.ora_layer_saving.restype = C.c_double
     lib.ora_layer_saving.argtypes = [P, I, I]
     for f in ("ora_seq_len", "ora_seq_upper_valid", "ora_seq_pending"):
@@ -117,6 +120,20 @@ def schedule_run(shape, sched, n_steps: int, cycle_offset: int = 0, kind: str = 
     return depth, is_text
 
 
+def schedule_run_moves(shape, sched, n_steps: int, moves, cycle_offset: int = 0, text_budget: int = 0,
+                       kind: str = "f32"):
+    """schedule_run with the speech phase moved on the way: moves = [(step, phase), ...], ascending"""
+    lib = load(kind)
+    cfg = make_config(shape, sched, 1)
+    depth = np.zeros(n_steps, dtype=np.int32)
+    is_text = np.zeros(n_steps, dtype=np.int32)
+    ms = np.array([m[0] for m in moves], dtype=np.int32)
+    mp = np.array([m[1] for m in moves], dtype=np.int32)
+    rc = lib.ora_schedule_run_moves(C.byref(cfg), cycle_offset, text_budget, n_steps, len(moves), _ptr(ms), _ptr(mp),
+                                    _ptr(depth), _ptr(is_text))
+    return (depth, is_text) if rc == 0 else None
+
+
 def layer_saving(depth: np.ndarray, n_layers: int, kind: str = "f32") -> float:
     d = np.ascontiguousarray(depth, dtype=np.int32)
     return float(load(kind).ora_layer_saving(_ptr(d), len(d), n_layers))
@@ -160,6 +177,14 @@ class Seq:
         self.handle = self.lib.ora_seq_open(model.handle, cycle_offset)
         if not self.handle:
             raise MemoryError("oracle sequence")
+
+    def set_phase(self, phase: int) -> int:
+        """move the sequence's phase on speech positions"""
+        return self.lib.ora_seq_set_phase(self.handle, phase)
+
+    @property
+    def j_stream(self) -> int:
+        return self.lib.ora_seq_j_stream(self.handle)
 
     def text_budget(self, budget: int) -> int:
         """after `budget` text tokens in all the sequence generates speech only"""

@@ -92,6 +92,7 @@ typedef struct {
   int texts;        /* number of text tokens emitted so far */
   int run;          /* speech positions since the last text position (= index inside the chunk) */
   int text_budget;  /* > 0: after this many text tokens every position is speech */
+  int speech_phase; /* the sequence's phase on speech positions (the configuration's unless moved) */
   int n_pending;    /* early-exited positions whose upper KV is deferred */
   real *pend_h;     /* [2K][d]: h^(e) of the pending positions, oldest first, then the current */
   int *pend_pos;    /* [2K] */
@@ -398,8 +399,8 @@ static void sched_start(const ora_config *c, int cycle_offset, sched_state *st) 
 }
 
 /* modality and depth of the position about to be generated */
-static void sched_decide(const ora_config *c, int cycle_offset, int text_budget, const sched_state *st,
-                         int *is_text, int *full) {
+static void sched_decide(const ora_config *c, int cycle_offset, int text_budget, int speech_phase,
+                         const sched_state *st, int *is_text, int *full) {
   int cyc = c->n_text + c->n_speech;
   int slot = (int)(((int64_t)st->g + cycle_offset) % cyc);
   int text_over = text_budget > 0 && st->texts >= text_budget;
@@ -412,7 +413,7 @@ static void sched_decide(const ora_config *c, int cycle_offset, int text_budget,
   } else {
     /* inside a chunk: the slot's place in it; after the text has ended the running chunk goes on */
     int j = (c->scope == 1) ? st->j_stream : (text_over ? st->run : slot - c->n_text);
-    *full = c->period_k == 1 || (j % c->period_k == c->phase);
+    *full = c->period_k == 1 || (j % c->period_k == speech_phase);
   }
 }
 
@@ -456,7 +457,7 @@ static int config_ok(const ora_config *c) {
     sched_start(c, 0, &st);
     for (int g = 0; g < 2 * cyc; ++g) {
       int is_text, full;
-      sched_decide(c, 0, 0, &st, &is_text, &full);
+      sched_decide(c, 0, 0, c->phase, &st, &is_text, &full);
       sched_advance(&st, is_text);
       if (full) { any_full = 1; run = 0; } else if (++run > longest) longest = run;
     }
@@ -474,7 +475,29 @@ int ora_schedule_run_budget(const ora_config *c, int cycle_offset, int text_budg
   sched_start(c, cycle_offset, &st);
   for (int g = 0; g < n_steps; ++g) {
     int is_text, full;
-    sched_decide(c, cycle_offset, text_budget, &st, &is_text, &full);
+    sched_decide(c, cycle_offset, text_budget, c->phase, &st, &is_text, &full);
+    depth_out[g] = full ? c->n_layers : c->exit_layer;
+    is_text_out[g] = is_text;
+    sched_advance(&st, is_text);
+  }
+  return ORA_OK;
+}
+
+/* the same with the speech phase moved on the way: before generated token move_step[i] is decided
+ * the phase becomes move_phase[i] (move_step ascending) */
+int ora_schedule_run_moves(const ora_config *c, int cycle_offset, int text_budget, int n_steps, int n_moves,
+                           const int32_t *move_step, const int32_t *move_phase, int32_t *depth_out,
+                           int32_t *is_text_out) {
+  if (!config_ok(c) || cycle_offset < 0 || (n_moves > 0 && c->text_period_k > 1)) return ORA_EINVAL;
+  for (int i = 0; i < n_moves; ++i)
+    if (move_phase[i] < 0 || move_phase[i] >= c->period_k) return ORA_EINVAL;
+  sched_state st;
+  sched_start(c, cycle_offset, &st);
+  int phase = c->phase, next = 0;
+  for (int g = 0; g < n_steps; ++g) {
+    while (next < n_moves && move_step[next] <= g) phase = move_phase[next++];
+    int is_text, full;
+    sched_decide(c, cycle_offset, text_budget, phase, &st, &is_text, &full);
     depth_out[g] = full ? c->n_layers : c->exit_layer;
     is_text_out[g] = is_text;
     sched_advance(&st, is_text);
@@ -523,6 +546,7 @@ ora_seq *ora_seq_open(ora_model *m, int cycle_offset) {
   if (!s) return NULL;
   s->m = m;
   s->cycle_offset = cycle_offset;
+  s->speech_phase = c->phase;
   {
     sched_state st;
     sched_start(c, cycle_offset, &st);
@@ -632,7 +656,7 @@ int ora_step(ora_seq *s, int forced_next, int32_t *tok_out, int32_t *depth_out,
 
   int is_text, full;
   sched_state st = {s->g, s->j_stream, s->texts, s->run};
-  sched_decide(c, s->cycle_offset, s->text_budget, &st, &is_text, &full);
+  sched_decide(c, s->cycle_offset, s->text_budget, s->speech_phase, &st, &is_text, &full);
 
   ora_tmp t;
   if (tmp_alloc(c, pend_cap(c), &t)) return ORA_ENOMEM;
@@ -699,6 +723,18 @@ int ora_seq_text_budget(ora_seq *s, int budget) {
   s->text_budget = budget;
   return ORA_OK;
 }
+
+/* The phase on speech positions is free (Table II's Even / Odd / Triple variants): a caller may
+ * move it for a sequence's future positions, e.g. to line up the full-depth steps of a batch.
+ * Not with early exits on text positions (the joined runs of early exits would outgrow the
+ * pending buffer). */
+int ora_seq_set_phase(ora_seq *s, int phase) {
+  if (!s || phase < 0 || phase >= s->m->c.period_k || s->m->c.text_period_k > 1) return ORA_EINVAL;
+  s->speech_phase = phase;
+  return ORA_OK;
+}
+
+int ora_seq_j_stream(const ora_seq *s) { return s->j_stream; }
 
 int ora_seq_len(const ora_seq *s) { return s->len; }
 int ora_seq_upper_valid(const ora_seq *s) { return s->upper_valid; }

@@ -25,7 +25,7 @@ EXPORTS = ("spark_workspace_bytes", "spark_init", "spark_seq_open", "spark_prefi
            "spark_decode", "spark_get_logits", "spark_get_kv", "spark_seq_state",
            "spark_get_stats", "spark_seq_close", "spark_destroy", "spark_last_error",
            "spark_profile_select", "spark_profile_read", "spark_set_sampling", "spark_decode_sampled",
-           "spark_seq_text_budget", "spark_schedule_preview")
+           "spark_seq_text_budget", "spark_schedule_preview", "spark_seq_set_phase", "spark_align_phases")
 
 
 class SparkConfig(C.Structure):
@@ -81,6 +81,8 @@ def load_library() -> C.CDLL:
     lib.spark_decode.argtypes = [P, I, I, P, P, P, P]
     lib.spark_set_sampling.argtypes = [P, C.c_float, C.c_float]
     lib.spark_seq_text_budget.argtypes = [P, I, I]
+    lib.spark_seq_set_phase.argtypes = [P, I, I]
+    lib.spark_align_phases.argtypes = [P, I, P]
     lib.spark_schedule_preview.argtypes = [C.POINTER(SparkConfig), I, I, I, P, P]
     lib.spark_decode_sampled.argtypes = [P, I, I, P, P, P, P, P]
     lib.spark_get_logits.argtypes = [P, I, P, C.POINTER(I)]
@@ -221,6 +223,13 @@ class Spark:
 
     def seq_text_budget(self, seq_id: int, n_text_tokens: int) -> None:
         self._check(self.lib.spark_seq_text_budget(self.handle, seq_id, n_text_tokens))
+
+    def seq_set_phase(self, seq_id: int, phase: int) -> None:
+        self._check(self.lib.spark_seq_set_phase(self.handle, seq_id, phase))
+
+    def align_phases(self, seq_ids) -> None:
+        ids = np.ascontiguousarray(seq_ids, dtype=np.int32)
+        self._check(self.lib.spark_align_phases(self.handle, len(ids), _iptr(ids)))
 
     def set_sampling(self, temperature: float, top_p: float) -> None:
         self._check(self.lib.spark_set_sampling(self.handle, temperature, top_p))

@@ -9,8 +9,8 @@
 
 namespace spark {
 
-// device-resident per-sequence state, 9 ints
-enum { ST_LEN = 0, ST_G, ST_JSTREAM, ST_NPENDING, ST_OFFSET, ST_NEXT, ST_ACTIVE, ST_LASTFULL, ST_TEXTBUDGET, ST_WORDS };
+// device-resident per-sequence state, 10 ints
+enum { ST_LEN = 0, ST_G, ST_JSTREAM, ST_NPENDING, ST_OFFSET, ST_NEXT, ST_ACTIVE, ST_LASTFULL, ST_TEXTBUDGET, ST_PHASE, ST_WORDS };
 // plan words
 enum { PL_NLOWER = 0, PL_NUPPER, PL_NEE, PL_NFULL, PL_ERR, PL_BARRIER_ERR, PL_WORDS = 8 };
 enum { ERR_NAN = 1, ERR_INACTIVE = 2, ERR_BARRIER = 4 };
@@ -42,15 +42,17 @@ __host__ __device__ inline int nth_text_position(const SchedParams &sp, int offs
   return (cyc - off) + (rest / sp.n_text) * cyc + rest % sp.n_text;
 }
 
+// speech_phase: the sequence's own phase on speech positions (sp.phase unless the caller moved it to
+// line the sequence's full-depth steps up with those of the other sequences of its batch).
 __host__ __device__ inline void schedule_decide(const SchedParams &sp, int g, int offset, int j_stream,
-                                                int text_budget, int &is_text, int &full) {
+                                                int text_budget, int speech_phase, int &is_text, int &full) {
   const int cyc = sp.n_text + sp.n_speech;
   const int slot = (int)(((long long)g + offset) % cyc);
   const int texts = g - j_stream;                 // text positions so far
   const bool text_over = text_budget > 0 && texts >= text_budget;
   is_text = slot < sp.n_text && !text_over;
   const int period = is_text ? sp.text_period_k : sp.period_k;
-  const int want = is_text ? sp.text_phase : sp.phase;
+  const int want = is_text ? sp.text_phase : speech_phase;
   int idx;
   if (is_text) idx = sp.scope == 0 ? slot : texts;
   else if (sp.scope != 0) idx = j_stream;
@@ -73,7 +75,7 @@ sched_dispatch_k(SchedParams sp, int n, const int *__restrict__ seq_ids, const i
     const int *st = state + seq * ST_WORDS;
     len = st[ST_LEN];
     npend = st[ST_NPENDING];
-    schedule_decide(sp, st[ST_G], st[ST_OFFSET], st[ST_JSTREAM], st[ST_TEXTBUDGET], is_text, full);
+    schedule_decide(sp, st[ST_G], st[ST_OFFSET], st[ST_JSTREAM], st[ST_TEXTBUDGET], st[ST_PHASE], is_text, full);
     lower[i] = RowDesc{seq * sp.rmax + npend, seq, len, i};
     out_depth[i] = full ? sp.n_layers : sp.exit_layer;
     step_flags[i] = full | (is_text << 1);

@@ -48,6 +48,7 @@ struct Seq {
   bool open = false, prefilled = false;
   int cycle_offset = 0, len = 0, g = 0, j_stream = 0, n_pending = 0, last_full = 0;
   int text_budget = 0;   // > 0: speech only after this many text tokens
+  int phase = 0;         // the sequence's phase on speech positions (the configuration's, unless moved)
   std::vector<int> pages;
   int64_t text_steps = 0, speech_full = 0, speech_ee = 0, text_ee = 0;
   int64_t flush_rows[2 * SPARK_MAX_PERIOD] = {0};
@@ -160,7 +161,7 @@ bool config_ok(const spark_config *c, char *why, size_t n) {
     bool any_full = false;
     for (int g = 0; g < 2 * cyc; ++g) {
       int is_text, full;
-      schedule_decide(sp, g, 0, 0, 0, is_text, full);
+      schedule_decide(sp, g, 0, 0, 0, sp.phase, is_text, full);
       if (full) { any_full = true; run = 0; } else { longest = std::max(longest, ++run); }
     }
     BAD(!any_full, "a cycle without a full-depth slot would never complete its KV");
@@ -848,7 +849,7 @@ int decode_chunk(spark_ctx *c, int steps, int n, const int32_t *seq_ids, const i
     for (int i = 0; i < n; ++i) {
       int is_text, full;
       const Seq &sq = c->seqs[seq_ids[i]];
-      schedule_decide(c->sp, mir[i].g, sq.cycle_offset, mir[i].j, sq.text_budget, is_text, full);
+      schedule_decide(c->sp, mir[i].g, sq.cycle_offset, mir[i].j, sq.text_budget, sq.phase, is_text, full);
       want_depth[st * n + i] = full ? g.n_layers : g.exit_layer;
       want_text[st * n + i] = is_text;
       want_rows[st * n + i] = full ? mir[i].npend + 1 : 0;
@@ -968,7 +969,7 @@ int spark_schedule_preview(const spark_config *cfg, int32_t cycle_offset, int32_
   int j_stream = 0;
   for (int g = 0; g < n_steps; ++g) {
     int is_text, full;
-    schedule_decide(sp, g, cycle_offset, j_stream, text_budget, is_text, full);   // the function the device runs
+    schedule_decide(sp, g, cycle_offset, j_stream, text_budget, sp.phase, is_text, full);   // the function the device runs
     depth_out[g] = full ? cfg->n_layers : cfg->exit_layer;
     is_text_out[g] = is_text;
     if (!is_text) ++j_stream;
@@ -1066,6 +1067,7 @@ int spark_seq_open(spark_ctx *c, int32_t cycle_offset, int32_t *seq_id) {
       c->seqs[i] = Seq();
       c->seqs[i].open = true;
       c->seqs[i].cycle_offset = cycle_offset % (c->cfg.n_text + c->cfg.n_speech);
+      c->seqs[i].phase = c->cfg.phase;
       *seq_id = i;
       return SPARK_OK;
     }
@@ -1094,6 +1096,7 @@ int spark_prefill(spark_ctx *c, int32_t seq_id, const int32_t *prompt, int32_t n
   st[ST_NEXT] = prompt[n - 1];
   st[ST_ACTIVE] = 1;
   st[ST_TEXTBUDGET] = s->text_budget;
+  st[ST_PHASE] = s->phase;
   HIP_TRY(c, hipMemcpyAsync(at<int>(c, c->lo.state) + (size_t)seq_id * ST_WORDS, st, sizeof(st),
                             hipMemcpyHostToDevice, c->stream));
   HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -1205,6 +1208,44 @@ int spark_seq_text_budget(spark_ctx *c, int32_t seq_id, int32_t n_text_tokens) {
     HIP_TRY(c, hipMemcpyAsync(at<int>(c, c->lo.state) + (size_t)seq_id * ST_WORDS + ST_TEXTBUDGET,
                               &s->text_budget, sizeof(int), hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+  }
+  return SPARK_OK;
+}
+
+namespace {
+int set_phase(spark_ctx *c, int seq_id, Seq *s, int phase) {
+  s->phase = phase;
+  if (s->prefilled) {   // the state is on the device already
+    HIP_TRY(c, hipMemcpyAsync(at<int>(c, c->lo.state) + (size_t)seq_id * ST_WORDS + ST_PHASE, &s->phase,
+                              sizeof(int), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+  }
+  return SPARK_OK;
+}
+}  // namespace
+
+int spark_seq_set_phase(spark_ctx *c, int32_t seq_id, int32_t phase) {
+  if (!c) return SPARK_EINVAL;
+  Seq *s = find_seq(c, seq_id);
+  if (!s) return fail(c, SPARK_ENOSEQ, "unknown sequence id %d", seq_id);
+  if (phase < 0 || phase >= c->cfg.period_k) return fail(c, SPARK_EINVAL, "phase outside [0, period_k)");
+  // a moved phase can join two runs of early exits: K-1 before and K-1 after the move, which the
+  // pending slots hold; runs that early-exited text positions could extend further are not allowed
+  if (c->cfg.text_period_k > 1) return fail(c, SPARK_EINVAL, "the phase cannot be moved when text exits early too");
+  return set_phase(c, seq_id, s, phase);
+}
+
+int spark_align_phases(spark_ctx *c, int32_t n, const int32_t *seq_ids) {
+  if (!c || n < 1 || !seq_ids) return SPARK_EINVAL;
+  if (c->cfg.scope != SPARK_SCOPE_STREAM) return fail(c, SPARK_EINVAL, "phases are aligned over stream counters only");
+  if (c->cfg.text_period_k > 1) return fail(c, SPARK_EINVAL, "the phase cannot be moved when text exits early too");
+  for (int i = 0; i < n; ++i)
+    if (!find_seq(c, seq_ids[i])) return fail(c, SPARK_ENOSEQ, "unknown sequence id %d", seq_ids[i]);
+  const int K = c->cfg.period_k;
+  for (int i = 0; i < n; ++i) {
+    Seq *s = find_seq(c, seq_ids[i]);
+    // the K-th speech position from now runs full depth, for every sequence alike
+    if (int rc = set_phase(c, seq_ids[i], s, (s->j_stream + K - 1) % K)) return rc;
   }
   return SPARK_OK;
 }

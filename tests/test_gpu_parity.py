@@ -343,3 +343,56 @@ def test_long_contexts(sb, name, shape_kw, page, long_prompt):
     res = compare_run(sp, shape, sched, weights, prompts, [0, 2], 24, check_kv_every=8, chunk=3, label=name)
     assert len(np.unique(res["depths"])) == 2
     sp.close()
+
+
+def test_moved_and_aligned_phases(sb, tiny_weights):
+    """a sequence's speech phase moved between steps, and a batch aligned (Sec. IV-B.3: an
+    early-exit step skips the upper layers only if no sequence of the batch needs them): depths,
+    tokens and logits against the oracle with the same moves; after the alignment the sequences,
+    all in their speech tail, run full depth on the same steps"""
+    from oracle import binding as ob
+    w = wl.TINY
+    say("case moved phases")
+    sched = w.schedule.replace(scope=wl.SCOPE_STREAM, n_text=1, n_speech=2)
+    K = sched.period_k
+    sp = sb.Spark(w.shape, sched, tiny_weights, max_batch=3, max_seq_len=160, kv_page_tokens=16)
+    om = ob.Model(w.shape, sched, tiny_weights, max_seq_len=160)
+    offsets, budgets = [0, 1, 2], [2, 4, 3]
+    sids = [sp.seq_open(o) for o in offsets]
+    oseqs = [om.open(o) for o in offsets]
+    for b in range(3):
+        prompt = wl.make_prompt(w.shape, 9 + 2 * b, seed=40 + b)
+        sp.prefill(sids[b], prompt)
+        assert oseqs[b].prefill(prompt) == 0
+        sp.seq_text_budget(sids[b], budgets[b])
+        assert oseqs[b].text_budget(budgets[b]) == 0
+    n = 60
+    forced = np.stack([wl.make_forced_stream(w.shape, n, 1, 2, offsets[b], seed=50 + b) for b in range(3)], axis=1)
+    depths = []
+    for i in range(n):
+        if i == 7:                                   # one sequence alone
+            sp.seq_set_phase(sids[1], 0)
+            assert oseqs[1].set_phase(0) == 0
+            with pytest.raises(sb.SparkError):
+                sp.seq_set_phase(sids[1], K)
+        if i == 24:                                  # the whole batch, all in their speech tail by now
+            sp.align_phases(sids)
+            for b in range(3):
+                assert oseqs[b].set_phase((oseqs[b].j_stream + K - 1) % K) == 0
+        tok, dep = sp.step(sids, forced[i])
+        for b in range(3):
+            rc, otok, odep, ologits = oseqs[b].step(forced_next=int(forced[i, b]))
+            assert rc == 0 and dep[b] == odep, (i, b, dep[b], odep)
+            glogits, _ = sp.get_logits(sids[b])
+            assert np.max(np.abs(glogits - ologits)) <= 1e-4
+            assert tok[b] == otok or ologits[otok] - ologits[tok[b]] <= 2e-4
+        depths.append(dep.copy())
+    depths = np.array(depths)
+    tail = depths[24:]
+    assert np.all(tail == tail[:, :1])                        # the same depth for all three, step by step
+    full = np.flatnonzero(tail[:, 0] == w.shape.n_layers)
+    assert full[0] == K - 1 and np.all(np.diff(full) == K)
+    assert not np.all(depths[8:24] == depths[8:24, :1])       # before the alignment they differed
+    for os_ in oseqs:
+        os_.close()
+    om.close(); sp.close()

@@ -311,3 +311,64 @@ def test_text_budget_reproduces_the_speech_share_of_the_paper():
     b = ob.schedule_run(shape_with_layers(28), sched, 60, 1, text_budget=0)
     c = ob.schedule_run(shape_with_layers(28), sched, 60, 1, text_budget=10 ** 6)
     assert list(a[0]) == list(b[0]) == list(c[0]) and list(a[1]) == list(c[1])
+
+
+# ---------------------------------------------------------------- a phase that moves
+
+def test_moved_phase_against_brute_force():
+    """Table II: the phase is a free choice (Even / Odd / Triple).  A sequence's phase may be
+    moved for its future speech positions; written out from lists: the rule with the phase that
+    is in force at each position."""
+    rng = np.random.default_rng(29)
+    L, checked = 12, 0
+    for _ in range(200):
+        e = int(rng.integers(1, L))
+        K = int(rng.integers(2, 6))
+        nt, ns = int(rng.integers(1, 4)), int(rng.integers(1, 9))
+        scope = int(rng.integers(0, 2))
+        off = int(rng.integers(0, nt + ns))
+        n = 7 * (nt + ns)
+        steps = sorted(int(x) for x in rng.integers(0, n, size=int(rng.integers(1, 4))))
+        moves = [(s, int(rng.integers(0, K))) for s in steps]
+        sched = wl.Schedule(e, K, int(rng.integers(0, K)), scope, nt, ns)
+        base = ob.schedule_run(shape_with_layers(L), sched, n, off)
+        if base is None:
+            continue
+        got = ob.schedule_run_moves(shape_with_layers(L), sched, n, moves, off)
+        speech_seen, phase = 0, sched.phase
+        for g in range(n):
+            for s, p in moves:
+                if s <= g:
+                    phase = p       # the last move at or before g wins (moves are ascending)
+            slot = (g + off) % (nt + ns)
+            if slot < nt:
+                assert got[1][g] == 1 and got[0][g] == L
+            else:
+                idx = slot - nt if scope == wl.SCOPE_CHUNK else speech_seen
+                assert got[1][g] == 0 and got[0][g] == (L if idx % K == phase else e), (g, moves)
+                speech_seen += 1
+        checked += 1
+    assert checked > 100
+
+
+def test_aligned_phases_make_full_depth_steps_coincide():
+    """The alignment a batch scheduler wants: every sequence gets phase (j + K - 1) mod K, j its
+    speech count so far.  From then on, sequences that generate speech only run full depth on the
+    same steps, every K-th; the run of early exits joined by the move stays within 2K - 2."""
+    L, e, K = 28, 20, 4
+    sched = wl.Schedule(e, K, 3, wl.SCOPE_STREAM, 1, 2)
+    n, at = 120, 50
+    rows = []
+    for off, budget in [(0, 5), (1, 9), (2, 3), (1, 12)]:
+        d0, t0 = ob.schedule_run(shape_with_layers(L), sched, n, off, text_budget=budget)
+        assert not t0[at - 6:].any()                       # every sequence is in its speech tail by then
+        j = int((t0[:at] == 0).sum())                      # speech positions before step `at`
+        d, t = ob.schedule_run_moves(shape_with_layers(L), sched, n, [(at, (j + K - 1) % K)], off, text_budget=budget)
+        assert np.array_equal(d[:at], d0[:at]) and np.array_equal(t, t0)
+        rows.append(d[at:])
+        ee_runs = "".join("f" if x == L else "e" for x in d).split("f")
+        assert max(len(r) for r in ee_runs) <= 2 * K - 2
+    rows = np.array(rows)
+    assert np.all(rows == rows[0])                          # the same steps for all four
+    full = np.flatnonzero(rows[0] == L)
+    assert full[0] == K - 1 and np.all(np.diff(full) == K)
