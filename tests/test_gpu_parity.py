@@ -138,6 +138,15 @@ def test_free_running_matches_oracle_until_a_near_tie(sb, tiny_weights):
     ("bf16-gqa16", dict(dtype=wl.DTYPE_BF16, n_layers=5, d_model=1024, n_q_heads=16, n_kv_heads=1,
                         head_dim=64, d_ffn=2048 + 264, vocab_text=2000, vocab_speech=777),
      dict(exit_layer=3, period_k=3, phase=2, n_text=2, n_speech=7)),
+    # MFMA attention (bf16 cache, head_dim 128) with 1, 4, 8 and 16 query heads per KV head
+    ("bf16-hd128-g1", dict(dtype=wl.DTYPE_BF16, n_layers=3, d_model=256, n_q_heads=2, n_kv_heads=2, head_dim=128,
+                           d_ffn=512), dict(exit_layer=2)),
+    ("bf16-hd128-g4", dict(dtype=wl.DTYPE_BF16, n_layers=3, d_model=256, n_q_heads=4, n_kv_heads=1, head_dim=128,
+                           d_ffn=512), dict(exit_layer=2)),
+    ("bf16-hd128-g8", dict(dtype=wl.DTYPE_BF16, n_layers=3, d_model=512, n_q_heads=8, n_kv_heads=1, head_dim=128,
+                           d_ffn=512), dict(exit_layer=1)),
+    ("bf16-hd128-g16", dict(dtype=wl.DTYPE_BF16, n_layers=3, d_model=512, n_q_heads=16, n_kv_heads=1, head_dim=128,
+                            d_ffn=768), dict(exit_layer=2, n_text=1, n_speech=2, scope=wl.SCOPE_STREAM)),
     ("fp32-wide", dict(n_layers=3, d_model=4096, n_q_heads=4, n_kv_heads=2, head_dim=128,
                        d_ffn=5000 - 8, vocab_text=700, vocab_speech=300),
      dict(exit_layer=2)),
