@@ -114,7 +114,8 @@ def main() -> int:
         dev_w = wl.make_weights(shape, seed=0)
     B = args.batch
     if B > 1:
-        plens = [int(x) for x in wl.make_prompt_lengths(B, 256, 2048, seed=3)]
+        plens = [args.prompt_len] * B if args.prompt_len else \
+            [int(x) for x in wl.make_prompt_lengths(B, 256, 2048, seed=3)]
         max_seq = min(16384, (max(plens) + W + K + 4 * args.profile_steps + 64 + 63) // 64 * 64)
     else:
         plens = [prompt_len]
@@ -264,7 +265,7 @@ def main() -> int:
         "dtype": "bf16" if shape.dtype == wl.DTYPE_BF16 else "f32", "data": "synthetic",
         "config": {"workload": f"{shape.name}: L={shape.n_layers} d={shape.d_model} "
                                f"{shape.n_q_heads}q/{shape.n_kv_heads}kv hd={shape.head_dim} F={shape.d_ffn} "
-                               f"V={shape.vocab}; prompt {prompt_len if B == 1 else '256..2048'}, decode {K}, batch {B}, "
+                               f"V={shape.vocab}; prompt {prompt_len if B == 1 or args.prompt_len else '256..2048'}, decode {K}, batch {B}, "
                                f"{sched.n_text}:{sched.n_speech} text:speech, e={sched.exit_layer}, "
                                f"K={sched.period_k}, phase={sched.phase}, "
                                f"{'K_text=' + str(sched.text_period_k) + ', ' if sched.text_period_k > 1 else ''}"
