@@ -31,15 +31,10 @@ template <int VEC, int NT> __device__ __forceinline__ void zero_tail(float *xrow
     *(float4 *)(xrow + lds_pos<VEC>(k)) = make_float4(0.f, 0.f, 0.f, 0.f);
 }
 
-// hidden-state slot of pass row mm (a chain of selects: indexing rd[] with a variable would put
-// the array in scratch memory)
-template <int MT> __device__ __forceinline__ int row_slot(const RowDesc *rd, int mm) {
-  int slot = rd[0].x_slot;
-#pragma unroll
-  for (int q = 1; q < MT; ++q)
-    if (q == mm) slot = rd[q].x_slot;
-  return slot;
-}
+// The kernel hands the prologues its row descriptors with the rows beyond the pass already replaced
+// by the last valid one, so rd[m] is read with the unrolled loops' constant m: an index computed
+// at run time (even through a chain of selects, which the compiler turns back into an index) puts
+// the array in scratch memory, a memory round trip per access.
 
 // ------------------------------------------------------------------ prologues (fill LDS)
 
@@ -57,7 +52,7 @@ struct ProPlain {
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
       int mm = m < n_valid ? m : n_valid - 1;
-      const int slot = indirect ? row_slot<MT>(rd, mm) : tile0 + mm;
+      const int slot = indirect ? rd[m].x_slot : tile0 + mm;
       const float *row = src + (size_t)slot * stride + k0;
       float *xrow = xs + m * kc;
       for (int kb = threadIdx.x * 4; kb < klen; kb += NT * 4 * BATCH) {
@@ -107,7 +102,7 @@ struct ProNorm {
         for (int b = 0; b < RB; ++b) {
           const int m = m0 + b < MT ? m0 + b : MT - 1;
           const int mm = m < n_valid ? m : n_valid - 1;
-          const float *row = hidden + (size_t)(indirect ? row_slot<MT>(rd, mm) : tile0 + mm) * d;
+          const float *row = hidden + (size_t)(indirect ? rd[m].x_slot : tile0 + mm) * d;
 #pragma unroll
           for (int i = 0; i < NI; ++i) {
             const int k = threadIdx.x * 4 + i * NT * 4;
@@ -152,7 +147,7 @@ struct ProNorm {
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
       int mm = m < n_valid ? m : n_valid - 1;
-      const float *row = hidden + (size_t)(indirect ? row_slot<MT>(rd, mm) : tile0 + mm) * d;
+      const float *row = hidden + (size_t)(indirect ? rd[m].x_slot : tile0 + mm) * d;
       float ss = 0.f;
       for (int k = threadIdx.x * 4; k < d; k += NT * 4) {
         float4 v = *(const float4 *)(row + k);
@@ -165,7 +160,7 @@ struct ProNorm {
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
       int mm = m < n_valid ? m : n_valid - 1;
-      const float *row = hidden + (size_t)(indirect ? row_slot<MT>(rd, mm) : tile0 + mm) * d;
+      const float *row = hidden + (size_t)(indirect ? rd[m].x_slot : tile0 + mm) * d;
       float tot = 0.f;
 #pragma unroll
       for (int w = 0; w < (NT / 64); ++w) tot += red[w * MT + m];

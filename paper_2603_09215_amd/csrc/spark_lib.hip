@@ -28,9 +28,10 @@ namespace {
 constexpr int PREFILL_CHUNK = 256;   // most prompt rows pushed through the layers together (buffers are sized for it)
 constexpr size_t MFMA_PARTIAL_BYTES = 48u << 20;  // k-split partial sums of one projection
 constexpr int MAX_STEPS_PER_CALL = 256;
-// rows from which the MFMA projections run (measured: four rows 4 % faster on them than in one
-// pass of the vector kernel, three rows 5 % slower)
-constexpr int MFMA_MIN_ROWS = 4;
+// rows from which the MFMA projections run: up to four rows are one pass of the vector kernel
+// (measured at four rows: level at the GLM shape, 14-20 % faster for a batch of four at the Step
+// shape); five rows would be two such passes
+constexpr int MFMA_MIN_ROWS = 5;
 constexpr int MAX_SEQ_LEN = 16384;
 
 struct Layout {  // byte offsets into the scratch buffer
@@ -80,6 +81,7 @@ struct spark_ctx {
   int mfma_small_tiles = 32;   // launches with fewer 8-wave tiles use 4-wave workgroups (SPARK_MFMA_SMALL_TILES)
   int mfma_min_rows = MFMA_MIN_ROWS;   // SPARK_MFMA_MIN_ROWS
   int attn_pieces = 0;   // SPARK_ATTN_PIECES: 64-token pieces per attention workgroup (0: by the launch's size)
+  int gemv_big_kb = 40;         // SPARK_GEMV_BIG_KB: vector-kernel launches with more LDS per workgroup run eight waves per workgroup
   int attn_mfma_min_rows = 1;   // passes with at least this many rows run attention on the MFMA units (where the shape allows)
   float temperature = 0.f, top_p = 0.f;   // nucleus sampling, off while temperature <= 0
   int prefill_chunk = 128;   // prompt rows per pass, see spark_init
@@ -282,7 +284,7 @@ int launch_gemv(spark_ctx *c, const Pro &pro, const Epi &epi, const RowDesc *row
   if (whole_row && kc < n_in) return fail(c, SPARK_EINVAL, "row of %d does not fit in LDS", n_in);
   // much LDS per workgroup means few workgroups per CU: those launches run eight waves per
   // workgroup, so that a CU still has 16 waves streaming
-  const bool big = sizeof(float) * (size_t)mt * kc > 54 * 1024;   // at most two workgroups per CU
+  const bool big = sizeof(float) * (size_t)mt * kc > (size_t)c->gemv_big_kb * 1024;   // at most three workgroups per CU
   const int threads = big ? GEMV_BIG_THREADS : GEMV_THREADS, waves = threads / 64;
   size_t lds = sizeof(float) * ((size_t)mt * kc + waves * mt);
   // one resident set of blocks: the kernel loops over its tasks, so the grid is sized to what the
@@ -1016,6 +1018,7 @@ int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_p
   const char *pass = getenv("SPARK_PASS_KERNEL");
   c->use_pass_kernel = pass && pass[0] == '1';
   if (const char *v = getenv("SPARK_ATTN_MFMA_MIN_ROWS")) c->attn_mfma_min_rows = std::max(1, atoi(v));
+  if (const char *v = getenv("SPARK_GEMV_BIG_KB")) c->gemv_big_kb = std::max(1, atoi(v));
   if (const char *v = getenv("SPARK_ATTN_PIECES")) c->attn_pieces = std::max(0, std::min(8, atoi(v)));
   if (const char *v = getenv("SPARK_MFMA_SMALL_TILES")) c->mfma_small_tiles = atoi(v);
   if (const char *v = getenv("SPARK_MFMA_MIN_ROWS")) c->mfma_min_rows = std::max(1, atoi(v));
