@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import pathlib
+import re
 import subprocess
 from concurrent.futures import ThreadPoolExecutor
 
@@ -28,12 +29,38 @@ def is_stale() -> bool:
     return any(p.stat().st_mtime > t for p in deps)
 
 
+def kernel_resources(remarks: str) -> dict[str, dict[str, int]]:
+    """per kernel, the figures of the compiler's resource-usage remarks (registers, scratch bytes
+    per lane, spills, waves per SIMD, LDS bytes)"""
+    table: dict[str, dict[str, int]] = {}
+    name = None
+    for line in remarks.splitlines():
+        m = re.search(r"remark: Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+            table[name] = {}
+            continue
+        m = re.search(r"remark:\s+([A-Za-z][A-Za-z /\[\]]*?): (\d+) \[-Rpass-analysis", line)
+        if m and name:
+            table[name][m.group(1).strip()] = int(m.group(2))
+    return table
+
+
 def _compile(src: pathlib.Path) -> pathlib.Path:
+    """One translation unit.  A kernel that uses scratch memory fails the build: every access to it
+    is a memory round trip, and in these kernels it has only ever meant an array that the compiler
+    could not keep in registers (an index computed at run time)."""
     obj = OBJ_DIR / (src.stem + ".o")
-    cmd = ["hipcc", *HIPCC_FLAGS, "-c", "-o", str(obj), str(src)]
+    cmd = ["hipcc", *HIPCC_FLAGS, "-Rpass-analysis=kernel-resource-usage", "-c", "-o", str(obj), str(src)]
     proc = subprocess.run(cmd, capture_output=True, text=True)
     if proc.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src.name}:\n" + proc.stderr[-4000:])
+    table = kernel_resources(proc.stderr)
+    (OBJ_DIR / (src.stem + ".resources.txt")).write_text(
+        "".join(f"{k} {' '.join(f'{a}={b}' for a, b in v.items())}\n" for k, v in sorted(table.items())))
+    bad = [k for k, v in table.items() if v.get("ScratchSize [bytes/lane]", 0) or v.get("VGPRs Spill", 0)]
+    if bad:
+        raise RuntimeError(f"{src.name}: kernels with scratch memory or spilled registers:\n  " + "\n  ".join(bad))
     return obj
 
 

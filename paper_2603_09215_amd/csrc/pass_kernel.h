@@ -103,12 +103,7 @@ __device__ __forceinline__ void pass_stage_norm(float *xs, int kc, const float *
   // raw row into LDS and the sum of squares on the way
 #pragma unroll
   for (int m = 0; m < MT; ++m) {
-    const int mm = m < n_valid ? m : n_valid - 1;
-    int x_slot = rd[0].x_slot;
-#pragma unroll
-    for (int i = 1; i < MT; ++i)
-      if (i == mm) x_slot = rd[i].x_slot;
-    const float *row = hidden + (size_t)x_slot * d;
+    const float *row = hidden + (size_t)rd[m].x_slot * d;   // rows beyond the pass repeat the last one
     float ss = 0.f;
     for (int k = tid * 4; k < d; k += PASS_THREADS * 4) {
       const float4 v = *(const float4 *)(row + k);
@@ -256,10 +251,7 @@ __device__ __forceinline__ void pass_gemv_phase(const PhaseIn &in, const Epi &ep
       const int rnd = rem / MT, m = rem - rnd * MT;
       const int task = rnd * n_waves + blockIdx.x * PASS_WAVES + w;
       if (task < pg.n_tasks && m < n_valid) {
-        RowDesc mine = rd[0];
-#pragma unroll
-        for (int mm = 1; mm < MT; ++mm)
-          if (mm == m) mine = rd[mm];
+        const RowDesc mine = rd[m];
         old = epi.load_old(task, mine);
       }
     }
@@ -347,10 +339,7 @@ __device__ __forceinline__ void pass_gemv_phase(const PhaseIn &in, const Epi &ep
       const int rnd = rem / MT, m = rem - rnd * MT;
       const int task = rnd * n_waves + blockIdx.x * PASS_WAVES + w;
       if (task < pg.n_tasks && m < n_valid) {
-        RowDesc mine = rd[0];
-#pragma unroll
-        for (int mm = 1; mm < MT; ++mm)
-          if (mm == m) mine = rd[mm];
+        const RowDesc mine = rd[m];
         const float *y = yres + ((w * PASS_MAX_ROUNDS + rnd) * MT + m) * 2;
         if constexpr (EpiReadsOld<Epi>::value) {
           if (i == lane) epi.finish_old(task, mine, y[0], y[1], old);
@@ -402,9 +391,11 @@ spark_pass_k(PassParams<WT> p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_waves = gridDim.x * PASS_WAVES, wave_global = blockIdx.x * PASS_WAVES + wave;
   const int n_valid = min(MT, p.m_rows);
-  RowDesc rd[MT];
-#pragma unroll
-  for (int m = 0; m < MT; ++m) rd[m] = p.rows[m < n_valid ? m : n_valid - 1];
+  // the row descriptors live in LDS: several places pick one by an index known only at run time,
+  // which in registers would send the array to scratch memory
+  __shared__ RowDesc rd[MT];
+  if (tid < MT) rd[tid] = p.rows[tid < n_valid ? tid : n_valid - 1];
+  __syncthreads();
   unsigned round = p.round_base;
   int tl = 0;
   auto mark = [&]() {
@@ -459,10 +450,7 @@ spark_pass_k(PassParams<WT> p) {
       for (int t = blockIdx.x; t < n_valid * per_row; t += gridDim.x) {
         const int r = t / per_row, rem = t - r * per_row;
         const int hk = rem / p.n_splits, split = rem - hk * p.n_splits;
-        RowDesc mine = rd[0];
-#pragma unroll
-        for (int m = 0; m < MT; ++m)
-          if (m == r) mine = rd[m];
+        const RowDesc mine = rd[r];
         if (split * ATTN_SLICE <= mine.pos) {
           __syncthreads();  // LDS of the previous task is free
           attn_task<WT, HD, G, PASS_THREADS, true>(mine, r, hk, hk * G, G, split, p.qbuf, p.kv, l,

@@ -68,3 +68,23 @@ def test_no_gpu_means_loud_failure():
         pytest.skip("a GPU is present")
     with pytest.raises(RuntimeError):
         sb.Spark(wl.TINY.shape, wl.TINY.schedule, {}, 1, 64)
+
+
+def test_no_kernel_uses_scratch_memory():
+    """The build writes the compiler's per-kernel resource figures next to the objects and refuses
+    a kernel with scratch memory or spilled vector registers (an array indexed at run time ends up
+    there, a memory round trip per access); this reads the same figures back."""
+    import pathlib
+    import pytest
+    bdir = pathlib.Path(__file__).resolve().parent.parent / "paper_2603_09215_amd" / "_build"
+    files = sorted(bdir.glob("*.resources.txt"))
+    if not files:
+        pytest.skip("the library was not built in this tree")
+    n = 0
+    for f in files:
+        for line in f.read_text().splitlines():
+            name, figures = line.split(" ", 1)
+            n += 1
+            assert "ScratchSize [bytes/lane]=0" in figures, name
+            assert "VGPRs Spill=0" in figures, name
+    assert n > 100      # every kernel of the library is listed
