@@ -277,6 +277,11 @@ int launch_gemv(spark_ctx *c, const Pro &pro, const Epi &epi, const RowDesc *row
   if (mt == 1 && sizeof(float) * align_up(n_in, 512) + 64 > budget &&
       sizeof(float) * align_up(n_in, 512) + 64 <= 81920)
     budget = 81920;
+  // the same for several rows that miss 64 KiB by a little (say four of 4096): a norm prologue
+  // then needs one pass over the weights instead of two, a plain one a single chunk
+  if (sizeof(float) * mt * align_up(n_in, 512) + 256 > budget &&
+      sizeof(float) * mt * align_up(n_in, 512) + 256 <= 81920)
+    budget = 81920;
   const size_t lds_budget = budget - sizeof(float) * (GEMV_BIG_THREADS / 64) * 4;
   while (mt > 1 && whole_row && sizeof(float) * mt * align_up(n_in, 512) > lds_budget) --mt;
   int kc_cap = (int)(lds_budget / (sizeof(float) * mt)) / 512 * 512;
