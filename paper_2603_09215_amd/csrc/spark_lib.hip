@@ -269,19 +269,13 @@ int launch_gemv(spark_ctx *c, const Pro &pro, const Epi &epi, const RowDesc *row
   if (m_rows <= 0) return SPARK_OK;
   // activation rows per pass over the weights: as many as fit in the LDS budget next to the
   // partial-sum words; a norm prologue needs the whole row resident.  The budget is 64 KiB, or
-  // 80 KiB when that lets a single row (e.g. the 18944-wide MLP activation) stay in one chunk:
-  // two such workgroups still fit in a CU's 160 KiB.
+  // 80 KiB for rows that do not fit in that (two such workgroups still fit in a CU's 160 KiB): a
+  // single row of the MLP width (18944) then stays in one chunk, four rows of 4096 under a norm
+  // prologue take one pass over the weights instead of two, and what has to be cut into chunks
+  // anyway is cut into fewer
   const bool whole_row = std::is_same<Pro, ProNorm>::value;
   int mt = std::min(4, m_rows);
-  size_t budget = 65536;
-  if (mt == 1 && sizeof(float) * align_up(n_in, 512) + 64 > budget &&
-      sizeof(float) * align_up(n_in, 512) + 64 <= 81920)
-    budget = 81920;
-  // the same for several rows that miss 64 KiB by a little (say four of 4096): a norm prologue
-  // then needs one pass over the weights instead of two, a plain one a single chunk
-  if (sizeof(float) * mt * align_up(n_in, 512) + 256 > budget &&
-      sizeof(float) * mt * align_up(n_in, 512) + 256 <= 81920)
-    budget = 81920;
+  const size_t budget = sizeof(float) * mt * align_up(n_in, 512) + 256 > 65536 ? 81920 : 65536;
   const size_t lds_budget = budget - sizeof(float) * (GEMV_BIG_THREADS / 64) * 4;
   while (mt > 1 && whole_row && sizeof(float) * mt * align_up(n_in, 512) > lds_budget) --mt;
   int kc_cap = (int)(lds_budget / (sizeof(float) * mt)) / 512 * 512;
