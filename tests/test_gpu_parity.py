@@ -291,6 +291,23 @@ def test_batched_decode_on_the_mfma_path(sb):
     sp.close()
 
 
+@pytest.mark.parametrize("B", [3, 4, 5])
+def test_row_counts_around_the_mfma_threshold(sb, B):
+    """bf16 sequences with the same cycle offset: every pass of the lower layers has exactly B rows
+    (three and four: one pass of the vector kernel; five: the MFMA projections), the flushes B to
+    4B rows; head size 128, so attention runs on its MFMA kernel throughout"""
+    shape = wl.TINY.shape.replace(name="bf16-rows", dtype=wl.DTYPE_BF16, n_layers=4, d_model=512,
+                                  n_q_heads=4, n_kv_heads=2, head_dim=128, d_ffn=1024 + 40,
+                                  vocab_text=900, vocab_speech=301)
+    sched = wl.TINY.schedule
+    say(f"case {B} rows per pass")
+    weights = wl.make_weights(shape, seed=8, gain_std=0.1)
+    prompts = [wl.make_prompt(shape, 5 + 9 * i, seed=60 + i) for i in range(B)]
+    sp = sb.Spark(shape, sched, weights, max_batch=B, max_seq_len=128, kv_page_tokens=64)
+    compare_run(sp, shape, sched, weights, prompts, [0] * B, 13, check_kv_every=6, label=f"rows {B} bf16")
+    sp.close()
+
+
 def test_text_ends_before_the_speech(sb, tiny_weights):
     """Sec. IV-A: after a sequence's text budget every position is speech.  Per-chunk and stream
     counters, several sequences with different budgets and cycle offsets in one batch, multi-step
