@@ -291,7 +291,7 @@ def test_batched_decode_on_the_mfma_path(sb):
     sp.close()
 
 
-@pytest.mark.parametrize("B", [3, 4, 5])
+@pytest.mark.parametrize("B", [3, 4, 5, 7, 8])
 def test_row_counts_around_the_mfma_threshold(sb, B):
     """bf16 sequences with the same cycle offset: every pass of the lower layers has exactly B rows
     (three and four: one pass of the vector kernel; five: the MFMA projections), the flushes B to
