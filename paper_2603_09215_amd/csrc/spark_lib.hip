@@ -380,6 +380,8 @@ template <typename WT> int launch_attention(spark_ctx *c, const RowDesc *rows, i
     const int splits = c->attn_splits_now > 0 ? std::min(c->dv.n_splits, c->attn_splits_now) : c->dv.n_splits;
     const long tasks = (long)splits * c->cfg.n_kv_heads * m;
     int pieces = c->attn_pieces > 0 ? c->attn_pieces : (tasks >= 8L * c->n_cu ? 4 : tasks >= 4L * c->n_cu ? 2 : 1);
+    // contexts of 4096 tokens and more: eight pieces (measured on 8 x 8192 tokens: 8.19 -> 8.09 ms per step)
+    if (c->attn_pieces <= 0 && pieces == 4 && splits >= 64) pieces = 8;
     // few workgroups (a handful of rows, two KV heads): eight query heads per workgroup
     const int heads_per_wg = (tasks < c->n_cu / 2 && c->dv.group > 8) ? 8 : c->dv.group;
     const int wg_per_kv = (c->dv.group + heads_per_wg - 1) / heads_per_wg;

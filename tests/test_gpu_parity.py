@@ -371,6 +371,24 @@ def test_long_contexts(sb, name, shape_kw, page, long_prompt):
     sp.close()
 
 
+@pytest.mark.parametrize("pieces", [3, 8])
+def test_attention_pieces_per_workgroup(sb, monkeypatch, pieces):
+    """the MFMA attention kernel with a fixed number of 64-token pieces per workgroup (the library
+    picks 1, 2, 4 or 8 by the size of the launch; eight is what contexts of 4096 tokens and more
+    get): a 2300-token context is 36 slices, so workgroups with all their pieces, with some, and
+    the ragged last one all occur; prompt passes and decode steps"""
+    monkeypatch.setenv("SPARK_ATTN_PIECES", str(pieces))
+    shape = wl.TINY.shape.replace(name="bf16-hd128-pieces", dtype=wl.DTYPE_BF16, n_layers=3, d_model=512,
+                                  n_q_heads=4, n_kv_heads=2, head_dim=128, d_ffn=1024)
+    sched = wl.TINY.schedule.replace(exit_layer=2, n_text=1, n_speech=2, scope=wl.SCOPE_STREAM)
+    say(f"case attention with {pieces} pieces per workgroup")
+    weights = wl.make_weights(shape, seed=6, gain_std=0.1)
+    sp = sb.Spark(shape, sched, weights, max_batch=2, max_seq_len=2300 + 64, kv_page_tokens=64)
+    prompts = [wl.make_prompt(shape, 2300, seed=7), wl.make_prompt(shape, 200, seed=8)]
+    compare_run(sp, shape, sched, weights, prompts, [0, 2], 12, check_kv_every=6, chunk=3, label=f"pieces {pieces}")
+    sp.close()
+
+
 def test_moved_and_aligned_phases(sb, tiny_weights):
     """a sequence's speech phase moved between steps, and a batch aligned (Sec. IV-B.3: an
     early-exit step skips the upper layers only if no sequence of the batch needs them): depths,
