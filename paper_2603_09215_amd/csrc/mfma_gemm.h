@@ -367,11 +367,12 @@ mfma_finish_tile_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, int n_
   {
     const int ml = threadIdx.x & 31, tl = threadIdx.x >> 5, task = min(task0 + tl, n_tasks - 1);
     float y0 = 0.f, y1 = 0.f;
-    for (int s = 0; s < n_split; ++s) {
-      const float *p = part + (((size_t)s * n_tasks + task) * 2) * m_pad + row0 + ml;
-      y0 += p[0];
-      y1 += p[m_pad];
-    }
+    if (row0 + ml < m_pad)
+      for (int s = 0; s < n_split; ++s) {
+        const float *p = part + (((size_t)s * n_tasks + task) * 2) * m_pad + row0 + ml;
+        y0 += p[0];
+        y1 += p[m_pad];
+      }
     s_y[0][tl][ml] = y0;
     s_y[1][tl][ml] = y1;
   }

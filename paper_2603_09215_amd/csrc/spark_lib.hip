@@ -522,7 +522,9 @@ int launch_mfma_shape(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, 
   const int z = (m + mrows - 1) / mrows;
   const int bx = (n_tasks + TASKS_PER_BLOCK - 1) / TASKS_PER_BLOCK;
   const int n_chunks = (n_in + MG_KC - 1) / MG_KC;
-  const int m_pad = (int)align_up(m, 32);
+  // rows of the partial sums: padded to eight only (a pass of eight rows then writes and reads a
+  // quarter of what 32 padded rows would)
+  const int m_pad = (int)align_up(m, 8);
   // resident workgroups on the chip: the k range is split until one round of them has work
   int occ = mfma_occupancy<MTILES, Epi, true, WAVES>(c);
   if (occ < 0) return occ;
@@ -558,7 +560,7 @@ int launch_mfma_shape(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, 
     const int tpt = finish_tasks_per_thread(epi);
     const int total = ((n_tasks + tpt - 1) / tpt) * m_pad;
     if (tpt == 1)   // epilogues without a running state: stores coalesced over tasks
-      mfma_finish_tile_k<Epi><<<dim3((n_tasks + 31) / 32, m_pad / 32), 1024, 0, c->stream>>>(epi, rows, m, n_tasks, split,
+      mfma_finish_tile_k<Epi><<<dim3((n_tasks + 31) / 32, (m_pad + 31) / 32), 1024, 0, c->stream>>>(epi, rows, m, n_tasks, split,
                                                                                               part, m_pad);
     else
       mfma_finish_k<Epi><<<(total + 255) / 256, 256, 0, c->stream>>>(epi, rows, m, n_tasks, split, part, m_pad, tpt);
