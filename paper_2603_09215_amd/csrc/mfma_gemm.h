@@ -325,6 +325,24 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
   }
 }
 
+// The partial sums of one (task, row) over the k ranges, added in the order of the ranges; the
+// loads of eight ranges are issued before the first is used (a loop that loads and adds pays a
+// round trip per range, and a projection with few tiles has up to 32 of them).
+__device__ __forceinline__ void sum_splits(const float *__restrict__ part, int n_split, int n_tasks, int task,
+                                           int m_pad, int m, float &y0, float &y1) {
+  const size_t stride = (size_t)n_tasks * 2 * m_pad;
+  const float *p = part + ((size_t)task * 2) * m_pad + m;
+  int s = 0;
+  for (; s + 8 <= n_split; s += 8) {
+    float a[8], b[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { a[i] = p[(s + i) * stride]; b[i] = p[(s + i) * stride + m_pad]; }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { y0 += a[i]; y1 += b[i]; }
+  }
+  for (; s < n_split; ++s) { y0 += p[s * stride]; y1 += p[s * stride + m_pad]; }
+}
+
 // sums the k-split partials and runs the epilogue: one thread per activation row and group of
 // `tasks_per_thread` consecutive tasks (more than one where the epilogue keeps a running state,
 // like the arg-max of the vocabulary heads, that is worth reducing before it goes to memory)
@@ -342,11 +360,7 @@ mfma_finish_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, int n_tasks
   const RowDesc rd = rows[m];
   for (int task = t_begin; task < t_end; ++task) {
     float y0 = 0.f, y1 = 0.f;
-    for (int s = 0; s < n_split; ++s) {
-      const float *p = part + (((size_t)s * n_tasks + task) * 2) * m_pad + m;
-      y0 += p[0];
-      y1 += p[m_pad];
-    }
+    sum_splits(part, n_split, n_tasks, task, m_pad, m, y0, y1);
     epi.finish(task, m, rd, y0, y1, st);
   }
   epi.end(m, rd, st);
@@ -367,12 +381,7 @@ mfma_finish_tile_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, int n_
   {
     const int ml = threadIdx.x & 31, tl = threadIdx.x >> 5, task = min(task0 + tl, n_tasks - 1);
     float y0 = 0.f, y1 = 0.f;
-    if (row0 + ml < m_pad)
-      for (int s = 0; s < n_split; ++s) {
-        const float *p = part + (((size_t)s * n_tasks + task) * 2) * m_pad + row0 + ml;
-        y0 += p[0];
-        y1 += p[m_pad];
-      }
+    if (row0 + ml < m_pad) sum_splits(part, n_split, n_tasks, task, m_pad, row0 + ml, y0, y1);
     s_y[0][tl][ml] = y0;
     s_y[1][tl][ml] = y1;
   }
