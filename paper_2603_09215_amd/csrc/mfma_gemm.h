@@ -67,6 +67,47 @@ prep_rows_k(const RowDesc *__restrict__ rows, const float *__restrict__ src, int
   __shared__ float red[4];
   const int r = blockIdx.x;
   const float *row = src + (size_t)(indirect ? rows[r].x_slot : r) * stride;
+  if (gamma && n <= 4096) {
+    // the row and the gains in registers: every load is issued before the first is used (one
+    // memory round trip instead of one per loop trip of two passes)
+    constexpr int NI = 4;
+    float4 v[NI], g[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int k = threadIdx.x * 4 + i * 1024;
+      v[i] = *(const float4 *)(row + (k < n ? k : 0));
+      g[i] = *(const float4 *)(gamma + (k < n ? k : 0));
+    }
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+      if (threadIdx.x * 4 + i * 1024 < n) ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float inv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)n + eps);
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int k = threadIdx.x * 4 + i * 1024;
+      if (k < n) {
+        const float f[4] = {v[i].x * inv * g[i].x, v[i].y * inv * g[i].y, v[i].z * inv * g[i].z, v[i].w * inv * g[i].w};
+        bf16_t h[4], mid[4], l[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) split3_bf16(f[e], h[e], mid[e], l[e]);
+        bf16_t *dst = xs + (size_t)r * n_pad + k;
+        *(uint2 *)dst = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
+        *(uint2 *)(dst + part_stride) = make_uint2(mid[0] | ((uint32_t)mid[1] << 16), mid[2] | ((uint32_t)mid[3] << 16));
+        *(uint2 *)(dst + 2 * part_stride) = make_uint2(l[0] | ((uint32_t)l[1] << 16), l[2] | ((uint32_t)l[3] << 16));
+      }
+    }
+    for (int k = n + threadIdx.x * 4; k < n_pad; k += 1024) {
+      bf16_t *dst = xs + (size_t)r * n_pad + k;
+      *(uint2 *)dst = make_uint2(0, 0);
+      *(uint2 *)(dst + part_stride) = make_uint2(0, 0);
+      *(uint2 *)(dst + 2 * part_stride) = make_uint2(0, 0);
+    }
+    return;
+  }
   float inv = 1.0f;
   if (gamma) {
     float ss = 0.f;
