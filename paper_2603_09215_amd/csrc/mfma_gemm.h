@@ -399,10 +399,29 @@ mfma_finish_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, int n_tasks
   typename Epi::State st;
   epi.init(st);
   const RowDesc rd = rows[m];
-  for (int task = t_begin; task < t_end; ++task) {
-    float y0 = 0.f, y1 = 0.f;
-    sum_splits(part, n_split, n_tasks, task, m_pad, m, y0, y1);
-    epi.finish(task, m, rd, y0, y1, st);
+  // eight tasks at a time: the loads of their partial sums of one k range are issued together
+  // (a thread that takes its tasks one by one pays a round trip per task and range); every task's
+  // ranges are still added in their order
+  constexpr int G = 8;
+  const size_t stride = (size_t)n_tasks * 2 * m_pad;
+  for (int task = t_begin; task < t_end; task += G) {
+    float y0[G], y1[G];
+#pragma unroll
+    for (int i = 0; i < G; ++i) y0[i] = y1[i] = 0.f;
+    for (int s = 0; s < n_split; ++s) {
+      float a[G], b[G];
+#pragma unroll
+      for (int i = 0; i < G; ++i) {
+        const float *p = part + s * stride + ((size_t)min(task + i, t_end - 1) * 2) * m_pad + m;
+        a[i] = p[0];
+        b[i] = p[m_pad];
+      }
+#pragma unroll
+      for (int i = 0; i < G; ++i) { y0[i] += a[i]; y1[i] += b[i]; }
+    }
+#pragma unroll
+    for (int i = 0; i < G; ++i)
+      if (task + i < t_end) epi.finish(task + i, m, rd, y0[i], y1[i], st);
   }
   epi.end(m, rd, st);
 }
