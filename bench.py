@@ -54,6 +54,52 @@ def step_bytes(shape, sched, ctx_len: float):
     return ee, full, w_layer
 
 
+def short_leg(Spark, torch, name, dev_w, batch, aligned, steps, warmup, prompt_len=None):
+    """a short decode of another benchmark configuration, so that its rate is part of the same
+    record: `steps` timed steps after `warmup`, inputs resident, same conventions as the headline"""
+    w = wl.WORKLOADS[name]
+    shape, sched = w.shape, w.schedule
+    if batch > 1:
+        plens = [int(x) for x in wl.make_prompt_lengths(batch, 256, 2048, seed=3)]
+    else:
+        plens = [prompt_len or w.prompt_len]
+    max_seq = min(16384, (max(plens) + warmup + steps + 64 + 63) // 64 * 64)
+    sp = Spark(shape, sched, dev_w, max_batch=batch, max_seq_len=max_seq, kv_page_tokens=64, device="cuda:0")
+    cyc = sched.n_text + sched.n_speech
+    sids = [sp.seq_open(i % cyc if batch > 1 and not aligned else 0) for i in range(batch)]
+    t0 = time.perf_counter()
+    for i, (s_, n) in enumerate(zip(sids, plens)):
+        sp.prefill(s_, wl.make_prompt(shape, n, seed=1 + i, ids=w.prompt_ids))
+    torch.cuda.synchronize()
+    prefill_s = time.perf_counter() - t0
+    sp.decode(warmup, sids)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    tok, dep = sp.decode(steps, sids)
+    torch.cuda.synchronize()
+    el = time.perf_counter() - t1
+    esz = 2 if shape.dtype == wl.DTYPE_BF16 else 4
+    ctx = float(np.mean(plens)) + warmup + steps / 2
+    ee_b, full_b, w_layer = step_bytes(shape, sched, ctx)
+    head_b = shape.vocab * shape.d_model * esz
+    any_full = int((dep == shape.n_layers).any(axis=1).sum())
+    any_ee = int((dep != shape.n_layers).any(axis=1).sum())
+    kv_b = (sched.exit_layer * steps + (shape.n_layers - sched.exit_layer) * any_full) * \
+        sum(plens) * 2 * shape.n_kv_heads * shape.head_dim * esz / steps
+    avg_bytes = (steps * sched.exit_layer * w_layer + any_full * ((shape.n_layers - sched.exit_layer) * w_layer + head_b)
+                 + any_ee * (head_b + shape.d_model ** 2 * esz)) / steps + kv_b
+    out = {"workload": f"{name}, batch {batch}, prompts {plens[0] if batch == 1 else '256..2048'}, "
+                       f"{'aligned' if aligned and batch > 1 else 'mixed' if batch > 1 else 'single'} cycle offsets, "
+                       f"e={sched.exit_layer}, K={sched.period_k}",
+           "steps": steps, "warmup": warmup, "tokens_per_s": round(steps * batch / el, 1),
+           "ms_per_step": round(el * 1e3 / steps, 4), "prefill_tokens_per_s": round(sum(n - 1 for n in plens) / prefill_s, 1),
+           "steps_with_a_full_depth_row": any_full, "steps_with_an_early_exit_row": any_ee,
+           "algorithmic_GB_per_step": round(avg_bytes / 1e9, 3),
+           "frac_of_hbm_peak": round(avg_bytes / (el / steps) / 1e9 / HBM_PEAK_GBS, 4)}
+    sp.close()
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -61,7 +107,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=36)
     ap.add_argument("--workload", default="step_audio_2_mini", choices=sorted(wl.WORKLOADS))
     ap.add_argument("--prompt-len", type=int, default=None)
-    ap.add_argument("--cpu-steps", type=int, default=12, help="oracle steps timed for cpu_baseline (0 = skip)")
+    ap.add_argument("--cpu-steps", type=int, default=16, help="oracle steps timed for cpu_baseline (0 = skip)")
+    ap.add_argument("--other-configs", type=int, default=1,
+                    help="1 (default, headline workload only): after the headline measurement also time short legs "
+                         "of the GLM-4-Voice shape at batch 1 and of batch 32 at the Step-Audio-2-mini shape "
+                         "(mixed and aligned cycle offsets); 0 = skip")
     ap.add_argument("--profile-steps", type=int, default=48)
     ap.add_argument("--batch", type=int, default=1,
                     help="sequences decoded together (default 1: the headline workload); >1 gives "
@@ -201,20 +251,33 @@ def main() -> int:
     sp.profile_select("gateup")
     if args.profile_steps > 0:
         sp.decode(args.profile_steps, sids)
-    n_launch, tot_ms = sp.profile_read()
+    n_launch, tot_ms, empty_ms = sp.profile_read()
     sp.profile_select(-1)
+    # the launch duration is the whole event bracket (it includes the bracket's own cost, about a
+    # microsecond, so the figure errs low); the bracket net of an empty one is reported beside it
     avg_ms = tot_ms / max(1, n_launch)
+    net_ms = (tot_ms - empty_ms) / max(1, n_launch)
     achieved = gateup_bytes / (avg_ms * 1e-3) / 1e9 if n_launch else 0.0
+    # what a plain streaming read gets on this device, next to the published peak: all gate
+    # matrices of the model (several GB, far beyond the last-level cache), non-temporal loads
+    ceiling_nt, _ = sp.measure_read(sp.dev_weights["wg"], reps=4, nontemporal=True)
+    ceiling_plain, _ = sp.measure_read(sp.dev_weights["wg"], reps=4, nontemporal=False)
     roofline = {"bound": "hbm", "kernel": "gemv_rows_k<gate/up + SwiGLU>", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": measured_traffic(shape), "bytes_per_launch": gateup_bytes, "avg_launch_ms": round(avg_ms, 5),
-                "launches_timed": int(n_launch)}
+                "traffic": measured_traffic(shape),
+                "traffic_source": "profiles/ (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs), not this run",
+                "bytes_per_launch": gateup_bytes, "avg_launch_ms": round(avg_ms, 5),
+                "avg_launch_ms_net_of_an_empty_bracket": round(net_ms, 5),
+                "launches_timed": int(n_launch),
+                "measured_read_ceiling_GBps": round(ceiling_nt, 1),
+                "measured_read_ceiling_plain_loads_GBps": round(ceiling_plain, 1),
+                "frac_of_measured_ceiling": round(achieved / max(ceiling_nt, 1e-9), 4)}
 
     sampler = None
     if sampled and args.profile_steps > 0:
         sp.profile_select("sample")
         decode(args.profile_steps, 0)
-        n_s, ms_s = sp.profile_read()
+        n_s, ms_s, _ = sp.profile_read()
         sp.profile_select(-1)
         sampler = {"temperature": args.temperature, "top_p": args.top_p,
                    "avg_launch_ms": round(ms_s / max(1, n_s), 5), "launches_timed": int(n_s)}
@@ -242,9 +305,9 @@ def main() -> int:
     if args.cpu_steps > 0:
         from oracle import binding as ob
         host_w = wl.device_weights_to_host(sp.dev_weights)
-        om = ob.Model(shape, sched, host_w, max_seq_len=64)
+        om = ob.Model(shape, sched, host_w, max_seq_len=64 + args.cpu_steps)
         osq = om.open(0)
-        osq.prefill(prompt[:4])
+        osq.prefill(prompt[:32])
         c0 = time.perf_counter()
         for _ in range(args.cpu_steps):
             rc, *_ = osq.step(want_logits=False)
@@ -252,7 +315,7 @@ def main() -> int:
         cpu_s = time.perf_counter() - c0
         cpu = {"value": round(args.cpu_steps / cpu_s, 4), "unit": "tokens/s", "cores": ob.num_threads(),
                "kind": "oracle",
-               "sample": f"{args.cpu_steps} decode steps after a 4-token prompt, same shape, weights and schedule"}
+               "sample": f"{args.cpu_steps} decode steps after a 32-token prompt, same shape, weights and schedule"}
         osq.close(); om.close()
 
     if "ee" in classes and "full" in classes:
@@ -282,8 +345,20 @@ def main() -> int:
     }
     if sampler:
         line["sampler"] = sampler
-    print(json.dumps(line), flush=True)
     sp.close()
+    # ---- the other benchmark configurations, short legs (outside the headline's timed region)
+    default_run = (args.workload == "step_audio_2_mini" and B == 1 and not sampled and args.exit_layer is None
+                   and args.period is None and args.text_period is None and not args.speech_share)
+    if args.other_configs and default_run:
+        others = {}
+        others["batch32_mixed"] = short_leg(Spark, torch, "step_audio_2_mini", dev_w, 32, False, 48, 16)
+        others["batch32_aligned"] = short_leg(Spark, torch, "step_audio_2_mini", dev_w, 32, True, 48, 16)
+        del dev_w
+        torch.cuda.empty_cache()
+        glm_w = wl.make_weights_on_device(wl.WORKLOADS["glm_4_voice"].shape, seed=0, device="cuda:0")
+        others["glm_4_voice_batch1"] = short_leg(Spark, torch, "glm_4_voice", glm_w, 1, False, 78, 39)
+        line["other_configs"] = others
+    print(json.dumps(line), flush=True)
     return 0
 
 

@@ -114,6 +114,10 @@ typedef struct spark_ctx spark_ctx;
 
 /* Sizes of the two device buffers the caller must provide for this configuration: the paged KV
  * pool (every sequence at max_seq_len) and the scratch area (activations, schedule state, logits).
+ * What has to be kept follows from Sec. IV-B.3: the KV cache of all L layers for every position,
+ * and the hidden states h^(e) of the early-exited positions until the next full-depth step; on
+ * memory management itself the paper is silent.  cfg [host]; the two sizes are written to
+ * kv_pool_bytes / scratch_bytes [host] (either may be NULL).
  * Returns SPARK_EINVAL for a configuration the library refuses. */
 int spark_workspace_bytes(const spark_config *cfg, size_t *kv_pool_bytes, size_t *scratch_bytes);
 
@@ -124,15 +128,23 @@ int spark_workspace_bytes(const spark_config *cfg, size_t *kv_pool_bytes, size_t
 int spark_schedule_preview(const spark_config *cfg, int32_t cycle_offset, int32_t text_budget,
                            int32_t n_steps, int32_t *depth_out, int32_t *is_text_out);
 
-/* Create a context.  kv_pool and scratch [device] must be at least the sizes reported above and
- * 256-byte aligned; hip_stream is a hipStream_t (NULL = the default stream) on which every kernel
- * of this context is launched.  The weights struct is copied; the tensors are not. */
+/* Create a context: the inputs of Algorithm 1 -- a model with L layers (Sec. III), the exit layer
+ * l_EE with its layer-specific head (Sec. IV-B.2), the period K and phase of the schedule
+ * (Sec. IV-B.1) and the interleave ratio N_text : N_speech (Sec. III).  cfg, weights [host];
+ * kv_pool and scratch [device] must be at least the sizes reported above and 256-byte aligned and
+ * stay the caller's (they must outlive the context; their contents need not be cleared);
+ * hip_stream is a hipStream_t (NULL = the default stream) on which every kernel of this context is
+ * launched.  The weights struct is copied; the tensors are not.  *out [host] receives the context,
+ * to be released with spark_destroy.  SPARK_EINVAL: refused configuration or a NULL tensor;
+ * SPARK_ENOMEM: a buffer is NULL, too small or misaligned; SPARK_EHIP: a runtime call failed. */
 int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_pool,
                size_t kv_pool_bytes, void *scratch, size_t scratch_bytes, void *hip_stream,
                spark_ctx **out);
 
-/* Open a sequence.  cycle_offset >= 0 is the slot of the interleave cycle at which the first
- * generated token falls (0 = first text slot).  Writes the id to *seq_id. */
+/* Open a sequence: one response of the interleaved generation of Sec. III.  cycle_offset >= 0 is
+ * the slot of the N_text + N_speech interleave cycle at which the first generated token falls
+ * (0 = first text slot); where a response enters the cycle the paper does not say.  Writes the id
+ * (0 .. max_batch-1) to *seq_id [host].  SPARK_ENOSEQ: all max_batch slots are open. */
 int spark_seq_open(spark_ctx *ctx, int32_t cycle_offset, int32_t *seq_id);
 
 /* The text of an interleaved response ends before its speech does (Sec. IV-A: speech tokens are
@@ -156,9 +168,13 @@ int spark_seq_text_budget(spark_ctx *ctx, int32_t seq_id, int32_t n_text_tokens)
 int spark_seq_set_phase(spark_ctx *ctx, int32_t seq_id, int32_t phase);
 int spark_align_phases(spark_ctx *ctx, int32_t n, const int32_t *seq_ids);
 
-/* Condition on a prompt [host] of n >= 1 ids: positions 0..n-2 are run at full depth and fill
- * the KV of every layer; the last id is held as the input of the first spark_step, so that every
- * generated token comes out of spark_step with its executed depth.  One prompt per sequence. */
+/* Condition on a prompt [host] of n >= 1 ids (Sec. III: generation is conditioned on the input;
+ * on how the prompt is processed the paper is silent): positions 0..n-2 are run at full depth and
+ * fill the KV of every layer, which is the state every full-depth step restores (end of
+ * Sec. IV-B.3); the last id is held as the input of the first spark_step, so that every generated
+ * token comes out of spark_step with its executed depth.  One prompt per sequence (SPARK_ESTATE on
+ * a second); SPARK_EINVAL: empty prompt or an id outside the vocabulary; SPARK_ENOMEM: longer
+ * than max_seq_len or no KV pages left.  Returns when the prompt pass has completed. */
 int spark_prefill(spark_ctx *ctx, int32_t seq_id, const int32_t *prompt, int32_t n);
 
 /* One decoding step for n distinct prefilled sequences seq_ids[0..n) [host] (Algorithm 1).
@@ -194,8 +210,9 @@ int spark_decode_sampled(spark_ctx *ctx, int32_t n_steps, int32_t n, const int32
                          const int32_t *forced_next, const uint64_t *rand_words,
                          int32_t *out_tokens, int32_t *out_depth);
 
-/* Logits [host, V floats] of the head that decoded the sequence's latest position, and which head
- * it was (*head = e or L). */
+/* Logits [host, V floats] of the head that decoded the sequence's latest position -- g_L of Eq. 1
+ * or the layer-specific g_e of Eq. 2 -- and which head it was (*head = e or L; may be NULL).
+ * SPARK_ESTATE: the sequence has not been stepped or was not in the latest step. */
 int spark_get_logits(spark_ctx *ctx, int32_t seq_id, float *out_logits, int32_t *head);
 
 /* Copy one position's cached key and value vectors (n_kv_heads*head_dim floats each) of one layer
@@ -203,16 +220,22 @@ int spark_get_logits(spark_ctx *ctx, int32_t seq_id, float *out_logits, int32_t 
 int spark_get_kv(spark_ctx *ctx, int32_t seq_id, int32_t layer, int32_t pos, float *k_out,
                  float *v_out);
 
-/* Current context length, number of positions whose upper-layer KV is complete, and number of
- * pending early-exited positions of a sequence (any pointer may be NULL). */
+/* Current context length, number of positions whose upper-layer KV (layers e+1..L) is complete,
+ * and number of pending early-exited positions of a sequence: the bookkeeping of Sec. IV-B.3
+ * (after every full-depth step the cache is complete, len == upper_valid).  All [host]; any
+ * pointer may be NULL. */
 int spark_seq_state(spark_ctx *ctx, int32_t seq_id, int32_t *len, int32_t *upper_valid,
                     int32_t *n_pending);
 
+/* The exit-layer log of a sequence so far (Sec. V-A "Metrics", Eq. 4); out [host]. */
 int spark_get_stats(spark_ctx *ctx, int32_t seq_id, spark_stats *out);
 
-/* Release a sequence and its KV pages. */
+/* Release a sequence and its KV pages (the paper is silent on the lifetime of a response); waits
+ * for the context's stream. */
 int spark_seq_close(spark_ctx *ctx, int32_t seq_id);
 
+/* Wait for the context's stream and release the context (its host memory and staging buffers;
+ * the caller's device buffers are untouched).  NULL is ignored. */
 void spark_destroy(spark_ctx *ctx);
 
 /* Text of the last error of this context (never NULL; valid until the next call on ctx). */
@@ -221,8 +244,9 @@ const char *spark_last_error(const spark_ctx *ctx);
 /* Measurement support.  While `kernel_class` is >= 0, every launch of that class of kernel during
  * spark_step / spark_decode is bracketed by HIP events on the context's stream;
  * spark_profile_read waits for them and reports the number of bracketed launches and their summed
- * duration in milliseconds since the last read, net of the cost of an empty bracket (measured
- * with a third event behind every bracket).  Classes: see SPARK_KC_*.  -1 switches it off. */
+ * duration in milliseconds since the last read (total_ms), and in empty_ms [nullable] the summed
+ * duration of as many empty brackets (a third event behind every bracket measures it), i.e. what
+ * the event mechanism itself adds to total_ms.  Classes: see SPARK_KC_*.  -1 switches it off. */
 #define SPARK_KC_QKV 0
 #define SPARK_KC_ATTN 1
 #define SPARK_KC_OPROJ 2
@@ -230,11 +254,29 @@ const char *spark_last_error(const spark_ctx *ctx);
 #define SPARK_KC_DOWN 4
 #define SPARK_KC_LENS 5
 #define SPARK_KC_HEAD 6
-#define SPARK_KC_PASS 7   /* the persistent kernel that runs a whole run of layers in one launch */
+/* 7 is unused */
 #define SPARK_KC_SAMPLE 8 /* the temperature / nucleus sampler */
 #define SPARK_KC_COUNT 9
 int spark_profile_select(spark_ctx *ctx, int32_t kernel_class);
-int spark_profile_read(spark_ctx *ctx, int64_t *n_launches, double *total_ms);
+int spark_profile_read(spark_ctx *ctx, int64_t *n_launches, double *total_ms, double *empty_ms);
+
+/* Measurement support: what the memory system delivers to the simplest possible reader, to be
+ * quoted next to the published peak.  Reads buf [device, 16-byte aligned, bytes a multiple of 16]
+ * `reps` times with a plain grid-stride kernel of 16-byte loads (nontemporal != 0: with the
+ * non-temporal hint the weight-streaming kernels use) on the context's stream, bracketed by HIP
+ * events after one untimed pass, and writes the rate in GB/s (10^9 bytes) to *gbps [host] and the
+ * XOR of all 32-bit words of buf to *checksum [host, may be NULL].  buf should be larger than the
+ * last-level cache (256 MB) for the figure to be a memory figure. */
+int spark_measure_read(spark_ctx *ctx, const void *buf, size_t bytes, int32_t reps, int32_t nontemporal,
+                       double *gbps, uint32_t *checksum);
+
+/* Kernel-selection switches of one context, for tests and sweeps; the defaults are the measured
+ * choices and nothing in the results depends on them beyond rounding order.  name [host]:
+ *   "mfma" (0: every row count stays on the vector kernels), "mfma_min_rows" (rows from which the
+ *   projections run on the MFMA units), "mfma_small_tiles", "mfma_xcd_max_split",
+ *   "attn_pieces" (64-token pieces per attention workgroup, 0 = by the size of the launch, at most
+ *   8), "attn_mfma_min_rows", "gemv_big_kb".  SPARK_EINVAL for an unknown name. */
+int spark_tune(spark_ctx *ctx, const char *name, int32_t value);
 
 #ifdef __cplusplus
 }

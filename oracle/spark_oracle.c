@@ -301,10 +301,13 @@ static void attn_out_row(ora_seq *s, int l, const real *q, int pos, real *h, rea
   const ora_config *c = &m->c;
   int d = c->d_model, hd = c->head_dim, nq = c->n_q_heads, nkv = c->n_kv_heads;
   int group = nq / nkv, kvw = nkv * hd;
+  /* the query heads are independent of each other: one thread each, with its own score buffer
+   * (score_buf holds max_seq_len entries per thread); the arithmetic of a head is unchanged */
+#pragma omp parallel for schedule(static)
   for (int hq = 0; hq < nq; ++hq) {
     int hk = hq / group; /* grouped-query attention: consecutive query heads share a kv head */
-    attend_head(q + hq * hd, s->K[l], s->V[l], kvw, hk * hd, hd, pos + 1, score_buf,
-                a_buf + hq * hd);
+    attend_head(q + hq * hd, s->K[l], s->V[l], kvw, hk * hd, hd, pos + 1,
+                score_buf + (size_t)omp_get_thread_num() * c->max_seq_len, a_buf + hq * hd);
   }
   matvec(m->w.wo, lofs(m, l, d, (size_t)nq * hd), c->dtype, d, nq * hd, a_buf, o_buf);
   for (int i = 0; i < d; ++i) h[i] += o_buf[i];
@@ -335,7 +338,7 @@ static int tmp_alloc(const ora_config *c, int rows, ora_tmp *t) {
   t->o = malloc(sizeof(real) * d);
   t->g = malloc(sizeof(real) * c->d_ffn);
   t->u = malloc(sizeof(real) * c->d_ffn);
-  t->scores = malloc(sizeof(real) * c->max_seq_len);
+  t->scores = malloc(sizeof(real) * (size_t)c->max_seq_len * (size_t)omp_get_max_threads());
   t->logits = malloc(sizeof(real) * (size_t)(c->vocab_text + c->vocab_speech));
   t->t = malloc(sizeof(real) * d);
   return (t->n && t->q && t->a && t->o && t->g && t->u && t->scores && t->logits && t->t) ? 0 : -1;

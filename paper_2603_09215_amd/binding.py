@@ -15,8 +15,7 @@ HERE = pathlib.Path(__file__).resolve().parent
 LIB_PATH = HERE / "libspark.so"
 
 SPARK_MAX_PERIOD = 16
-KC = {"qkv": 0, "attn": 1, "oproj": 2, "gateup": 3, "down": 4, "lens": 5, "head": 6, "pass": 7,
-      "sample": 8}
+KC = {"qkv": 0, "attn": 1, "oproj": 2, "gateup": 3, "down": 4, "lens": 5, "head": 6, "sample": 8}
 
 ERRORS = {-1: "SPARK_EINVAL", -2: "SPARK_ENOSEQ", -3: "SPARK_ENOMEM", -4: "SPARK_ESTATE",
           -5: "SPARK_EHIP", -6: "SPARK_ENAN"}
@@ -25,7 +24,8 @@ EXPORTS = ("spark_workspace_bytes", "spark_init", "spark_seq_open", "spark_prefi
            "spark_decode", "spark_get_logits", "spark_get_kv", "spark_seq_state",
            "spark_get_stats", "spark_seq_close", "spark_destroy", "spark_last_error",
            "spark_profile_select", "spark_profile_read", "spark_set_sampling", "spark_decode_sampled",
-           "spark_seq_text_budget", "spark_schedule_preview", "spark_seq_set_phase", "spark_align_phases")
+           "spark_seq_text_budget", "spark_schedule_preview", "spark_seq_set_phase", "spark_align_phases",
+           "spark_tune", "spark_measure_read")
 
 
 class SparkConfig(C.Structure):
@@ -75,6 +75,8 @@ def load_library() -> C.CDLL:
                                           C.POINTER(C.c_size_t)]
     lib.spark_init.argtypes = [C.POINTER(SparkConfig), C.POINTER(SparkWeights), P, C.c_size_t, P,
                                C.c_size_t, P, C.POINTER(P)]
+    lib.spark_tune.argtypes = [P, C.c_char_p, I]
+    lib.spark_measure_read.argtypes = [P, P, C.c_size_t, I, I, C.POINTER(C.c_double), C.POINTER(C.c_uint32)]
     lib.spark_seq_open.argtypes = [P, I, C.POINTER(I)]
     lib.spark_prefill.argtypes = [P, I, P, I]
     lib.spark_step.argtypes = [P, I, P, P, P, P]
@@ -95,7 +97,7 @@ def load_library() -> C.CDLL:
     lib.spark_last_error.argtypes = [P]
     lib.spark_last_error.restype = C.c_char_p
     lib.spark_profile_select.argtypes = [P, I]
-    lib.spark_profile_read.argtypes = [P, C.POINTER(C.c_int64), C.POINTER(C.c_double)]
+    lib.spark_profile_read.argtypes = [P, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]
     _lib = lib
     return lib
 
@@ -162,10 +164,11 @@ class Spark:
         torch.cuda.set_device(device)
         self.dev_weights = weights_to_device(weights, device)
         self.kv_pool = torch.empty(max(kv_b.value, 256), dtype=torch.uint8, device=device)
-        self.scratch = torch.empty(max(sc_b.value, 256), dtype=torch.uint8, device=device)
+        self.scratch_bytes = sc_b.value
         self.stream = stream if stream is not None else torch.cuda.current_stream()
         w = SparkWeights(*[self.dev_weights[n].data_ptr() for n in WEIGHT_FIELDS])
         torch.cuda.synchronize()
+        self.scratch = torch.empty(max(sc_b.value, 256), dtype=torch.uint8, device=device)
         rc = self.lib.spark_init(C.byref(self.cfg), C.byref(w), self.kv_pool.data_ptr(),
                                  kv_b.value, self.scratch.data_ptr(), sc_b.value,
                                  C.c_void_p(self.stream.cuda_stream), C.byref(self.handle))
@@ -284,6 +287,18 @@ class Spark:
         self._check(self.lib.spark_profile_select(self.handle, k))
 
     def profile_read(self):
-        n, ms = C.c_int64(), C.c_double()
-        self._check(self.lib.spark_profile_read(self.handle, C.byref(n), C.byref(ms)))
-        return n.value, ms.value
+        """(bracketed launches, their summed duration in ms, summed duration of as many empty brackets)"""
+        n, ms, empty = C.c_int64(), C.c_double(), C.c_double()
+        self._check(self.lib.spark_profile_read(self.handle, C.byref(n), C.byref(ms), C.byref(empty)))
+        return n.value, ms.value, empty.value
+
+    def tune(self, name: str, value: int) -> None:
+        self._check(self.lib.spark_tune(self.handle, name.encode(), int(value)))
+
+    def measure_read(self, tensor, reps: int = 8, nontemporal: bool = True):
+        """(GB/s, xor checksum) of a plain streaming read of a torch device tensor"""
+        gbps, chk = C.c_double(), C.c_uint32()
+        nbytes = tensor.numel() * tensor.element_size() // 16 * 16
+        self._check(self.lib.spark_measure_read(self.handle, C.c_void_p(tensor.data_ptr()), nbytes, reps,
+                                                int(nontemporal), C.byref(gbps), C.byref(chk)))
+        return gbps.value, chk.value

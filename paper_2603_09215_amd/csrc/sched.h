@@ -12,8 +12,8 @@ namespace spark {
 // device-resident per-sequence state, 10 ints
 enum { ST_LEN = 0, ST_G, ST_JSTREAM, ST_NPENDING, ST_OFFSET, ST_NEXT, ST_ACTIVE, ST_LASTFULL, ST_TEXTBUDGET, ST_PHASE, ST_WORDS };
 // plan words
-enum { PL_NLOWER = 0, PL_NUPPER, PL_NEE, PL_NFULL, PL_ERR, PL_BARRIER_ERR, PL_WORDS = 8 };
-enum { ERR_NAN = 1, ERR_INACTIVE = 2, ERR_BARRIER = 4 };
+enum { PL_NLOWER = 0, PL_NUPPER, PL_NEE, PL_NFULL, PL_ERR, PL_WORDS = 8 };
+enum { ERR_NAN = 1, ERR_INACTIVE = 2 };
 
 struct SchedParams {
   int n_layers, exit_layer, period_k, phase, scope, n_text, n_speech;

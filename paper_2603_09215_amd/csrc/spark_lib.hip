@@ -10,14 +10,16 @@
 #include <cstring>
 #include <type_traits>
 #include <map>
+#include <new>
+#include <string>
 #include <vector>
 
 #include "../../include/spark.h"
 #include "attention.h"
 #include "device_common.h"
 #include "gemv.h"
+#include "measure.h"
 #include "mfma_gemm.h"
-#include "pass_launch.h"
 #include "sampling.h"
 #include "sched.h"
 
@@ -36,7 +38,7 @@ constexpr int MAX_SEQ_LEN = 16384;
 
 struct Layout {  // byte offsets into the scratch buffer
   size_t state, page_table, plan, lower, upper, ee, full, prefill_rows, prefill_tokens, seq_ids,
-      forced, step_flags, out_tokens, out_depth, best, arrivals, barrier, sample_hist, sample_arrive, sample_count, hidden, xsplit, xsplit2, mfma_part, sample_q, sample_cand, rand_words, qbuf, attn_out, part, act, lens_u,
+      forced, step_flags, out_tokens, out_depth, best, arrivals, sample_hist, sample_arrive, sample_count, hidden, xsplit, xsplit2, mfma_part, sample_q, sample_cand, rand_words, qbuf, attn_out, part, act, lens_u,
       logits, rope, inv_freq, total;
 };
 
@@ -72,17 +74,15 @@ struct spark_ctx {
   int *h_in;   // pinned: seq_ids[max_batch] + forced[MAX_STEPS][max_batch]
   int *h_out;  // pinned: tokens[MAX_STEPS][max_batch] + depth[...] + plan[PL_WORDS]
   char err[512];
-  // persistent layer-pass kernel
-  bool use_pass_kernel = false;
-  bool use_mfma = true;        // SPARK_NO_MFMA=1 keeps every row count on the vector kernels
-  unsigned bar_round = 0;      // grid barriers passed since the barrier words were zeroed
-  unsigned long long *timeline_dev = nullptr;  // debugging aid, see SPARK_PASS_TIMELINE
-  int mfma_xcd_max_split = 4;   // SPARK_MFMA_XCD_MAX_SPLIT: row tiles share an XCD when k has at most this many ranges
-  int mfma_small_tiles = 32;   // launches with fewer 8-wave tiles use 4-wave workgroups (SPARK_MFMA_SMALL_TILES)
-  int mfma_min_rows = MFMA_MIN_ROWS;   // SPARK_MFMA_MIN_ROWS
-  int attn_pieces = 0;   // SPARK_ATTN_PIECES: 64-token pieces per attention workgroup (0: by the launch's size)
-  int gemv_big_kb = 40;         // SPARK_GEMV_BIG_KB: vector-kernel launches with more LDS per workgroup run eight waves per workgroup
-  int attn_mfma_min_rows = 1;   // passes with at least this many rows run attention on the MFMA units (where the shape allows)
+  // kernel selection; the defaults are the measured choices, spark_tune moves them (tests, sweeps)
+  bool mfma_ok = true;         // the shape allows the MFMA projections (16-byte vectors of 8 weights)
+  bool use_mfma = true;        // "mfma" = 0 keeps every row count on the vector kernels
+  int mfma_xcd_max_split = 4;  // row tiles share an XCD when k has at most this many ranges
+  int mfma_small_tiles = 32;   // launches with fewer 8-wave tiles use 4-wave workgroups
+  int mfma_min_rows = MFMA_MIN_ROWS;
+  int attn_pieces = 0;         // 64-token pieces per attention workgroup (0: by the launch's size)
+  int gemv_big_kb = 40;        // vector-kernel launches with more LDS per workgroup run eight waves per workgroup
+  int attn_mfma_min_rows = 1;  // passes with at least this many rows run attention on the MFMA units (where the shape allows)
   float temperature = 0.f, top_p = 0.f;   // nucleus sampling, off while temperature <= 0
   int prefill_chunk = 128;   // prompt rows per pass, see spark_init
   int attn_splits_now = 0;   // context slices the rows of the passes being enqueued can reach (0: unknown, launch all)
@@ -210,7 +210,6 @@ void layout(const spark_config &c, const Derived &d, Layout &l) {
   l.out_depth = take(sizeof(int) * (size_t)MAX_STEPS_PER_CALL * c.max_batch);
   l.best = take(sizeof(unsigned long long) * c.max_batch);
   l.arrivals = take(sizeof(int) * (size_t)d.max_rows * c.n_q_heads);   // per (row, group of query heads)
-  l.barrier = take(sizeof(unsigned) * (8 * 32 + 32));
   l.sample_hist = take(sizeof(unsigned long long) * (size_t)SAMPLE_BINS * c.max_batch);   // zero between launches
   l.sample_arrive = take(sizeof(unsigned) * c.max_batch);
   l.sample_count = take(sizeof(unsigned) * c.max_batch);
@@ -396,85 +395,6 @@ template <typename WT> int launch_attention(spark_ctx *c, const RowDesc *rows, i
   return prof_end(c, SPARK_KC_ATTN);
 }
 
-// ------------------------------------------------------------------ persistent layer pass
-
-constexpr size_t PASS_LDS_BUDGET = 128 * 1024;
-
-typedef hipError_t (*pass_launcher_bf16)(const PassParams<bf16_t> &, int, int, size_t, size_t, hipStream_t);
-typedef hipError_t (*pass_launcher_f32)(const PassParams<float> &, int, int, size_t, size_t, hipStream_t);
-
-// Shapes the persistent kernel is built for; others take the kernel-per-operation path.
-pass_launcher_bf16 pick_pass(bf16_t, int hd, int group) {
-  if (hd == 128 && group == 7) return launch_pass_bf16_128_7;
-  if (hd == 128 && group == 16) return launch_pass_bf16_128_16;
-  if (hd == 64 && group == 2) return launch_pass_bf16_64_2;
-  return nullptr;
-}
-pass_launcher_f32 pick_pass(float, int hd, int group) {
-  if (hd == 64 && group == 2) return launch_pass_f32_64_2;
-  return nullptr;
-}
-
-template <typename WT> bool pass_supported(int hd, int group) { return pick_pass(WT(), hd, group) != nullptr; }
-
-template <typename WT> int launch_pass(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
-  const spark_config &g = c->cfg;
-  const Derived &dv = c->dv;
-  const int hd = g.head_dim, qw = g.n_q_heads * hd, mt = m;
-  // LDS: the larger of the attention workspace (at most 16 heads of 128) and mt
-  // activation rows of one chunk
-  const size_t attn_bytes = sizeof(float) * attn_lds_floats<128, 16, PASS_THREADS>();
-  auto chunk = [&](int n_in) {
-    int cap = (int)(PASS_LDS_BUDGET / (sizeof(float) * mt)) / 512 * 512;
-    return std::min((int)align_up(n_in, 512), cap);
-  };
-  PassParams<WT> p;
-  p.kc_d = chunk(g.d_model); p.kc_q = chunk(qw); p.kc_f = chunk(g.d_ffn);
-  if (p.kc_d < g.d_model) return fail(c, SPARK_EINVAL, "row of %d does not fit in LDS", g.d_model);
-  const int most_tasks = std::max(std::max((g.n_q_heads + 2 * g.n_kv_heads) * (hd / 2), g.d_model / 2), g.d_ffn);
-  if ((most_tasks + c->n_cu * PASS_WAVES - 1) / (c->n_cu * PASS_WAVES) > PASS_MAX_ROUNDS)
-    return fail(c, SPARK_EINVAL, "%d weight-row pairs are more than the pass kernel holds results for", most_tasks);
-  size_t lds = sizeof(float) * mt * (size_t)std::max(p.kc_d, std::max(p.kc_q, p.kc_f));
-  lds = std::max(lds, attn_bytes);
-  p.d = g.d_model; p.nq = g.n_q_heads; p.nkv = g.n_kv_heads; p.hd = hd; p.F = g.d_ffn;
-  p.eps = g.rms_eps;
-  p.wq = (const WT *)c->w.wq; p.wk = (const WT *)c->w.wk; p.wv = (const WT *)c->w.wv;
-  p.wo = (const WT *)c->w.wo; p.wg = (const WT *)c->w.wg; p.wu = (const WT *)c->w.wu;
-  p.wd = (const WT *)c->w.wd;
-  p.attn_norm = c->w.attn_norm; p.mlp_norm = c->w.mlp_norm;
-  p.l0 = l0; p.l1 = l1; p.rows = rows; p.m_rows = m;
-  p.hidden = at<float>(c, c->lo.hidden); p.qbuf = at<float>(c, c->lo.qbuf);
-  p.attn_out = at<float>(c, c->lo.attn_out); p.act = at<float>(c, c->lo.act);
-  p.part = at<float>(c, c->lo.part); p.arrivals = at<int>(c, c->lo.arrivals);
-  p.rope = at<float2>(c, c->lo.rope); p.kv = kv_view(c);
-  p.n_splits = dv.n_splits; p.scale = 1.0f / sqrtf((float)hd);
-  unsigned *bw = at<unsigned>(c, c->lo.barrier);
-  p.gb = GridBarrier{bw, bw + 8 * 32, (unsigned *)(at<int>(c, c->lo.plan) + PL_BARRIER_ERR)};
-  p.round_base = c->bar_round;
-  p.timeline = c->timeline_dev;
-  int rc = prof_begin(c, SPARK_KC_PASS);
-  if (rc) return rc;
-  HIP_TRY(c, pick_pass(WT(), hd, dv.group)(p, mt, c->n_cu, lds, PASS_LDS_BUDGET, c->stream));
-  c->bar_round += 5u * (unsigned)(l1 - l0) - 1u;
-  if (c->timeline_dev) {  // debugging aid: print the phase times of this launch
-    // marks of workgroup 0 per layer: before and after the barrier that ends each of the five
-    // phases (q/k/v, attention, o, gate/up, down)
-    const int nl = l1 - l0;
-    std::vector<unsigned long long> t(1 + 10 * nl);
-    HIP_TRY(c, hipStreamSynchronize(c->stream));
-    HIP_TRY(c, hipMemcpy(t.data(), c->timeline_dev, t.size() * 8, hipMemcpyDeviceToHost));
-    double seg[10] = {0};
-    for (int l = 0; l < nl; ++l)
-      for (int k = 0; k < 10; ++k)
-        if (l * 10 + k + 1 < 10 * nl) seg[k] += (double)(t[1 + l * 10 + k] - t[l * 10 + k]) * 0.01;
-    fprintf(stderr, "[pass m=%d layers %d..%d] us/layer work+wait  qkv %.1f+%.1f  attn %.1f+%.1f  o %.1f+%.1f  "
-            "gateup %.1f+%.1f  down %.1f+%.1f  total %.1f\n", m, l0, l1, seg[0] / nl, seg[1] / nl,
-            seg[2] / nl, seg[3] / nl, seg[4] / nl, seg[5] / nl, seg[6] / nl, seg[7] / nl, seg[8] / nl,
-            seg[9] / nl, (double)(t[10 * nl - 1] - t[0]) * 0.01 / nl);
-  }
-  return prof_end(c, SPARK_KC_PASS);
-}
-
 // ------------------------------------------------------------------ MFMA path (16..128+ rows, bf16)
 
 
@@ -641,12 +561,9 @@ int run_layers_mfma(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
 
 // layers [l0, l1) on m rows described by `rows` (device)
 template <typename WT>
-int run_layers(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m, bool one_sequence = false) {
+int run_layers(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
   const spark_config &g = c->cfg;
   if (l0 >= l1 || m <= 0) return SPARK_OK;
-  // up to four consecutive positions of one sequence: the whole run of layers is one launch
-  if (one_sequence && m <= 4 && c->use_pass_kernel && pass_supported<WT>(g.head_dim, c->dv.group))
-    return launch_pass<WT>(c, l0, l1, rows, m);
   // many rows: the projections are dense contractions for the MFMA units
   if (std::is_same<WT, bf16_t>::value && m >= c->mfma_min_rows && c->use_mfma)
     return run_layers_mfma(c, l0, l1, rows, m);
@@ -777,10 +694,10 @@ int enqueue_step(spark_ctx *c, int n, int n_upper, int n_ee, int n_full, const i
   embed_rows_k<WT><<<n, 256, 0, c->stream>>>(lower, state, nullptr, (const WT *)c->w.embed,
                                              g.d_model, at<float>(c, c->lo.hidden));
   HIP_TRY(c, hipGetLastError());
-  if ((rc = run_layers<WT>(c, 0, g.exit_layer, lower, n, n == 1))) return rc;
+  if ((rc = run_layers<WT>(c, 0, g.exit_layer, lower, n))) return rc;
   if (n_ee && (rc = run_lens_head<WT>(c, ee, n_ee))) return rc;
   if (n_full) {
-    if ((rc = run_layers<WT>(c, g.exit_layer, g.n_layers, upper, n_upper, n == 1))) return rc;
+    if ((rc = run_layers<WT>(c, g.exit_layer, g.n_layers, upper, n_upper))) return rc;
     if ((rc = run_final_head<WT>(c, full, n_full))) return rc;
   }
   if (rand_dev && c->temperature > 0.f) {   // the drawn token takes the arg-max's place
@@ -819,6 +736,22 @@ int decode_chunk(spark_ctx *c, int steps, int n, const int32_t *seq_ids, const i
     if (forced)
       for (int st = 0; st < steps; ++st)
         if (forced[st * n + i] >= c->dv.V) return fail(c, SPARK_EINVAL, "forced id out of range");
+  }
+  // the schedule of the whole call, before anything is enqueued: the pending rows and the current
+  // row of a sequence must fit its slots of the hidden-state arena at every step
+  for (int i = 0; i < n; ++i) {
+    const Seq &sq = c->seqs[seq_ids[i]];
+    int gg = sq.g, jj = sq.j_stream, npend = sq.n_pending;
+    for (int st = 0; st < steps; ++st) {
+      int is_text, full;
+      schedule_decide(c->sp, gg, sq.cycle_offset, jj, sq.text_budget, sq.phase, is_text, full);
+      npend = full ? 0 : npend + 1;
+      if (npend + 1 > c->dv.rmax)
+        return fail(c, SPARK_ESTATE, "sequence %d would hold %d pending positions, its slots hold %d",
+                    seq_ids[i], npend, c->dv.rmax - 1);
+      ++gg;
+      if (!is_text) ++jj;
+    }
   }
   for (int i = 0; i < n; ++i)
     if ((rc = ensure_pages(c, seq_ids[i], c->seqs[seq_ids[i]].len + steps))) return rc;
@@ -910,16 +843,10 @@ int decode_chunk(spark_ctx *c, int steps, int n, const int32_t *seq_ids, const i
     Seq &s = c->seqs[seq_ids[i]];
     s.g = mir[i].g; s.j_stream = mir[i].j; s.n_pending = mir[i].npend; s.len = mir[i].len;
   }
-  if (h_plan[PL_BARRIER_ERR]) h_plan[PL_ERR] |= ERR_BARRIER;
   if (h_plan[PL_ERR]) {
     int e = h_plan[PL_ERR];
     int zero = 0;  // error path only: clear the flag so that the context stays usable
     (void)hipMemcpy(at<int>(c, c->lo.plan) + PL_ERR, &zero, sizeof(int), hipMemcpyHostToDevice);
-    (void)hipMemcpy(at<int>(c, c->lo.plan) + PL_BARRIER_ERR, &zero, sizeof(int), hipMemcpyHostToDevice);
-    if (e & ERR_BARRIER) {
-      c->use_pass_kernel = false;
-      return fail(c, SPARK_EHIP, "a grid barrier of the layer-pass kernel timed out");
-    }
     if (e & ERR_NAN) return fail(c, SPARK_ENAN, "a head produced a NaN logit");
     return fail(c, SPARK_ESTATE, "device saw an inactive sequence");
   }
@@ -982,16 +909,10 @@ int spark_schedule_preview(const spark_config *cfg, int32_t cycle_offset, int32_
   return SPARK_OK;
 }
 
-int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_pool,
-               size_t kv_pool_bytes, void *scratch, size_t scratch_bytes, void *hip_stream,
-               spark_ctx **out) {
-  if (!out) return SPARK_EINVAL;
-  *out = nullptr;
-  char why[128];
-  if (!cfg || !weights || !config_ok(cfg, why, sizeof(why))) return SPARK_EINVAL;
-  const void *const *wp = (const void *const *)weights;
-  for (size_t i = 0; i < sizeof(spark_weights) / sizeof(void *); ++i)
-    if (!wp[i]) return SPARK_EINVAL;
+namespace {
+
+int init_context(const spark_config *cfg, const spark_weights *weights, void *kv_pool, size_t kv_pool_bytes,
+                 void *scratch, size_t scratch_bytes, void *hip_stream, spark_ctx **out) {
   spark_ctx *c = new spark_ctx();
   c->cfg = *cfg;
   c->w = *weights;
@@ -1016,20 +937,9 @@ int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_p
   if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
     return bail(SPARK_EHIP);
   c->n_cu = prop.multiProcessorCount;
-  // The persistent layer-pass kernel is built and parity-tested but, as measured, not faster than
-  // one kernel per operation yet; it is used when SPARK_PASS_KERNEL=1.
-  const char *pass = getenv("SPARK_PASS_KERNEL");
-  c->use_pass_kernel = pass && pass[0] == '1';
-  if (const char *v = getenv("SPARK_ATTN_MFMA_MIN_ROWS")) c->attn_mfma_min_rows = std::max(1, atoi(v));
-  if (const char *v = getenv("SPARK_GEMV_BIG_KB")) c->gemv_big_kb = std::max(1, atoi(v));
-  if (const char *v = getenv("SPARK_ATTN_PIECES")) c->attn_pieces = std::max(0, std::min(8, atoi(v)));
-  if (const char *v = getenv("SPARK_MFMA_SMALL_TILES")) c->mfma_small_tiles = atoi(v);
-  if (const char *v = getenv("SPARK_MFMA_MIN_ROWS")) c->mfma_min_rows = std::max(1, atoi(v));
-  if (const char *v = getenv("SPARK_MFMA_XCD_MAX_SPLIT")) c->mfma_xcd_max_split = atoi(v);
-  const char *no_mfma = getenv("SPARK_NO_MFMA");
   // the MFMA kernels load 16-byte vectors of 8 weights; other widths stay on the vector kernel
-  c->use_mfma = !(no_mfma && no_mfma[0] == '1') && cfg->d_model % 8 == 0 &&
-                (cfg->n_q_heads * cfg->head_dim) % 8 == 0 && cfg->d_ffn % 8 == 0;
+  c->mfma_ok = cfg->d_model % 8 == 0 && (cfg->n_q_heads * cfg->head_dim) % 8 == 0 && cfg->d_ffn % 8 == 0;
+  c->use_mfma = c->mfma_ok;
   // Prompt rows per pass: on the MFMA path the widest projection (gate/up) is cut into tiles of 256
   // weight-row pairs x 64 prompt rows; the row count is chosen so that one round of tiles about
   // fills the chip, which needs no k split and no second kernel for that projection.
@@ -1037,16 +947,15 @@ int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_p
     const int x_tiles = (cfg->d_ffn + MG_TASKS_PER_BLOCK - 1) / MG_TASKS_PER_BLOCK;
     c->prefill_chunk = std::max(128, std::min(PREFILL_CHUNK, 64 * (c->n_cu / std::max(1, x_tiles))));
   }
-  const char *tl = getenv("SPARK_PASS_TIMELINE");   // debugging aid: per-phase times on stderr
-  if (tl && tl[0] == '1' &&
-      hipMalloc((void **)&c->timeline_dev, sizeof(unsigned long long) * 16384) != hipSuccess)
-    return bail(SPARK_EHIP);
   size_t in_ints = (size_t)cfg->max_batch * (1 + MAX_STEPS_PER_CALL);
   size_t out_ints = (size_t)cfg->max_batch * 2 * MAX_STEPS_PER_CALL + PL_WORDS;
   if (hipHostMalloc((void **)&c->h_in, sizeof(int) * in_ints, hipHostMallocDefault) != hipSuccess ||
       hipHostMalloc((void **)&c->h_out, sizeof(int) * out_ints, hipHostMallocDefault) != hipSuccess)
     return bail(SPARK_EHIP);
-  // device state, rotary table
+  // device state, rotary table.  Everything up to the hidden-state arena starts at zero: sequence
+  // state, page table, plan and error word, and the counters that kernels hand to the next launch
+  // at zero (attention arrivals, the sampler's histogram, arrivals and candidate counts).  The
+  // scratch area may hold another context's leftovers.
   if (hipMemsetAsync(c->scratch + c->lo.state, 0, c->lo.hidden - c->lo.state, c->stream) != hipSuccess)
     return bail(SPARK_EHIP);
   const int half = cfg->head_dim / 2;
@@ -1062,6 +971,40 @@ int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_p
   if (hipGetLastError() != hipSuccess || hipStreamSynchronize(c->stream) != hipSuccess)
     return bail(SPARK_EHIP);
   *out = c;
+  return SPARK_OK;
+}
+
+bool init_args_ok(const spark_config *cfg, const spark_weights *weights) {
+  char why[128];
+  if (!cfg || !weights || !config_ok(cfg, why, sizeof(why))) return false;
+  const void *const *wp = (const void *const *)weights;
+  for (size_t i = 0; i < sizeof(spark_weights) / sizeof(void *); ++i)
+    if (!wp[i]) return false;
+  return true;
+}
+
+}  // namespace
+
+int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_pool,
+               size_t kv_pool_bytes, void *scratch, size_t scratch_bytes, void *hip_stream,
+               spark_ctx **out) {
+  if (!out) return SPARK_EINVAL;
+  *out = nullptr;
+  if (!init_args_ok(cfg, weights)) return SPARK_EINVAL;
+  return init_context(cfg, weights, kv_pool, kv_pool_bytes, scratch, scratch_bytes, hip_stream, out);
+}
+
+int spark_tune(spark_ctx *c, const char *name, int32_t value) {
+  if (!c || !name) return SPARK_EINVAL;
+  const std::string k(name);
+  if (k == "mfma") c->use_mfma = value != 0 && c->mfma_ok;
+  else if (k == "mfma_min_rows") c->mfma_min_rows = std::max(1, (int)value);
+  else if (k == "mfma_small_tiles") c->mfma_small_tiles = value;
+  else if (k == "mfma_xcd_max_split") c->mfma_xcd_max_split = value;
+  else if (k == "attn_pieces") c->attn_pieces = std::max(0, std::min(8, (int)value));
+  else if (k == "attn_mfma_min_rows") c->attn_mfma_min_rows = std::max(1, (int)value);
+  else if (k == "gemv_big_kb") c->gemv_big_kb = std::max(1, (int)value);
+  else return fail(c, SPARK_EINVAL, "unknown tuning name '%s'", name);
   return SPARK_OK;
 }
 
@@ -1238,6 +1181,22 @@ int spark_seq_set_phase(spark_ctx *c, int32_t seq_id, int32_t phase) {
   // a moved phase can join two runs of early exits: K-1 before and K-1 after the move, which the
   // pending slots hold; runs that early-exited text positions could extend further are not allowed
   if (c->cfg.text_period_k > 1) return fail(c, SPARK_EINVAL, "the phase cannot be moved when text exits early too");
+  if (c->cfg.scope == SPARK_SCOPE_CHUNK && c->cfg.exit_layer < c->cfg.n_layers) {
+    // per-chunk counters repeat with the cycle: the moved phase needs a full-depth slot in it, and
+    // its runs of early exits, joined with the K-1 that may be pending from before the move, must
+    // fit the pending slots (the check spark_init makes for the configuration's own phase)
+    const int cyc = c->cfg.n_text + c->cfg.n_speech;
+    int run = 0, longest = 0;
+    bool any_full = false;
+    for (int g = 0; g < 2 * cyc; ++g) {
+      int is_text, full;
+      schedule_decide(c->sp, g, 0, 0, 0, phase, is_text, full);
+      if (full) { any_full = true; run = 0; } else { longest = std::max(longest, ++run); }
+    }
+    if (!any_full) return fail(c, SPARK_EINVAL, "with phase %d no slot of the cycle would run full depth", phase);
+    if (longest + c->cfg.period_k > pending_slots(&c->cfg))
+      return fail(c, SPARK_EINVAL, "with phase %d a run of early exits would outgrow the pending slots", phase);
+  }
   return set_phase(c, seq_id, s, phase);
 }
 
@@ -1312,7 +1271,6 @@ void spark_destroy(spark_ctx *c) {
   if (!c) return;
   (void)hipStreamSynchronize(c->stream);
   for (hipEvent_t ev : c->prof_ev) (void)hipEventDestroy(ev);
-  if (c->timeline_dev) (void)hipFree(c->timeline_dev);
   if (c->h_in) (void)hipHostFree(c->h_in);
   if (c->h_out) (void)hipHostFree(c->h_out);
   delete c;
@@ -1328,7 +1286,7 @@ int spark_profile_select(spark_ctx *c, int32_t kernel_class) {
   return SPARK_OK;
 }
 
-int spark_profile_read(spark_ctx *c, int64_t *n_launches, double *total_ms) {
+int spark_profile_read(spark_ctx *c, int64_t *n_launches, double *total_ms, double *empty_ms) {
   if (!c || !n_launches || !total_ms) return SPARK_EINVAL;
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   double tot = 0, empty = 0;
@@ -1339,10 +1297,50 @@ int spark_profile_read(spark_ctx *c, int64_t *n_launches, double *total_ms) {
     tot += ms;
     empty += ms0;
   }
-  tot -= empty;   // what the brackets themselves cost
   *n_launches = (int64_t)(c->prof_used / 3);
   *total_ms = tot;
+  if (empty_ms) *empty_ms = empty;   // what the brackets themselves cost
   c->prof_used = 0;
+  return SPARK_OK;
+}
+
+int spark_measure_read(spark_ctx *c, const void *buf, size_t bytes, int32_t reps, int32_t nontemporal,
+                       double *gbps, uint32_t *checksum) {
+  if (!c || !buf || !gbps || reps < 1) return SPARK_EINVAL;
+  if (bytes < 16 || bytes % 16 || ((uintptr_t)buf & 15)) return fail(c, SPARK_EINVAL, "buffer must be 16-byte aligned and sized");
+  // the wave sums go where the attention partials live between steps (at least 69 KB)
+  const int blocks = c->n_cu * 8, words = blocks * (READ_THREADS / 64);
+  const size_t part_bytes = c->lo.act - c->lo.part;
+  if (sizeof(unsigned) * words > part_bytes) return fail(c, SPARK_ENOMEM, "scratch too small for the read kernel's sums");
+  unsigned *sink = at<unsigned>(c, c->lo.part);
+  const read_u32x4 *p = (const read_u32x4 *)buf;
+  const size_t n16 = bytes / 16;
+  hipEvent_t e0, e1;
+  HIP_TRY(c, hipEventCreate(&e0));
+  HIP_TRY(c, hipEventCreate(&e1));
+  auto launch = [&]() {
+    if (nontemporal) read_stream_k<true><<<blocks, READ_THREADS, 0, c->stream>>>(p, n16, sink);
+    else read_stream_k<false><<<blocks, READ_THREADS, 0, c->stream>>>(p, n16, sink);
+  };
+  launch();   // untimed: code object, TLB
+  int rc = SPARK_OK;
+  float ms = 0.f;
+  if (hipEventRecord(e0, c->stream) != hipSuccess) rc = SPARK_EHIP;
+  for (int r = 0; r < reps && rc == SPARK_OK; ++r) launch();
+  if (rc == SPARK_OK && (hipGetLastError() != hipSuccess || hipEventRecord(e1, c->stream) != hipSuccess ||
+                         hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess))
+    rc = SPARK_EHIP;
+  if (rc == SPARK_OK && checksum) {
+    std::vector<unsigned> h(words);
+    if (hipMemcpy(h.data(), sink, sizeof(unsigned) * words, hipMemcpyDeviceToHost) != hipSuccess) rc = SPARK_EHIP;
+    unsigned x = 0;
+    for (unsigned v : h) x ^= v;
+    *checksum = x;
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (rc != SPARK_OK) return fail(c, rc, "the read measurement failed");
+  *gbps = (double)bytes * reps / ((double)ms * 1e-3) / 1e9;
   return SPARK_OK;
 }
 

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import workloads as wl
-from parity_util import compare_run, say
+from parity_util import compare_run, full_weights, say
 
 pytestmark = pytest.mark.gpu
 
@@ -53,21 +53,22 @@ def test_full_shape_short_run(name, n_steps, offset, n_prompt):
         pytest.skip("no GPU")
     from paper_2603_09215_amd import binding as sb
     w = wl.WORKLOADS[name]
-    say(f"case full shape {name}: drawing weights")
-    t0 = time.time()
-    dev_w = wl.make_weights_on_device(w.shape, seed=0)
-    host_w = wl.device_weights_to_host(dev_w)
-    say(f"  weights on device and host in {time.time() - t0:.1f}s")
+    say(f"case full shape {name}, prompt {n_prompt}")
+    dev_w, host_w = full_weights(name)
     sp = sb.Spark(w.shape, w.schedule, dev_w, max_batch=1, max_seq_len=n_prompt + 96, kv_page_tokens=64)
     prompt = wl.make_prompt(w.shape, n_prompt, seed=1, ids=w.prompt_ids)
     t0 = time.time()
     # Reference: the oracle's fp64 twin.  Its fp32 build sums 3584..18944-term dot products
     # sequentially, which leaves ~sqrt(n) * 2^-24 relative noise in K and V; re-rounding those to
-    # bf16 for the cache turns that noise into rounding flips that eat most of the 2e-2 budget
-    # (measured 0.018 / 0.022 on these two shapes), so the GPU's own error is measured against
-    # the twin whose noise is negligible.
+    # bf16 for the cache turns that noise into rounding flips that eat most of the 2e-2 budget,
+    # so the GPU's own error is measured against the twin whose noise is negligible.  The fp32
+    # build runs beside it for the first 12 steps of the 32-token cases and the three distances
+    # (GPU - fp64, GPU - fp32, fp32 - fp64) are logged; only the first is asserted.
+    # Every step that runs full depth also compares the cache entries of all layers at the
+    # last 2K + 1 positions: the deferred fill of layers e+1..L for the flushed rows.
     res = compare_run(sp, w.shape, w.schedule, host_w, [prompt], [offset], n_steps,
-                      check_kv_every=0, label=name, oracle_kind="f64")
+                      check_kv_every=1 if n_prompt == 32 else 0, label=f"{name}/prompt{n_prompt}",
+                      oracle_kind="f64", beside_f32_steps=12 if n_prompt == 32 else 0, trace_steps=True)
     say(f"  compared in {time.time() - t0:.1f}s")
     depths = res["depths"][:, 0]
     assert set(np.unique(depths)) <= {w.schedule.exit_layer, w.shape.n_layers}
@@ -78,8 +79,6 @@ def test_full_shape_short_run(name, n_steps, offset, n_prompt):
         # the sampler's candidate list holds, so its general path decides
         sampled_draws_match(sp, w, prompt, offset, n_steps=6, temperature=5.0, top_p=0.9)
     sp.close()
-    del dev_w, host_w
-    torch.cuda.empty_cache()
 
 
 def first_layer_cache_entries_match(sp, sid, w, dev_w, prompt, generated):
@@ -127,7 +126,7 @@ def test_bench_configuration_properties():
     from paper_2603_09215_amd import binding as sb
     w = wl.WORKLOADS["step_audio_2_mini"]
     say("case bench configuration")
-    dev_w = wl.make_weights_on_device(w.shape, seed=0)
+    dev_w, _ = full_weights("step_audio_2_mini")
     n = w.decode_len
     want_depth, want_text = ob.schedule_run(w.shape, w.schedule, n, 0)
     prompt = wl.make_prompt(w.shape, w.prompt_len, seed=1, ids=w.prompt_ids)
@@ -156,8 +155,6 @@ def test_bench_configuration_properties():
         runs.append(tok.copy())
         sp.close()
     assert np.array_equal(runs[0], runs[1])
-    del dev_w
-    torch.cuda.empty_cache()
 
 
 def test_batched_bench_configuration_properties():
@@ -171,7 +168,7 @@ def test_batched_bench_configuration_properties():
     from paper_2603_09215_amd import binding as sb
     w = wl.WORKLOADS["step_audio_2_mini"]
     say("case batched bench configuration")
-    dev_w = wl.make_weights_on_device(w.shape, seed=0)
+    dev_w, _ = full_weights("step_audio_2_mini")
     B, n = 12, 48
     cyc = w.schedule.n_text + w.schedule.n_speech
     plens = [int(x) for x in wl.make_prompt_lengths(B, 256, 2048, seed=3)]
@@ -191,5 +188,3 @@ def test_batched_bench_configuration_properties():
         runs.append(tok.copy())
         sp.close()
     assert np.array_equal(runs[0], runs[1])
-    del dev_w
-    torch.cuda.empty_cache()

@@ -227,29 +227,6 @@ def test_reopened_slot_reproduces_a_fresh_run(sb, tiny_weights):
     sp.close()
 
 
-def test_persistent_layer_pass_kernel(sb, tiny_weights, monkeypatch):
-    """the single-launch path (one persistent kernel per run of layers, grid barriers from
-    device-scope atomics) gives the same results; it is enabled per context by an environment
-    variable read at spark_init"""
-    monkeypatch.setenv("SPARK_PASS_KERNEL", "1")
-    w = wl.TINY
-    say("case pass kernel tiny")
-    sp = sb.Spark(w.shape, w.schedule, tiny_weights, max_batch=1, max_seq_len=128, kv_page_tokens=16)
-    compare_run(sp, w.shape, w.schedule, tiny_weights, [wl.make_prompt(w.shape, 16, seed=1)], [0], 64,
-                check_kv_every=4, label="pass tiny")
-    sp.close()
-    shape = wl.TINY.shape.replace(name="bf16-gqa7", dtype=wl.DTYPE_BF16, n_layers=6, d_model=896,
-                                  n_q_heads=7, n_kv_heads=1, head_dim=128, d_ffn=1712,
-                                  vocab_text=3001, vocab_speech=1000)
-    sched = wl.TINY.schedule.replace(exit_layer=4, n_text=1, n_speech=2, scope=wl.SCOPE_STREAM)
-    say("case pass kernel bf16-gqa7")
-    weights = wl.make_weights(shape, seed=3, gain_std=0.1)
-    sp = sb.Spark(shape, sched, weights, max_batch=1, max_seq_len=400, kv_page_tokens=32)
-    compare_run(sp, shape, sched, weights, [wl.make_prompt(shape, 300, seed=5)], [1], 24,
-                check_kv_every=4, label="pass bf16-gqa7")
-    sp.close()
-
-
 def test_text_schedule_with_long_flushes_on_a_bf16_model(sb):
     """text and speech both scheduled (Sec. V-C): runs of early exits cross the modality boundary,
     so one sequence completes up to six rows in a full-depth step; on a bf16 model four or more
@@ -372,18 +349,20 @@ def test_long_contexts(sb, name, shape_kw, page, long_prompt):
 
 
 @pytest.mark.parametrize("pieces", [3, 8])
-def test_attention_pieces_per_workgroup(sb, monkeypatch, pieces):
+def test_attention_pieces_per_workgroup(sb, pieces):
     """the MFMA attention kernel with a fixed number of 64-token pieces per workgroup (the library
     picks 1, 2, 4 or 8 by the size of the launch; eight is what contexts of 4096 tokens and more
     get): a 2300-token context is 36 slices, so workgroups with all their pieces, with some, and
     the ragged last one all occur; prompt passes and decode steps"""
-    monkeypatch.setenv("SPARK_ATTN_PIECES", str(pieces))
     shape = wl.TINY.shape.replace(name="bf16-hd128-pieces", dtype=wl.DTYPE_BF16, n_layers=3, d_model=512,
                                   n_q_heads=4, n_kv_heads=2, head_dim=128, d_ffn=1024)
     sched = wl.TINY.schedule.replace(exit_layer=2, n_text=1, n_speech=2, scope=wl.SCOPE_STREAM)
     say(f"case attention with {pieces} pieces per workgroup")
     weights = wl.make_weights(shape, seed=6, gain_std=0.1)
     sp = sb.Spark(shape, sched, weights, max_batch=2, max_seq_len=2300 + 64, kv_page_tokens=64)
+    sp.tune("attn_pieces", pieces)
+    with pytest.raises(sb.SparkError):
+        sp.tune("no_such_switch", 1)
     prompts = [wl.make_prompt(shape, 2300, seed=7), wl.make_prompt(shape, 200, seed=8)]
     compare_run(sp, shape, sched, weights, prompts, [0, 2], 12, check_kv_every=6, chunk=3, label=f"pieces {pieces}")
     sp.close()
