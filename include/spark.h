@@ -12,7 +12,8 @@
  * All compute runs in HIP kernels on the stream given to spark_init.  Pointers marked [device]
  * are device memory owned by the caller and must outlive the context; pointers marked [host] are
  * ordinary host memory.  Every call returns SPARK_OK or a negative SPARK_E* code; nothing throws
- * and there is no global state.  A context is not thread-safe.
+ * and the only state outside a context is the static scratch area of spark_init_static.  A context
+ * is not thread-safe.
  */
 #ifndef SPARK_H
 #define SPARK_H
@@ -39,6 +40,9 @@ extern "C" {
 #define SPARK_SCOPE_STREAM 1 /* period counter runs over all speech positions of the sequence */
 
 #define SPARK_MAX_PERIOD 16  /* largest supported K */
+
+/* size of the library's own scratch area, see spark_init_static */
+#define SPARK_STATIC_SCRATCH_BYTES (64u << 20)
 
 /* Model dimensions and schedule.  Plain data; `size` must be sizeof(spark_config). */
 typedef struct spark_config {
@@ -140,6 +144,20 @@ int spark_schedule_preview(const spark_config *cfg, int32_t cycle_offset, int32_
 int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_pool,
                size_t kv_pool_bytes, void *scratch, size_t scratch_bytes, void *hip_stream,
                spark_ctx **out);
+
+/* spark_init for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the scratch area is a static device array of
+ * SPARK_STATIC_SCRATCH_BYTES inside the library instead of a caller's buffer, and the staging
+ * buffers are ordinary host arrays; the call makes no hipMalloc / hipHostMalloc / hipFree.  The
+ * caller still passes the weights and the KV pool.  Configurations whose
+ * spark_workspace_bytes scratch size exceeds SPARK_STATIC_SCRATCH_BYTES are refused
+ * (SPARK_ENOMEM, with a message on stderr).  Each GPU has one such array: at most one context per
+ * device may live on it at a time (a second spark_init_static on the same device returns
+ * SPARK_ESTATE until the first is destroyed), the array keeps the previous context's contents
+ * (what must start at zero is cleared here), and calls on two contexts that share it would race.
+ * Everything else is spark_init. */
+int spark_init_static(const spark_config *cfg, const spark_weights *weights, void *kv_pool,
+                      size_t kv_pool_bytes, void *hip_stream, spark_ctx **out);
 
 /* Open a sequence: one response of the interleaved generation of Sec. III.  cycle_offset >= 0 is
  * the slot of the N_text + N_speech interleave cycle at which the first generated token falls

@@ -25,7 +25,7 @@ EXPORTS = ("spark_workspace_bytes", "spark_init", "spark_seq_open", "spark_prefi
            "spark_get_stats", "spark_seq_close", "spark_destroy", "spark_last_error",
            "spark_profile_select", "spark_profile_read", "spark_set_sampling", "spark_decode_sampled",
            "spark_seq_text_budget", "spark_schedule_preview", "spark_seq_set_phase", "spark_align_phases",
-           "spark_tune", "spark_measure_read")
+           "spark_init_static", "spark_tune", "spark_measure_read")
 
 
 class SparkConfig(C.Structure):
@@ -75,6 +75,8 @@ def load_library() -> C.CDLL:
                                           C.POINTER(C.c_size_t)]
     lib.spark_init.argtypes = [C.POINTER(SparkConfig), C.POINTER(SparkWeights), P, C.c_size_t, P,
                                C.c_size_t, P, C.POINTER(P)]
+    lib.spark_init_static.argtypes = [C.POINTER(SparkConfig), C.POINTER(SparkWeights), P, C.c_size_t, P,
+                                      C.POINTER(P)]
     lib.spark_tune.argtypes = [P, C.c_char_p, I]
     lib.spark_measure_read.argtypes = [P, P, C.c_size_t, I, I, C.POINTER(C.c_double), C.POINTER(C.c_uint32)]
     lib.spark_seq_open.argtypes = [P, I, C.POINTER(I)]
@@ -148,7 +150,7 @@ class Spark:
     """One decoding context on the current CUDA/HIP device."""
 
     def __init__(self, shape, sched, weights: dict, max_batch: int = 1, max_seq_len: int = 2048,
-                 kv_page_tokens: int = 64, device="cuda:0", stream=None):
+                 kv_page_tokens: int = 64, device="cuda:0", stream=None, static_scratch: bool = False):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("spark needs a GPU: no HIP device is visible")
@@ -168,13 +170,18 @@ class Spark:
         self.stream = stream if stream is not None else torch.cuda.current_stream()
         w = SparkWeights(*[self.dev_weights[n].data_ptr() for n in WEIGHT_FIELDS])
         torch.cuda.synchronize()
-        self.scratch = torch.empty(max(sc_b.value, 256), dtype=torch.uint8, device=device)
-        rc = self.lib.spark_init(C.byref(self.cfg), C.byref(w), self.kv_pool.data_ptr(),
-                                 kv_b.value, self.scratch.data_ptr(), sc_b.value,
-                                 C.c_void_p(self.stream.cuda_stream), C.byref(self.handle))
+        if static_scratch:   # spark_init_static: the library's own scratch area, nothing allocated
+            self.scratch = None
+            rc = self.lib.spark_init_static(C.byref(self.cfg), C.byref(w), self.kv_pool.data_ptr(), kv_b.value,
+                                            C.c_void_p(self.stream.cuda_stream), C.byref(self.handle))
+        else:
+            self.scratch = torch.empty(max(sc_b.value, 256), dtype=torch.uint8, device=device)
+            rc = self.lib.spark_init(C.byref(self.cfg), C.byref(w), self.kv_pool.data_ptr(),
+                                     kv_b.value, self.scratch.data_ptr(), sc_b.value,
+                                     C.c_void_p(self.stream.cuda_stream), C.byref(self.handle))
         if rc:
             self.handle = C.c_void_p()
-            raise SparkError(rc, "spark_init failed")
+            raise SparkError(rc, "spark_init_static failed" if static_scratch else "spark_init failed")
 
     # -- helpers
     def _check(self, rc: int):

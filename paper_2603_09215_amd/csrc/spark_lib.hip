@@ -83,6 +83,8 @@ struct spark_ctx {
   int attn_pieces = 0;         // 64-token pieces per attention workgroup (0: by the launch's size)
   int gemv_big_kb = 40;        // vector-kernel launches with more LDS per workgroup run eight waves per workgroup
   int attn_mfma_min_rows = 1;  // passes with at least this many rows run attention on the MFMA units (where the shape allows)
+  bool static_scratch = false; // the scratch area is the library's static device array (spark_init_static)
+  int device = 0;
   float temperature = 0.f, top_p = 0.f;   // nucleus sampling, off while temperature <= 0
   int prefill_chunk = 128;   // prompt rows per pass, see spark_init
   int attn_splits_now = 0;   // context slices the rows of the passes being enqueued can reach (0: unknown, launch all)
@@ -911,8 +913,10 @@ int spark_schedule_preview(const spark_config *cfg, int32_t cycle_offset, int32_
 
 namespace {
 
+// What spark_init and spark_init_static share.  `pinned`: the staging buffers for ids, forced tokens
+// and results are pinned host memory (hipHostMalloc); otherwise they are ordinary host arrays.
 int init_context(const spark_config *cfg, const spark_weights *weights, void *kv_pool, size_t kv_pool_bytes,
-                 void *scratch, size_t scratch_bytes, void *hip_stream, spark_ctx **out) {
+                 void *scratch, size_t scratch_bytes, void *hip_stream, bool static_scratch, spark_ctx **out) {
   spark_ctx *c = new spark_ctx();
   c->cfg = *cfg;
   c->w = *weights;
@@ -927,6 +931,7 @@ int init_context(const spark_config *cfg, const spark_weights *weights, void *kv
   c->stream = (hipStream_t)hip_stream;
   c->scratch = (char *)scratch;
   c->kv_pool = kv_pool;
+  c->static_scratch = static_scratch;
   c->sp = sched_params(cfg);
   c->seqs.resize(cfg->max_batch);
   for (int p = c->dv.n_pages_total - 1; p >= 0; --p) c->free_pages.push_back(p);
@@ -936,6 +941,7 @@ int init_context(const spark_config *cfg, const spark_weights *weights, void *kv
   hipDeviceProp_t prop;
   if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
     return bail(SPARK_EHIP);
+  c->device = dev;
   c->n_cu = prop.multiProcessorCount;
   // the MFMA kernels load 16-byte vectors of 8 weights; other widths stay on the vector kernel
   c->mfma_ok = cfg->d_model % 8 == 0 && (cfg->n_q_heads * cfg->head_dim) % 8 == 0 && cfg->d_ffn % 8 == 0;
@@ -949,13 +955,18 @@ int init_context(const spark_config *cfg, const spark_weights *weights, void *kv
   }
   size_t in_ints = (size_t)cfg->max_batch * (1 + MAX_STEPS_PER_CALL);
   size_t out_ints = (size_t)cfg->max_batch * 2 * MAX_STEPS_PER_CALL + PL_WORDS;
-  if (hipHostMalloc((void **)&c->h_in, sizeof(int) * in_ints, hipHostMallocDefault) != hipSuccess ||
-      hipHostMalloc((void **)&c->h_out, sizeof(int) * out_ints, hipHostMallocDefault) != hipSuccess)
+  if (static_scratch) {   // this variant allocates nothing through the HIP runtime
+    c->h_in = new (std::nothrow) int[in_ints];
+    c->h_out = new (std::nothrow) int[out_ints];
+    if (!c->h_in || !c->h_out) return bail(SPARK_ENOMEM);
+  } else if (hipHostMalloc((void **)&c->h_in, sizeof(int) * in_ints, hipHostMallocDefault) != hipSuccess ||
+             hipHostMalloc((void **)&c->h_out, sizeof(int) * out_ints, hipHostMallocDefault) != hipSuccess) {
     return bail(SPARK_EHIP);
+  }
   // device state, rotary table.  Everything up to the hidden-state arena starts at zero: sequence
   // state, page table, plan and error word, and the counters that kernels hand to the next launch
   // at zero (attention arrivals, the sampler's histogram, arrivals and candidate counts).  The
-  // scratch area may hold another context's leftovers.
+  // scratch area may hold another context's leftovers (the static array always does).
   if (hipMemsetAsync(c->scratch + c->lo.state, 0, c->lo.hidden - c->lo.state, c->stream) != hipSuccess)
     return bail(SPARK_EHIP);
   const int half = cfg->head_dim / 2;
@@ -985,13 +996,55 @@ bool init_args_ok(const spark_config *cfg, const spark_weights *weights) {
 
 }  // namespace
 
+// The scratch area of spark_init_static: one array per GPU the library is loaded on, held until the
+// process ends.  In host code the name `static_scratch_area` is a handle for hipGetSymbolAddress,
+// not an address: the per-device address is looked up once and kept in static_scratch_ptr.
+static __device__ __align__(256) unsigned char static_scratch_area[SPARK_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+char *static_scratch_ptr[MAX_DEVICES] = {nullptr};
+bool static_scratch_busy[MAX_DEVICES] = {false};
+}  // namespace
+
 int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_pool,
                size_t kv_pool_bytes, void *scratch, size_t scratch_bytes, void *hip_stream,
                spark_ctx **out) {
   if (!out) return SPARK_EINVAL;
   *out = nullptr;
   if (!init_args_ok(cfg, weights)) return SPARK_EINVAL;
-  return init_context(cfg, weights, kv_pool, kv_pool_bytes, scratch, scratch_bytes, hip_stream, out);
+  return init_context(cfg, weights, kv_pool, kv_pool_bytes, scratch, scratch_bytes, hip_stream, false, out);
+}
+
+int spark_init_static(const spark_config *cfg, const spark_weights *weights, void *kv_pool,
+                      size_t kv_pool_bytes, void *hip_stream, spark_ctx **out) {
+  if (!out) return SPARK_EINVAL;
+  *out = nullptr;
+  if (!init_args_ok(cfg, weights)) return SPARK_EINVAL;
+  Derived d;
+  Layout l;
+  derive(*cfg, d);
+  layout(*cfg, d, l);
+  if (l.total > (size_t)SPARK_STATIC_SCRATCH_BYTES) {
+    fprintf(stderr, "spark_init_static: this configuration needs %zu bytes of scratch, the static area holds %zu\n",
+            l.total, (size_t)SPARK_STATIC_SCRATCH_BYTES);
+    return SPARK_ENOMEM;
+  }
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return SPARK_EHIP;
+  if (static_scratch_busy[dev]) {
+    fprintf(stderr, "spark_init_static: device %d already has a live context on the static scratch area\n", dev);
+    return SPARK_ESTATE;
+  }
+  if (!static_scratch_ptr[dev]) {   // once per device, with that device current
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(static_scratch_area)) != hipSuccess || !p) return SPARK_EHIP;
+    static_scratch_ptr[dev] = (char *)p;
+  }
+  int rc = init_context(cfg, weights, kv_pool, kv_pool_bytes, static_scratch_ptr[dev],
+                        (size_t)SPARK_STATIC_SCRATCH_BYTES, hip_stream, true, out);
+  if (rc == SPARK_OK) static_scratch_busy[dev] = true;
+  return rc;
 }
 
 int spark_tune(spark_ctx *c, const char *name, int32_t value) {
@@ -1271,8 +1324,14 @@ void spark_destroy(spark_ctx *c) {
   if (!c) return;
   (void)hipStreamSynchronize(c->stream);
   for (hipEvent_t ev : c->prof_ev) (void)hipEventDestroy(ev);
-  if (c->h_in) (void)hipHostFree(c->h_in);
-  if (c->h_out) (void)hipHostFree(c->h_out);
+  if (c->static_scratch) {
+    delete[] c->h_in;
+    delete[] c->h_out;
+    if (c->device >= 0 && c->device < MAX_DEVICES) static_scratch_busy[c->device] = false;
+  } else {
+    if (c->h_in) (void)hipHostFree(c->h_in);
+    if (c->h_out) (void)hipHostFree(c->h_out);
+  }
   delete c;
 }
 
