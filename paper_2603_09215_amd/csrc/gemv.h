@@ -340,6 +340,14 @@ template <typename WT> struct EpiVocab {
   __device__ void end(int r, const RowDesc &rd, State &s) const {
     if (s.best) atomicMax(best + rd.out_idx, s.best);
   }
+  // the same in two steps, for a caller that first combines the states of several threads that
+  // serve one activation row in a word of LDS (zero = nothing yet)
+  __device__ void reduce_local(const State &s, unsigned long long *lds_word) const {
+    if (s.best) atomicMax(lds_word, s.best);
+  }
+  __device__ void end_reduced(const RowDesc &rd, unsigned long long key) const {
+    atomicMax(best + rd.out_idx, key);
+  }
 };
 
 // ------------------------------------------------------------------ the kernel

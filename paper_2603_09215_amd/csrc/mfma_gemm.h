@@ -385,45 +385,56 @@ __device__ __forceinline__ void sum_splits(const float *__restrict__ part, int n
 }
 
 // sums the k-split partials and runs the epilogue: one thread per activation row and group of
-// `tasks_per_thread` consecutive tasks (more than one where the epilogue keeps a running state,
-// like the arg-max of the vocabulary heads, that is worth reducing before it goes to memory)
+// `tasks_per_thread` consecutive tasks, for epilogues that keep a running state worth reducing
+// before it goes to memory (the arg-max of the vocabulary heads).  The running states of a
+// workgroup's threads that serve the same activation row are combined in LDS (64-bit maximum), so
+// that one atomic per row and workgroup reaches memory; with that the groups can be small (eight
+// tasks: every thread issues all loads of a k range at once and the launch has thousands of
+// waves; with 64 tasks per thread a head of 158 497 rows was 620 waves that each walked 32 dependent
+// round trips, 59 us).
 template <typename Epi>
 __global__ void __launch_bounds__(256)
 mfma_finish_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, int n_tasks, int n_split,
               const float *__restrict__ part, int m_pad, int tasks_per_thread) {
+  __shared__ unsigned long long s_best[256];   // per activation row of this workgroup (m_pad <= 256)
+  s_best[threadIdx.x] = 0ull;
+  __syncthreads();
   const int idx = blockIdx.x * 256 + threadIdx.x;
   const int group = idx / m_pad, m = idx - group * m_pad;
   const int t_begin = group * tasks_per_thread;
-  if (t_begin >= n_tasks || m >= m_rows) return;
-  const int t_end = min(n_tasks, t_begin + tasks_per_thread);
-  typename Epi::State st;
-  epi.init(st);
-  const RowDesc rd = rows[m];
-  // eight tasks at a time: the loads of their partial sums of one k range are issued together
-  // (a thread that takes its tasks one by one pays a round trip per task and range); every task's
-  // ranges are still added in their order
-  constexpr int G = 8;
-  const size_t stride = (size_t)n_tasks * 2 * m_pad;
-  for (int task = t_begin; task < t_end; task += G) {
-    float y0[G], y1[G];
+  if (t_begin < n_tasks && m < m_rows) {
+    const int t_end = min(n_tasks, t_begin + tasks_per_thread);
+    typename Epi::State st;
+    epi.init(st);
+    const RowDesc rd = rows[m];
+    // eight tasks at a time: the loads of their partial sums of one k range are issued together
+    // (a thread that takes its tasks one by one pays a round trip per task and range); every task's
+    // ranges are still added in their order
+    constexpr int G = 8;
+    const size_t stride = (size_t)n_tasks * 2 * m_pad;
+    for (int task = t_begin; task < t_end; task += G) {
+      float y0[G], y1[G];
 #pragma unroll
-    for (int i = 0; i < G; ++i) y0[i] = y1[i] = 0.f;
-    for (int s = 0; s < n_split; ++s) {
-      float a[G], b[G];
+      for (int i = 0; i < G; ++i) y0[i] = y1[i] = 0.f;
+      for (int s = 0; s < n_split; ++s) {
+        float a[G], b[G];
 #pragma unroll
-      for (int i = 0; i < G; ++i) {
-        const float *p = part + s * stride + ((size_t)min(task + i, t_end - 1) * 2) * m_pad + m;
-        a[i] = p[0];
-        b[i] = p[m_pad];
+        for (int i = 0; i < G; ++i) {
+          const float *p = part + s * stride + ((size_t)min(task + i, t_end - 1) * 2) * m_pad + m;
+          a[i] = p[0];
+          b[i] = p[m_pad];
+        }
+#pragma unroll
+        for (int i = 0; i < G; ++i) { y0[i] += a[i]; y1[i] += b[i]; }
       }
 #pragma unroll
-      for (int i = 0; i < G; ++i) { y0[i] += a[i]; y1[i] += b[i]; }
+      for (int i = 0; i < G; ++i)
+        if (task + i < t_end) epi.finish(task + i, m, rd, y0[i], y1[i], st);
     }
-#pragma unroll
-    for (int i = 0; i < G; ++i)
-      if (task + i < t_end) epi.finish(task + i, m, rd, y0[i], y1[i], st);
+    epi.reduce_local(st, s_best + m);
   }
-  epi.end(m, rd, st);
+  __syncthreads();
+  if ((int)threadIdx.x < m_rows && s_best[threadIdx.x]) epi.end_reduced(rows[threadIdx.x], s_best[threadIdx.x]);
 }
 
 // The same for epilogues without a running state, with the stores in mind: a workgroup of 1024

@@ -415,9 +415,10 @@ int launch_prep(spark_ctx *c, const RowDesc *rows, int m, const float *src, int 
   return SPARK_OK;
 }
 
-// tasks one thread of the finishing kernel takes: the vocabulary heads reduce their arg-max over 64
+// tasks one thread of the finishing kernel takes: the vocabulary heads reduce their arg-max over 8
+// per thread, then over the workgroup's threads of the same row
 template <typename Epi> int finish_tasks_per_thread(const Epi &) { return 1; }
-template <typename WT> int finish_tasks_per_thread(const EpiVocab<WT> &) { return 64; }
+template <typename WT> int finish_tasks_per_thread(const EpiVocab<WT> &) { return 8; }
 
 template <int MTILES, typename Epi, bool SPLIT, int WAVES>
 int mfma_occupancy(spark_ctx *c) {
@@ -479,13 +480,15 @@ int launch_mfma_shape(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, 
   if (split > 1) {
     mfma_rows_k<MTILES, Epi, true, WAVES><<<grid, 64 * WAVES, lds, c->stream>>>(
         epi, rows, m, xs, xst, n_in, n_tasks, cps, part, m_pad, bx, split, z, xcd_groups);
-    const int tpt = finish_tasks_per_thread(epi);
-    const int total = ((n_tasks + tpt - 1) / tpt) * m_pad;
-    if (tpt == 1)   // epilogues without a running state: stores coalesced over tasks
+    if constexpr (std::is_same<typename Epi::State, NoState>::value) {
+      // epilogues without a running state: stores coalesced over tasks
       mfma_finish_tile_k<Epi><<<dim3((n_tasks + 31) / 32, (m_pad + 31) / 32), 1024, 0, c->stream>>>(epi, rows, m, n_tasks, split,
                                                                                               part, m_pad);
-    else
+    } else {
+      const int tpt = finish_tasks_per_thread(epi);
+      const int total = ((n_tasks + tpt - 1) / tpt) * m_pad;
       mfma_finish_k<Epi><<<(total + 255) / 256, 256, 0, c->stream>>>(epi, rows, m, n_tasks, split, part, m_pad, tpt);
+    }
   } else {
     occ = mfma_occupancy<MTILES, Epi, false, WAVES>(c);
     if (occ < 0) return occ;

@@ -68,6 +68,8 @@ SCHEDULES = [
     dict(text_period_k=3, text_phase=0, period_k=4, phase=3, n_text=3, n_speech=4),
     dict(text_period_k=3, text_phase=0, period_k=2, phase=1, n_text=2, n_speech=3,
          scope=wl.SCOPE_STREAM),
+    # the largest supported period: fifteen pending positions and the current one in one pass
+    dict(period_k=16, phase=15, n_text=1, n_speech=20, scope=wl.SCOPE_STREAM, exit_layer=1),
 ]
 
 
@@ -419,3 +421,35 @@ def test_moved_and_aligned_phases(sb, tiny_weights):
     for os_ in oseqs:
         os_.close()
     om.close(); sp.close()
+
+
+def test_moved_phase_is_validated_and_pending_rows_cannot_outgrow_their_slots(sb, tiny_weights):
+    """per-chunk counters on a pure-speech cycle of three slots with K = 4: a phase of 3 would never
+    run full depth (refused, as spark_init refuses such a configuration); and a caller that keeps
+    moving the phase away from the slot about to run never completes the pending positions: the
+    step that would need a ninth hidden-state slot is refused before anything is enqueued, and the
+    sequence can go on once a full-depth step is allowed"""
+    w = wl.TINY
+    say("case moved phase validation")
+    sched = w.schedule.replace(scope=wl.SCOPE_CHUNK, n_text=0, n_speech=3, period_k=4, phase=0)
+    sp = sb.Spark(w.shape, sched, tiny_weights, max_batch=1, max_seq_len=64, kv_page_tokens=16)
+    sid = sp.seq_open(0)
+    sp.prefill(sid, wl.make_prompt(w.shape, 5, seed=1))
+    with pytest.raises(sb.SparkError) as ei:
+        sp.seq_set_phase(sid, 3)
+    assert ei.value.code == -1
+    depths = []
+    for g in range(7):                               # slot g % 3 runs next: keep the phase elsewhere
+        sp.seq_set_phase(sid, (g % 3 + 1) % 3)
+        depths.append(int(sp.step([sid])[1][0]))
+    assert depths == [w.schedule.exit_layer] * 7 and sp.seq_state(sid)["pending"] == 7
+    sp.seq_set_phase(sid, (7 % 3 + 1) % 3)
+    with pytest.raises(sb.SparkError) as ei:         # 8 pending rows + the next position > 8 slots
+        sp.step([sid])
+    assert ei.value.code == -4
+    assert sp.seq_state(sid) == {"len": 11, "upper_valid": 4, "pending": 7}   # nothing was enqueued
+    sp.seq_set_phase(sid, 7 % 3)                     # the slot about to run is the full-depth one
+    tok, dep = sp.step([sid])
+    assert dep[0] == w.shape.n_layers and sp.seq_state(sid)["pending"] == 0
+    assert sp.get_stats(sid)["flush_hist"] == {8: 1}
+    sp.close()
