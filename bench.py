@@ -131,6 +131,8 @@ def main() -> int:
     ap.add_argument("--temperature", type=float, default=0.0,
                     help="> 0: draw tokens by temperature / nucleus sampling instead of the arg-max")
     ap.add_argument("--top-p", type=float, default=0.9)
+    ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
+                    help="a kernel-selection switch of the library (spark_tune), for A/B measurements")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus must be 1 (no collectives, no "
@@ -170,6 +172,9 @@ def main() -> int:
     else:
         plens = [prompt_len]
     sp = Spark(shape, sched, dev_w, max_batch=B, max_seq_len=max_seq, kv_page_tokens=64, device="cuda:0")
+    for t in args.tune:
+        name, value = t.split("=")
+        sp.tune(name, int(value))
     cyc = sched.n_text + sched.n_speech
     sids = [sp.seq_open(i % cyc if B > 1 and not args.aligned else 0) for i in range(B)]
     prompts = [wl.make_prompt(shape, n, seed=1 + i, ids=w.prompt_ids) for i, n in enumerate(plens)]

@@ -101,6 +101,21 @@ __device__ __forceinline__ void split_store4(const SplitOut &so, int r, int k, f
         *(uint2 *)(so.xs + p * so.part_stride + (size_t)r * so.row_stride + z) = make_uint2(0, 0);
 }
 
+// two consecutive elements k, k+1 (k even) of row r
+__device__ __forceinline__ void split_store2(const SplitOut &so, int r, int k, float v0, float v1) {
+  bf16_t h0, m0, l0, h1, m1, l1;
+  split3_bf16(v0, h0, m0, l0);
+  split3_bf16(v1, h1, m1, l1);
+  bf16_t *dst = so.xs + (size_t)r * so.row_stride + k;
+  *(uint32_t *)dst = h0 | ((uint32_t)h1 << 16);
+  *(uint32_t *)(dst + so.part_stride) = m0 | ((uint32_t)m1 << 16);
+  *(uint32_t *)(dst + 2 * so.part_stride) = l0 | ((uint32_t)l1 << 16);
+  if (k + 2 >= so.width)
+    for (int z = so.width; z < so.row_stride; z += 2)
+#pragma unroll
+      for (int p = 0; p < 3; ++p) *(uint32_t *)(so.xs + p * so.part_stride + (size_t)r * so.row_stride + z) = 0u;
+}
+
 // one element
 __device__ __forceinline__ void split_store1(const SplitOut &so, int r, int k, float v) {
   bf16_t h, m, l;

@@ -181,6 +181,28 @@ struct ProNorm {
 
 struct NoState {};
 
+// RMSNorm is linear in 1/rms: a projection of gamma (.) h can be scaled by 1/rms(h) afterwards.
+// The launch that produces h (a residual projection's finishing step) then also writes the split
+// gamma (.) h and adds the row's sum of squares, as a fixed-point integer so that the order of
+// the additions does not matter, into one word per row; the next projection's epilogue reads it.
+constexpr float SSQ_SCALE = 16777216.0f;   // 2^24: sums of squares up to 1e12 fit 64 bits
+// words per row: the workgroups of the finishing launch add to word (workgroup % SSQ_WAYS) of the
+// row, so that few atomics meet at one address (56 workgroups on one word took 5 us to drain)
+constexpr int SSQ_WAYS = 8;
+struct RowScale {
+  const unsigned long long *ssq;   // [pass row][SSQ_WAYS] fixed-point sums of squares, nullptr: rows are normalised already
+  float inv_d, eps;
+  __device__ __forceinline__ float of(int r) const {
+    if (!ssq) return 1.0f;
+    unsigned long long w[SSQ_WAYS], tot = 0ull;
+#pragma unroll
+    for (int i = 0; i < SSQ_WAYS; ++i) w[i] = ssq[r * SSQ_WAYS + i];
+#pragma unroll
+    for (int i = 0; i < SSQ_WAYS; ++i) tot += w[i];
+    return 1.0f / sqrtf((float)((double)tot * (1.0 / (double)SSQ_SCALE)) * inv_d + eps);
+  }
+};
+
 // q, k, v projection + rotary embedding + KV-cache write.  Task t -> head t / (hd/2), pair index
 // i = t % (hd/2): weight rows (head*hd + i) and (head*hd + i + hd/2), the two elements that the
 // rotary embedding mixes.  Heads [0,nq) are queries, [nq,nq+nkv) keys, the rest values.
@@ -191,6 +213,7 @@ template <typename WT, bool DS = false> struct EpiQKV {
   float *qbuf;             // [pass row][nq*hd], rotated queries
   const float2 *rope;      // [pos][hd/2] (cos, sin)
   KVView kv;
+  RowScale scale = RowScale{nullptr, 0.f, 0.f};
   __device__ void init(State &) const {}
   __device__ void weight_rows(int task, const WT *&r0, const WT *&r1) const {
     int half = hd >> 1, head = task / half, i = task - head * half;
@@ -204,6 +227,7 @@ template <typename WT, bool DS = false> struct EpiQKV {
   }
   __device__ void finish(int task, int r, const RowDesc &rd, float y0, float y1, State &) const {
     int half = hd >> 1, head = task / half, i = task - head * half;
+    if (scale.ssq) { const float inv = scale.of(r); y0 *= inv; y1 *= inv; }
     if (head < nq + nkv) {
       float2 cs = rope[(size_t)rd.pos * half + i];
       float a = y0 * cs.x - y1 * cs.y, b = y1 * cs.x + y0 * cs.y;
@@ -243,16 +267,66 @@ template <typename WT, bool DS = false> struct EpiResidual {
     store2_maybe_ds<DS>(h, v);
   }
   // the same in two halves, for a caller that fetches the old value long before the sum is ready
+  typedef float2 Old;
   __device__ float2 load_old(int task, const RowDesc &rd) const {
     return load2_maybe_ds<DS>(hidden + (size_t)rd.x_slot * d + 2 * task);
   }
-  __device__ void finish_old(int task, const RowDesc &rd, float y0, float y1, float2 old) const {
+  __device__ void finish_old(int task, int r, const RowDesc &rd, float y0, float y1, float2 old, State &) const {
     store2_maybe_ds<DS>(hidden + (size_t)rd.x_slot * d + 2 * task, make_float2(old.x + y0, old.y + y1));
   }
   __device__ void end(int, const RowDesc &, State &) const {}
 };
+// hidden[x_slot][i] += y as above, and what the next projection needs of the new hidden state
+// h: the three bf16 parts of gamma (.) h for pass row r, and h's sum of squares (see RowScale).
+// For the finishing launch of a k-split projection, whose threads of one row are 32 lanes apart.
+template <typename WT> struct EpiResidualNorm {
+  struct State { float ssq; };
+  const WT *w;
+  int n_in, n_out;
+  float *hidden;
+  int d;
+  const float *gamma;          // gain of the norm that follows
+  SplitOut so;                 // where the split gamma (.) h goes
+  unsigned long long *ssq;     // [pass row][SSQ_WAYS], zero before the launch
+  __device__ void init(State &s) const { s.ssq = 0.f; }
+  __device__ void weight_rows(int task, const WT *&r0, const WT *&r1) const {
+    r0 = w + (size_t)(2 * task) * n_in;
+    r1 = r0 + n_in;
+  }
+  __device__ void finish(int task, int r, const RowDesc &rd, float y0, float y1, State &s) const {
+    float *h = hidden + (size_t)rd.x_slot * d + 2 * task;
+    float2 v = *(const float2 *)h;
+    v.x += y0; v.y += y1;
+    *(float2 *)h = v;
+    s.ssq += v.x * v.x + v.y * v.y;
+    const float2 g = *(const float2 *)(gamma + 2 * task);
+    split_store2(so, r, 2 * task, v.x * g.x, v.y * g.y);
+  }
+  // the old value and the gains, requested together long before the sums are ready
+  typedef float4 Old;
+  __device__ float4 load_old(int task, const RowDesc &rd) const {
+    const float2 v = *(const float2 *)(hidden + (size_t)rd.x_slot * d + 2 * task);
+    const float2 g = *(const float2 *)(gamma + 2 * task);
+    return make_float4(v.x, v.y, g.x, g.y);
+  }
+  __device__ void finish_old(int task, int r, const RowDesc &rd, float y0, float y1, float4 o, State &s) const {
+    const float2 v = make_float2(o.x + y0, o.y + y1);
+    *(float2 *)(hidden + (size_t)rd.x_slot * d + 2 * task) = v;
+    s.ssq += v.x * v.x + v.y * v.y;
+    split_store2(so, r, 2 * task, v.x * o.z, v.y * o.w);
+  }
+  // `sum`: the states of the threads that finished tasks of row r in this workgroup, added up
+  __device__ void add_row_sum(int r, float sum) const {
+    atomicAdd(ssq + r * SSQ_WAYS + (blockIdx.x % SSQ_WAYS), (unsigned long long)(sum * SSQ_SCALE + 0.5f));
+  }
+  __device__ void end(int, const RowDesc &, State &) const {}
+};
+template <typename E> struct EpiHasRowSum { static constexpr bool value = false; };
+template <typename WT> struct EpiHasRowSum<EpiResidualNorm<WT>> { static constexpr bool value = true; };
+
 template <typename E> struct EpiReadsOld { static constexpr bool value = false; };
 template <typename WT, bool DS> struct EpiReadsOld<EpiResidual<WT, DS>> { static constexpr bool value = true; };
+template <typename WT> struct EpiReadsOld<EpiResidualNorm<WT>> { static constexpr bool value = true; };
 
 // act[r][i] = silu(Wg_i . n) * (Wu_i . n)
 template <typename WT, bool DS = false> struct EpiSwiGLU {
@@ -278,12 +352,14 @@ template <typename WT> struct EpiSwiGLUSplit {
   const WT *wg, *wu;
   int d, F;
   SplitOut so;
+  RowScale scale = RowScale{nullptr, 0.f, 0.f};
   __device__ void init(State &) const {}
   __device__ void weight_rows(int task, const WT *&r0, const WT *&r1) const {
     r0 = wg + (size_t)task * d;
     r1 = wu + (size_t)task * d;
   }
   __device__ void finish(int task, int r, const RowDesc &, float y0, float y1, State &) const {
+    if (scale.ssq) { const float inv = scale.of(r); y0 *= inv; y1 *= inv; }
     float s = y0 / (1.0f + expf(-y0));
     split_store1(so, r, task, s * y1);
   }

@@ -206,6 +206,10 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
   const int x_stride = n_chunks * MG_KC;
   const int c_begin = by * chunks_per_split;
   const int c_end = min(n_chunks, c_begin + chunks_per_split);
+  // the rows' sums of squares that this projection's finishing launch will add up start at zero
+  if constexpr (EpiHasRowSum<Epi>::value)
+    if (blockIdx.x == 0)
+      for (int i = threadIdx.x; i < m_rows * SSQ_WAYS; i += 64 * WAVES) epi.ssq[i] = 0ull;
   if (c_begin >= c_end) return;
 
   // Load instruction i covers the wave's rows 8i..8i+7 (rows 0..31: first weight row of tasks
@@ -366,22 +370,22 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
   }
 }
 
-// The partial sums of one (task, row) over the k ranges, added in the order of the ranges; the
-// loads of eight ranges are issued before the first is used (a loop that loads and adds pays a
-// round trip per range, and a projection with few tiles has up to 32 of them).
+// The partial sums of one (task, row) over the k ranges, added in the order of the ranges.  All
+// loads are issued before the first is used: a loop that loads and adds pays a memory round trip
+// per trip, and a projection with few tiles has up to MG_MAX_SPLIT ranges.
+constexpr int MG_MAX_SPLIT = 32;
+// MAXS: the most ranges this instance adds (8 or MG_MAX_SPLIT): the loads live in 2 * MAXS
+// registers, and a finishing launch with hundreds of workgroups wants two of them on a CU
+template <int MAXS>
 __device__ __forceinline__ void sum_splits(const float *__restrict__ part, int n_split, int n_tasks, int task,
                                            int m_pad, int m, float &y0, float &y1) {
   const size_t stride = (size_t)n_tasks * 2 * m_pad;
   const float *p = part + ((size_t)task * 2) * m_pad + m;
-  int s = 0;
-  for (; s + 8 <= n_split; s += 8) {
-    float a[8], b[8];
+  float a[MAXS], b[MAXS];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { a[i] = p[(s + i) * stride]; b[i] = p[(s + i) * stride + m_pad]; }
+  for (int i = 0; i < MAXS; ++i) { const int s = i < n_split ? i : 0; a[i] = p[s * stride]; b[i] = p[s * stride + m_pad]; }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { y0 += a[i]; y1 += b[i]; }
-  }
-  for (; s < n_split; ++s) { y0 += p[s * stride]; y1 += p[s * stride + m_pad]; }
+  for (int i = 0; i < MAXS; ++i) if (i < n_split) { y0 += a[i]; y1 += b[i]; }
 }
 
 // sums the k-split partials and runs the epilogue: one thread per activation row and group of
@@ -443,27 +447,46 @@ mfma_finish_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, int n_tasks
 // runs the epilogue with the tasks fastest, so that what the epilogue writes (consecutive
 // elements of a row of the hidden state, of q, of the cache, of the split activations) leaves a
 // wave as whole segments instead of single words 7 KB apart.  grid (tasks / 32, m_pad / 32).
-template <typename Epi>
+template <typename Epi, int MAXS>
 __global__ void __launch_bounds__(1024)
 mfma_finish_tile_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, int n_tasks, int n_split,
                    const float *__restrict__ part, int m_pad) {
   __shared__ float s_y[2][32][33];
   const int task0 = blockIdx.x * 32, row0 = blockIdx.y * 32;
+  // what the epilogue will need besides the sums is requested first: the row's descriptor, and
+  // through it the old value of a residual projection; both round trips run under the loads of
+  // the partial sums
+  const int tl = threadIdx.x & 31, ml = threadIdx.x >> 5, task = task0 + tl, m = row0 + ml;
+  const bool live = task < n_tasks && m < m_rows;
+  const RowDesc rd = rows[m < m_rows ? m : 0];
+  auto old = [&]() {
+    if constexpr (EpiReadsOld<Epi>::value) return epi.load_old(live ? task : 0, rd);
+    else return 0;
+  }();
   {
-    const int ml = threadIdx.x & 31, tl = threadIdx.x >> 5, task = min(task0 + tl, n_tasks - 1);
+    const int ml_ = threadIdx.x & 31, tl_ = threadIdx.x >> 5, task_ = min(task0 + tl_, n_tasks - 1);
     float y0 = 0.f, y1 = 0.f;
-    if (row0 + ml < m_pad) sum_splits(part, n_split, n_tasks, task, m_pad, row0 + ml, y0, y1);
-    s_y[0][tl][ml] = y0;
-    s_y[1][tl][ml] = y1;
+    if (row0 + ml_ < m_pad) sum_splits<MAXS>(part, n_split, n_tasks, task_, m_pad, row0 + ml_, y0, y1);
+    s_y[0][tl_][ml_] = y0;
+    s_y[1][tl_][ml_] = y1;
   }
   __syncthreads();
-  const int tl = threadIdx.x & 31, ml = threadIdx.x >> 5, task = task0 + tl, m = row0 + ml;
-  if (task >= n_tasks || m >= m_rows) return;
-  const RowDesc rd = rows[m];
   typename Epi::State st;
   epi.init(st);
-  epi.finish(task, m, rd, s_y[0][tl][ml], s_y[1][tl][ml], st);
-  epi.end(m, rd, st);
+  if (live) {
+    if constexpr (EpiReadsOld<Epi>::value) epi.finish_old(task, m, rd, s_y[0][tl][ml], s_y[1][tl][ml], old, st);
+    else epi.finish(task, m, rd, s_y[0][tl][ml], s_y[1][tl][ml], st);
+  }
+  if constexpr (EpiHasRowSum<Epi>::value) {
+    // the 32 threads of a row are half a wave: their states are added with shuffles (a fixed
+    // order), and one of them hands the sum on
+    float sum = st.ssq;
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+    if (tl == 0 && m < m_rows) epi.add_row_sum(m, sum);
+  } else {
+    if (live) epi.end(m, rd, st);
+  }
 }
 
 }  // namespace spark

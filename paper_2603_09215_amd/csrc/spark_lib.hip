@@ -38,7 +38,7 @@ constexpr int MAX_SEQ_LEN = 16384;
 
 struct Layout {  // byte offsets into the scratch buffer
   size_t state, page_table, plan, lower, upper, ee, full, prefill_rows, prefill_tokens, seq_ids,
-      forced, step_flags, out_tokens, out_depth, best, arrivals, sample_hist, sample_arrive, sample_count, hidden, xsplit, xsplit2, mfma_part, sample_q, sample_cand, rand_words, qbuf, attn_out, part, act, lens_u,
+      forced, step_flags, out_tokens, out_depth, best, arrivals, row_ssq, sample_hist, sample_arrive, sample_count, hidden, xsplit, xsplit2, mfma_part, sample_q, sample_cand, rand_words, qbuf, attn_out, part, act, lens_u,
       logits, rope, inv_freq, total;
 };
 
@@ -83,6 +83,7 @@ struct spark_ctx {
   int attn_pieces = 0;         // 64-token pieces per attention workgroup (0: by the launch's size)
   int gemv_big_kb = 40;        // vector-kernel launches with more LDS per workgroup run eight waves per workgroup
   int attn_mfma_min_rows = 1;  // passes with at least this many rows run attention on the MFMA units (where the shape allows)
+  bool fuse_norm = true;       // the residual projections' finishing launches prepare the next norm's input (no separate launch)
   bool static_scratch = false; // the scratch area is the library's static device array (spark_init_static)
   int device = 0;
   float temperature = 0.f, top_p = 0.f;   // nucleus sampling, off while temperature <= 0
@@ -212,6 +213,7 @@ void layout(const spark_config &c, const Derived &d, Layout &l) {
   l.out_depth = take(sizeof(int) * (size_t)MAX_STEPS_PER_CALL * c.max_batch);
   l.best = take(sizeof(unsigned long long) * c.max_batch);
   l.arrivals = take(sizeof(int) * (size_t)d.max_rows * c.n_q_heads);   // per (row, group of query heads)
+  l.row_ssq = take(sizeof(unsigned long long) * 2 * SSQ_WAYS * (size_t)d.max_rows);   // sums of squares handed from a finishing launch to the next projection
   l.sample_hist = take(sizeof(unsigned long long) * (size_t)SAMPLE_BINS * c.max_batch);   // zero between launches
   l.sample_arrive = take(sizeof(unsigned) * c.max_batch);
   l.sample_count = take(sizeof(unsigned) * c.max_batch);
@@ -477,19 +479,20 @@ int launch_mfma_shape(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, 
   const int tiles_padded = xcd_groups ? (bx * split + 7) / 8 * 8 : bx * split;
   dim3 grid(tiles_padded * z);
   const size_t lds = mg_lds_bytes(MTILES, WAVES);
-  if (split > 1) {
+  if (split > 1 || EpiHasRowSum<Epi>::value) {   // (an epilogue that sums over a row runs in the finishing launch only)
     mfma_rows_k<MTILES, Epi, true, WAVES><<<grid, 64 * WAVES, lds, c->stream>>>(
         epi, rows, m, xs, xst, n_in, n_tasks, cps, part, m_pad, bx, split, z, xcd_groups);
-    if constexpr (std::is_same<typename Epi::State, NoState>::value) {
+    if constexpr (std::is_same<typename Epi::State, NoState>::value || EpiHasRowSum<Epi>::value) {
       // epilogues without a running state: stores coalesced over tasks
-      mfma_finish_tile_k<Epi><<<dim3((n_tasks + 31) / 32, (m_pad + 31) / 32), 1024, 0, c->stream>>>(epi, rows, m, n_tasks, split,
-                                                                                              part, m_pad);
+      const dim3 fgrid((n_tasks + 31) / 32, (m_pad + 31) / 32);
+      if (split <= 8) mfma_finish_tile_k<Epi, 8><<<fgrid, 1024, 0, c->stream>>>(epi, rows, m, n_tasks, split, part, m_pad);
+      else mfma_finish_tile_k<Epi, MG_MAX_SPLIT><<<fgrid, 1024, 0, c->stream>>>(epi, rows, m, n_tasks, split, part, m_pad);
     } else {
       const int tpt = finish_tasks_per_thread(epi);
       const int total = ((n_tasks + tpt - 1) / tpt) * m_pad;
       mfma_finish_k<Epi><<<(total + 255) / 256, 256, 0, c->stream>>>(epi, rows, m, n_tasks, split, part, m_pad, tpt);
     }
-  } else {
+  } else if constexpr (!EpiHasRowSum<Epi>::value) {
     occ = mfma_occupancy<MTILES, Epi, false, WAVES>(c);
     if (occ < 0) return occ;
     mfma_rows_k<MTILES, Epi, false, WAVES><<<grid, 64 * WAVES, lds, c->stream>>>(
@@ -534,9 +537,16 @@ int run_layers_mfma(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
   const int d = g.d_model, hd = g.head_dim, nq = g.n_q_heads, nkv = g.n_kv_heads, F = g.d_ffn;
   const size_t qw = (size_t)nq * hd, kvw = (size_t)nkv * hd;
   float *hidden = at<float>(c, c->lo.hidden);
+  // RMSNorm is linear in 1/rms: the finishing launch of a residual projection writes the split
+  // gamma (.) h for the projection that follows and adds up h's sum of squares per row; that
+  // projection's epilogue scales by 1/rms.  Only the first norm of a run is a launch of its own.
+  unsigned long long *ssq_attn = at<unsigned long long>(c, c->lo.row_ssq);
+  unsigned long long *ssq_mlp = ssq_attn + (size_t)SSQ_WAYS * c->dv.max_rows;
+  const bool fuse = c->fuse_norm;
   int rc;
   for (int l = l0; l < l1; ++l) {
-    if ((rc = launch_prep(c, rows, m, hidden, d, 1, c->w.attn_norm + (size_t)l * d, d))) return rc;
+    const bool qkv_scaled = fuse && l > l0;
+    if (!qkv_scaled && (rc = launch_prep(c, rows, m, hidden, d, 1, c->w.attn_norm + (size_t)l * d, d))) return rc;
     EpiQKV<WT> eq;
     eq.wq = (const WT *)c->w.wq + (size_t)l * qw * d;
     eq.wk = (const WT *)c->w.wk + (size_t)l * kvw * d;
@@ -545,21 +555,34 @@ int run_layers_mfma(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
     eq.qbuf = at<float>(c, c->lo.qbuf);
     eq.rope = at<float2>(c, c->lo.rope);
     eq.kv = kv_view(c);
+    if (qkv_scaled) eq.scale = RowScale{ssq_attn, 1.0f / (float)d, g.rms_eps};
     if ((rc = launch_mfma(c, eq, rows, m, d, (nq + 2 * nkv) * (hd / 2), true, SPARK_KC_QKV))) return rc;
 
     // attention leaves its output split for the MFMA kernel; so does the SwiGLU epilogue below
     if ((rc = launch_attention<WT>(c, rows, m, l, true))) return rc;
 
-    EpiResidual<WT> eo{(const WT *)c->w.wo + (size_t)l * d * qw, (int)qw, d, hidden, d};
-    if ((rc = launch_mfma(c, eo, rows, m, (int)qw, d / 2, true, SPARK_KC_OPROJ))) return rc;
-
-    if ((rc = launch_prep(c, rows, m, hidden, d, 1, c->w.mlp_norm + (size_t)l * d, d))) return rc;
     EpiSwiGLUSplit<WT> eg{(const WT *)c->w.wg + (size_t)l * F * d, (const WT *)c->w.wu + (size_t)l * F * d,
                           d, F, split_target(c, F, true)};
+    if (fuse) {
+      EpiResidualNorm<WT> eo{(const WT *)c->w.wo + (size_t)l * d * qw, (int)qw, d, hidden, d,
+                             c->w.mlp_norm + (size_t)l * d, split_target(c, d), ssq_mlp};
+      if ((rc = launch_mfma(c, eo, rows, m, (int)qw, d / 2, true, SPARK_KC_OPROJ))) return rc;
+      eg.scale = RowScale{ssq_mlp, 1.0f / (float)d, g.rms_eps};
+    } else {
+      EpiResidual<WT> eo{(const WT *)c->w.wo + (size_t)l * d * qw, (int)qw, d, hidden, d};
+      if ((rc = launch_mfma(c, eo, rows, m, (int)qw, d / 2, true, SPARK_KC_OPROJ))) return rc;
+      if ((rc = launch_prep(c, rows, m, hidden, d, 1, c->w.mlp_norm + (size_t)l * d, d))) return rc;
+    }
     if ((rc = launch_mfma(c, eg, rows, m, d, F, true, SPARK_KC_GATEUP))) return rc;
 
-    EpiResidual<WT> ed{(const WT *)c->w.wd + (size_t)l * d * F, F, d, hidden, d};
-    if ((rc = launch_mfma(c, ed, rows, m, F, d / 2, true, SPARK_KC_DOWN, true))) return rc;
+    if (fuse && l + 1 < l1) {
+      EpiResidualNorm<WT> ed{(const WT *)c->w.wd + (size_t)l * d * F, F, d, hidden, d,
+                             c->w.attn_norm + (size_t)(l + 1) * d, split_target(c, d), ssq_attn};
+      if ((rc = launch_mfma(c, ed, rows, m, F, d / 2, true, SPARK_KC_DOWN, true))) return rc;
+    } else {
+      EpiResidual<WT> ed{(const WT *)c->w.wd + (size_t)l * d * F, F, d, hidden, d};
+      if ((rc = launch_mfma(c, ed, rows, m, F, d / 2, true, SPARK_KC_DOWN, true))) return rc;
+    }
   }
   return SPARK_OK;
 }
@@ -1060,6 +1083,7 @@ int spark_tune(spark_ctx *c, const char *name, int32_t value) {
   else if (k == "attn_pieces") c->attn_pieces = std::max(0, std::min(8, (int)value));
   else if (k == "attn_mfma_min_rows") c->attn_mfma_min_rows = std::max(1, (int)value);
   else if (k == "gemv_big_kb") c->gemv_big_kb = std::max(1, (int)value);
+  else if (k == "fuse_norm") c->fuse_norm = value != 0;
   else return fail(c, SPARK_EINVAL, "unknown tuning name '%s'", name);
   return SPARK_OK;
 }
