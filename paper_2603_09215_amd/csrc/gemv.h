@@ -324,6 +324,8 @@ template <typename WT> struct EpiResidualNorm {
 template <typename E> struct EpiHasRowSum { static constexpr bool value = false; };
 template <typename WT> struct EpiHasRowSum<EpiResidualNorm<WT>> { static constexpr bool value = true; };
 
+template <typename E> struct EpiHasLocalReduce { static constexpr bool value = false; };
+
 template <typename E> struct EpiReadsOld { static constexpr bool value = false; };
 template <typename WT, bool DS> struct EpiReadsOld<EpiResidual<WT, DS>> { static constexpr bool value = true; };
 template <typename WT> struct EpiReadsOld<EpiResidualNorm<WT>> { static constexpr bool value = true; };
@@ -425,6 +427,8 @@ template <typename WT> struct EpiVocab {
     atomicMax(best + rd.out_idx, key);
   }
 };
+
+template <typename WT> struct EpiHasLocalReduce<EpiVocab<WT>> { static constexpr bool value = true; };
 
 // ------------------------------------------------------------------ the kernel
 
@@ -607,7 +611,25 @@ gemv_rows_k(Pro pro, Epi epi, const RowDesc *__restrict__ rows, int m_rows, int 
       issue(ring[j]);
     }
   }
-  if (lane < n_valid) {
+  if constexpr (EpiHasLocalReduce<Epi>::value) {
+    // a running state per wave and row (the heads' arg-max): the waves of the workgroup combine
+    // theirs in LDS, where the activations are no longer needed, and one atomic per row and
+    // workgroup goes to memory instead of one per wave (thousands of atomics on one address
+    // drain one after the other)
+    unsigned long long *s_best = (unsigned long long *)xs;
+    __syncthreads();
+    if (threadIdx.x < MT) s_best[threadIdx.x] = 0ull;
+    __syncthreads();
+    if (lane < n_valid) epi.reduce_local(st, s_best + lane);
+    __syncthreads();
+    if ((int)threadIdx.x < n_valid && s_best[threadIdx.x]) {
+      RowDesc mine = rd[0];
+#pragma unroll
+      for (int m = 0; m < MT; ++m)
+        if (lane == m) mine = rd[m];
+      epi.end_reduced(mine, s_best[threadIdx.x]);
+    }
+  } else if (lane < n_valid) {
     RowDesc mine = rd[0];
 #pragma unroll
     for (int m = 0; m < MT; ++m)

@@ -68,3 +68,27 @@ def test_full_shape_batched_decode(name, B, offsets, n_steps):
     say(f"  rows per step: full depth {rows_full.tolist()}, early exit {rows_ee.tolist()}; "
         f"{flushed} rows went through layers {e + 1}..{L}")
     sp.close()
+
+
+@pytest.mark.parametrize("exit_layer,period", [(14, 8), (24, 2)])
+def test_full_shape_batched_sweep_points(exit_layer, period):
+    """the far corners of the batched benchmark's sweep (exit layer 14 / 20 / 24, period 2 / 4 / 8)
+    at the full Step-Audio-2-mini shape: five sequences with mixed cycle offsets, so that the pass
+    through the upper layers has 14 or 4 of them and flushes of up to 8 rows per sequence occur
+    with the long period"""
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2603_09215_amd import binding as sb
+    w = wl.WORKLOADS["step_audio_2_mini"]
+    sched = w.schedule.replace(exit_layer=exit_layer, period_k=period, phase=period - 1)
+    say(f"case full shape batched sweep point e={exit_layer} K={period}")
+    dev_w, host_w = full_weights("step_audio_2_mini")
+    B, n_steps = 5, 10
+    offs = [i % 3 for i in range(B)]
+    prompts = [wl.make_prompt(w.shape, 3 + i, seed=71 + i, ids=w.prompt_ids) for i in range(B)]
+    sp = sb.Spark(w.shape, sched, dev_w, max_batch=B, max_seq_len=64, kv_page_tokens=64)
+    res = compare_run(sp, w.shape, sched, host_w, prompts, offs, n_steps, check_kv_every=2,
+                      label=f"step_audio_2_mini/B{B}/e{exit_layer}K{period}", oracle_kind="f64", trace_steps=True)
+    assert set(np.unique(res["depths"])) == {exit_layer, w.shape.n_layers}
+    sp.close()
