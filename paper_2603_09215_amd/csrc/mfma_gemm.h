@@ -194,6 +194,12 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
   constexpr int WD = MG_W_DEPTH;
   constexpr int XPOS = MROWS * (MG_KC / 8);                  // 16-byte vectors of one part of a chunk
   constexpr int XV = (XPOS + (64 * WAVES) - 1) / (64 * WAVES);   // of them per thread
+  // Every thread stages XV vectors, wrapping around when the workgroup has more threads than a
+  // chunk has vectors (32 rows in an eight-wave workgroup: two threads then write the same data to
+  // the same place).  A store under a condition would take its load with it: the compiler sinks a
+  // load whose only use is conditional into that branch, next to the store, and the wave then
+  // waits out the whole memory latency once per chunk instead of having the data a chunk ahead.
+  static_assert(XPOS % (64 * WAVES) == 0 || (64 * WAVES) % XPOS == 0, "the staging wraps evenly");
   constexpr int PART_ELEMS = MROWS * MG_ROWPAD;
   constexpr int WI = 8;                                      // load instructions per chunk: 8 rows x 128 bytes each
   extern __shared__ uint4 mg_smem[];
@@ -240,7 +246,7 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
   int x_src[XV], x_dst[XV];
 #pragma unroll
   for (int i = 0; i < XV; ++i) {
-    const int pos = min((int)threadIdx.x + i * (64 * WAVES), XPOS - 1);
+    const int pos = ((int)threadIdx.x + i * (64 * WAVES)) % XPOS;
     const int m = pos / (MG_KC / 8), kv = (pos - m * (MG_KC / 8)) * 8;
     x_src[i] = min(row0 + m, m_rows - 1) * x_stride + kv;    // rows past the end repeat the last one
     x_dst[i] = m * MG_ROWPAD + kv;
@@ -259,10 +265,8 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
   {
 #pragma unroll
     for (int i = 0; i < XV; ++i) {
-      if ((int)threadIdx.x + i * (64 * WAVES) < XPOS) {
 #pragma unroll
-        for (int p = 0; p < MG_PARTS; ++p) *(u32x4_t *)(s_x + p * PART_ELEMS + x_dst[i]) = xr[i][p];
-      }
+      for (int p = 0; p < MG_PARTS; ++p) *(u32x4_t *)(s_x + p * PART_ELEMS + x_dst[i]) = xr[i][p];
     }
   }
   __builtin_amdgcn_sched_barrier(0);
@@ -298,11 +302,9 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
       {
 #pragma unroll
         for (int i = 0; i < XV; ++i) {
-          if ((int)threadIdx.x + i * (64 * WAVES) < XPOS) {
 #pragma unroll
-            for (int p = 0; p < MG_PARTS; ++p)
-              *(u32x4_t *)(s_x + ((buf ^ 1) * MG_PARTS + p) * PART_ELEMS + x_dst[i]) = xr[i][p];
-          }
+          for (int p = 0; p < MG_PARTS; ++p)
+            *(u32x4_t *)(s_x + ((buf ^ 1) * MG_PARTS + p) * PART_ELEMS + x_dst[i]) = xr[i][p];
         }
       }
       __builtin_amdgcn_sched_barrier(0);
