@@ -402,6 +402,282 @@ mfma_rows_k(Epi epi, const RowDesc *__restrict__ rows, int m_rows, const bf16_t 
   }
 }
 
+// ------------------------------------------------------------------ the contraction on tiled weights
+//
+// A context that owns enough memory keeps a second copy of every bf16 projection matrix in the
+// order the MFMA consumes it: for each block of 32 tasks, for each of its two weight rows per
+// task, for each 64-wide chunk of k, one 4 KiB tile [step 0..3][lane 0..63][8 elements], lane l of
+// step s holding row l % 32, elements 64 c + 16 s + 8 (l / 32) .. + 7.  A wave then loads a whole
+// A operand with one fully coalesced instruction (64 lanes x 16 bytes, consecutive) straight into
+// registers: the weights never touch LDS, which leaves LDS to the activations, and a wave can hold
+// four A tiles (64 tasks), so that every B operand it reads from LDS feeds four MFMAs instead of
+// two.  tile_weights_k writes the copy once, when the context is created, from the same
+// weight_rows() of the epilogue that the kernels use.
+constexpr int TG_WAVES = 4;
+constexpr int TG_TILE = 32 * MG_KC;   // elements of one A tile of one chunk
+
+constexpr size_t tg_tiled_elems(int n_tasks, int n_in) {
+  return (size_t)((n_tasks + 31) / 32) * 2 * ((n_in + MG_KC - 1) / MG_KC) * TG_TILE;
+}
+
+template <typename Epi>
+__global__ void __launch_bounds__(256)
+tile_weights_k(Epi epi, int n_tasks, int n_in, int n_chunks, bf16_t *__restrict__ dst) {
+  const int c = blockIdx.x, tbw = blockIdx.y, tb = tbw >> 1, which = tbw & 1;
+  const int s = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int task = tb * 32 + (lane & 31);
+  const int k = c * MG_KC + s * 16 + (lane >> 5) * 8;
+  u32x4_t v = {0u, 0u, 0u, 0u};   // beyond the matrix: zeros
+  if (task < n_tasks && k < n_in) {
+    const bf16_t *a, *b;
+    epi.weight_rows(task, a, b);
+    v = *(const u32x4_t *)((which ? b : a) + k);
+  }
+  *(u32x4_t *)(dst + ((size_t)tbw * n_chunks + c) * TG_TILE + s * 512 + lane * 8) = v;
+}
+
+// dynamic LDS of mfma_tiled_k: two buffers of three parts of 32*MTILES padded activation rows, or
+// the four waves' pieces for turning the result tiles, whichever is larger
+constexpr size_t tg_lds_bytes(int mtiles) {
+  const size_t x = sizeof(bf16_t) * 2 * MG_PARTS * 32 * mtiles * MG_ROWPAD;
+  const size_t t = sizeof(float) * TG_WAVES * 2 * 32 * 33;
+  return x > t ? x : t;
+}
+
+// A workgroup of four waves takes 128 * TB tasks (wave w: TB blocks of 32 tasks, 2 * TB A tiles),
+// one k range and one tile of 32 * MTILES activation rows; grid and arguments as mfma_rows_k.
+// SPLIT, or an epilogue without a running state.
+//
+// The loop over the chunks is written group by group in the order it is to execute, and every
+// group ends with a scheduling barrier: a group is the 2 * TB MFMAs that share one B operand, the
+// LDS read of a B operand of the NEXT step, and at most a few of the chunk's other operations (a
+// weight load, an activation load, an LDS write of the staging), which issue while the MFMAs
+// execute.  Left to itself the compiler puts each LDS read next to its use and the loads at the
+// end of the chunk, and the MFMA pipe then idles half the time (measured on the gate/up projection
+// of a 192-row prompt pass: 174 us; in this order 133 us; the same loop without any memory
+// operation 110 us).
+template <int MTILES, int TB, typename Epi, bool SPLIT>
+__global__ void __launch_bounds__(64 * TG_WAVES)
+mfma_tiled_k(Epi epi, const bf16_t *__restrict__ tiled, const RowDesc *__restrict__ rows, int m_rows,
+             const bf16_t *__restrict__ xs, size_t part_stride, int n_in, int n_tasks, int chunks_per_split,
+             float *__restrict__ part, int m_pad, int n_task_tiles, int n_splits, int n_row_tiles,
+             int xcd_groups) {
+  static_assert(SPLIT || std::is_same<typename Epi::State, NoState>::value, "a running state needs the finishing launch");
+  static_assert(MTILES <= MG_MAX_MTILES && (TB == 1 || TB == 2), "accumulators are sized for 64 rows x 64 tasks");
+  int bx, by, bz;   // workgroup -> (task tile, k range, row tile), as in mfma_rows_k
+  if (!xcd_groups) {
+    const int tiles = n_task_tiles * n_splits;
+    bz = blockIdx.x / tiles;
+    const int tile = blockIdx.x - bz * tiles;
+    if (bz >= n_row_tiles) return;
+    by = tile / n_task_tiles;
+    bx = tile - by * n_task_tiles;
+  } else {
+    const int per_group = 8 * n_row_tiles;
+    const int group = blockIdx.x / per_group, r = blockIdx.x - group * per_group;
+    const int tile = group * 8 + (r & 7);
+    if (tile >= n_task_tiles * n_splits) return;
+    bz = r >> 3;
+    by = tile / n_task_tiles;
+    bx = tile - by * n_task_tiles;
+  }
+  constexpr int MROWS = 32 * MTILES;
+  constexpr int NT = 64 * TG_WAVES;
+  constexpr int XPOS = MROWS * (MG_KC / 8);
+  constexpr int XV = XPOS / NT;
+  static_assert(XPOS % NT == 0, "every thread stages the same number of vectors");
+  constexpr int PART_ELEMS = MROWS * MG_ROWPAD;
+  constexpr int STEPS = MG_KC / 16;
+  constexpr int QT = 2 * TB;                        // A tiles per wave
+  constexpr int NB = MG_PARTS * MTILES;             // B operands (and groups of QT MFMAs) per step
+  constexpr int NX = XV * MG_PARTS;                 // activation vectors a thread stages per chunk
+  static_assert(NX == NB, "one staging operation per group");
+  constexpr int PER = (QT + NB - 1) / NB;           // weight loads per group
+  constexpr int BUF_ELEMS = MG_PARTS * PART_ELEMS;
+  extern __shared__ uint4 tg_smem[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  bf16_t *s_x = (bf16_t *)tg_smem;                  // [2][3][MROWS * MG_ROWPAD]
+  const int row0 = bz * MROWS;
+  const int n_chunks = (n_in + MG_KC - 1) / MG_KC;
+  const int x_stride = n_chunks * MG_KC;
+  const int c_begin = by * chunks_per_split;
+  const int c_end = min(n_chunks, c_begin + chunks_per_split);
+  if constexpr (EpiHasRowSum<Epi>::value)
+    if (blockIdx.x == 0)
+      for (int i = threadIdx.x; i < m_rows * SSQ_WAYS; i += NT) epi.ssq[i] = 0ull;
+  if (c_begin >= c_end) return;
+  const int n_tb = (n_tasks + 31) / 32;
+  const int tb0 = (bx * TG_WAVES + wave) * TB;       // this wave's first block of 32 tasks
+
+  const bf16_t *abase[QT];   // A tile q: block tb0 + q / 2, weight row q % 2 of its tasks (blocks past the end: the last one)
+#pragma unroll
+  for (int q = 0; q < QT; ++q)
+    abase[q] = tiled + ((size_t)(min(tb0 + (q >> 1), n_tb - 1) * 2 + (q & 1)) * n_chunks) * TG_TILE + lane * 8;
+  const int a_off = (lane & 31) * MG_ROWPAD + (lane >> 5) * 8;
+
+  f32x16_t acc[QT][MTILES];
+#pragma unroll
+  for (int q = 0; q < QT; ++q)
+#pragma unroll
+    for (int c = 0; c < MTILES; ++c)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[q][c][r] = 0.f;
+
+  int x_src[XV], x_dst[XV];
+#pragma unroll
+  for (int i = 0; i < XV; ++i) {
+    const int pos = (int)threadIdx.x + i * NT;
+    const int m = pos / (MG_KC / 8), kv = (pos - m * (MG_KC / 8)) * 8;
+    x_src[i] = min(row0 + m, m_rows - 1) * x_stride + kv;    // rows past the end repeat the last one
+    x_dst[i] = m * MG_ROWPAD + kv;
+  }
+  u32x4_t xr[XV][MG_PARTS];
+  u32x4_t wr[2][QT][STEPS];   // ring of two chunks of weights: slot = chunk parity
+  const u32x4_t zero4 = {0u, 0u, 0u, 0u};
+
+  // all loads are unconditional (chunks past the range are clamped to its last one) so that the
+  // compiler waits for exactly the loads a step needs; a chunk past the range is staged as zeros
+  auto load_x1 = [&](int n, int chunk) {
+    const int k_ = min(chunk, c_end - 1) * MG_KC;
+    xr[n / MG_PARTS][n % MG_PARTS] = *(const u32x4_t *)(xs + (n % MG_PARTS) * part_stride + x_src[n / MG_PARTS] + k_);
+  };
+  auto store_x1 = [&](int n, int buf, bool real) {
+    *(u32x4_t *)(s_x + buf * BUF_ELEMS + (n % MG_PARTS) * PART_ELEMS + x_dst[n / MG_PARTS]) =
+        real ? xr[n / MG_PARTS][n % MG_PARTS] : zero4;
+  };
+  // B operand i of step s of a buffer: parts from the smallest to the largest (the large terms
+  // are added last), row tiles inside
+  auto load_b1 = [&](int i, int buf, int s) -> u32x4_t {
+    const int p = MG_PARTS - 1 - i / MTILES, c = i % MTILES;
+    return *(const u32x4_t *)(s_x + buf * BUF_ELEMS + p * PART_ELEMS + c * 32 * MG_ROWPAD + s * 16 + a_off);
+  };
+  auto load_a1 = [&](int slot, int q, int s, int chunk) {
+    wr[slot][q][s] = __builtin_nontemporal_load(
+        (const u32x4_t *)(abase[q] + (size_t)min(chunk, c_end - 1) * TG_TILE + s * 512));
+  };
+
+#pragma unroll
+  for (int n = 0; n < NX; ++n) load_x1(n, c_begin);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int n = 0; n < NX; ++n) store_x1(n, 0, true);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int n = 0; n < NX; ++n) load_x1(n, c_begin + 1);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s)
+#pragma unroll
+      for (int q = 0; q < QT; ++q) load_a1(j, q, s, c_begin + j);
+  __syncthreads();
+  u32x4_t bcur[NB], bnext[NB];
+#pragma unroll
+  for (int i = 0; i < NB; ++i) bcur[i] = zero4;
+
+  // Region k (one barrier each) works on chunk i = c_begin + k, whose weights sit in ring slot
+  // k % 2 and whose activations in LDS buffer k % 2:
+  //   step 3 of chunk i - 1 (its B operands were fetched before the last barrier; zeros in region 0),
+  //   steps 0..2 of chunk i, while the B operands of the step after each are fetched,
+  //   the staging of chunk i + 1 into the other buffer, the loads of the activations of chunk i + 2,
+  //   and the reloads of the weight registers whose step has just been finished with (chunks
+  //   i + 1 and i + 2).
+  // Every read of a buffer lies in the region of its chunk, every write to it in the regions next
+  // to that one, so the one barrier per region separates them; the MFMAs run on across it.
+  // An odd number of chunks gets one more region on zeros.
+  const int n_regions = (c_end - c_begin + 1) & ~1;
+  for (int k0 = 0; k0 < n_regions; k0 += 2) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int chunk = c_begin + k0 + j;
+      const int jp = j ^ 1;
+#pragma unroll
+      for (int t = 0; t < STEPS; ++t) {
+        // t = 0: step 3 of the previous chunk; t = 1..3: steps 0..2 of this one
+        const int slot = t == 0 ? jp : j, s = t == 0 ? STEPS - 1 : t - 1;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+          const int c = i % MTILES;
+#pragma unroll
+          for (int q = 0; q < QT; ++q)
+            acc[q][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wr[slot][q][s]),
+                                                                __builtin_bit_cast(bf16x8_t, bcur[i]), acc[q][c], 0, 0, 0);
+          bnext[i] = load_b1(i, j, t);   // operands of step t of this chunk (t = 0 follows the last barrier)
+#pragma unroll
+          for (int e = 0; e < PER; ++e) {
+            const int q = i * PER + e;
+            if (q < QT) {
+              if (t == 0) load_a1(jp, q, STEPS - 2, chunk + 1);        // step 2 of chunk i - 1 -> chunk i + 1
+              else if (t == 1) load_a1(jp, q, STEPS - 1, chunk + 1);   // step 3 of chunk i - 1 -> chunk i + 1
+              else load_a1(j, q, t - 2, chunk + 2);                    // steps 0, 1 of chunk i -> chunk i + 2
+            }
+          }
+          if (t == 1) store_x1(i, jp, chunk + 1 < c_end);
+          if (t == 2) load_x1(i, chunk + 2);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int i = 0; i < NB; ++i) bcur[i] = bnext[i];
+      }
+      __syncthreads();
+    }
+  }
+  // step 3 of the last chunk
+#pragma unroll
+  for (int i = 0; i < NB; ++i)
+#pragma unroll
+    for (int q = 0; q < QT; ++q)
+      acc[q][i % MTILES] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wr[1][q][STEPS - 1]),
+                                                                   __builtin_bit_cast(bf16x8_t, bcur[i]), acc[q][i % MTILES], 0, 0, 0);
+
+  // register r of acc[2 jb + which][c] <-> weight row `which` of task (tb0 + jb) * 32 + (r/4)*8 + (lane/32)*4 + r%4,
+  // activation row lane % 32 of row tile c
+  if constexpr (SPLIT) {
+#pragma unroll
+    for (int jb = 0; jb < TB; ++jb)
+#pragma unroll
+      for (int c = 0; c < MTILES; ++c) {
+        const int m = row0 + c * 32 + (lane & 31);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int task = (tb0 + jb) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+          if (task < n_tasks && m < m_pad) {
+            float *p = part + (((size_t)by * n_tasks + task) * 2) * m_pad + m;
+            p[0] = acc[2 * jb][c][r];
+            p[m_pad] = acc[2 * jb + 1][c][r];
+          }
+        }
+      }
+  } else {
+    // the epilogue's stores run along the tasks: each 32 x 32 tile is turned in the wave's piece of
+    // LDS (the buffers are free once every wave has left the loop)
+    __syncthreads();
+    float *s_t = (float *)tg_smem + wave * 2 * 32 * 33;
+    NoState st;
+    const int tl = lane & 31, rh = (lane >> 5) * 16;
+#pragma unroll
+    for (int jb = 0; jb < TB; ++jb) {
+#pragma unroll
+      for (int c = 0; c < MTILES; ++c) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int t = (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+          s_t[t * 33 + (lane & 31)] = acc[2 * jb][c][r];
+          s_t[32 * 33 + t * 33 + (lane & 31)] = acc[2 * jb + 1][c][r];
+        }
+        const int task = (tb0 + jb) * 32 + tl;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int m = row0 + c * 32 + rh + i;
+          const float y0 = s_t[tl * 33 + rh + i], y1 = s_t[32 * 33 + tl * 33 + rh + i];
+          if (task < n_tasks && m < m_rows) epi.finish(task, m, rows[m], y0, y1, st);
+        }
+      }
+    }
+  }
+}
+
 // The partial sums of one (task, row) over the k ranges, added in the order of the ranges.  All
 // loads are issued before the first is used: a loop that loads and adds pays a memory round trip
 // per trip, and a projection with few tiles has up to MG_MAX_SPLIT ranges.

@@ -39,12 +39,20 @@ constexpr int MAX_SEQ_LEN = 16384;
 struct Layout {  // byte offsets into the scratch buffer
   size_t state, page_table, plan, lower, upper, ee, full, prefill_rows, prefill_tokens, seq_ids,
       forced, step_flags, out_tokens, out_depth, best, arrivals, row_ssq, sample_hist, sample_arrive, sample_count, hidden, xsplit, xsplit2, mfma_part, sample_q, sample_cand, rand_words, qbuf, attn_out, part, act, lens_u,
-      logits, rope, inv_freq, total;
+      logits, rope, inv_freq, total,
+      tiled, total_tiled;   // the MFMA-ordered copy of the projection weights lies behind everything else (absent on the static area)
 };
 
 struct Derived {
   int V, rmax, max_rows, max_pages, n_pages_total, slice, n_splits, group, esz;
   size_t page_elems, kv_pool_bytes;
+};
+
+// Where the MFMA-ordered copies of the projection matrices lie (element offsets from the start of
+// the tiled region; per layer for the four projections of a layer).
+struct TiledMap {
+  std::vector<size_t> qkv, o, gateup, down;
+  size_t lens_a = 0, lens_head = 0, lm_head = 0, total = 0;
 };
 
 struct Seq {
@@ -64,6 +72,7 @@ struct spark_ctx {
   spark_weights w;
   Derived dv;
   Layout lo;
+  TiledMap tm;
   SchedParams sp;
   hipStream_t stream;
   char *scratch;
@@ -83,6 +92,8 @@ struct spark_ctx {
   int attn_pieces = 0;         // 64-token pieces per attention workgroup (0: by the launch's size)
   int gemv_big_kb = 40;        // vector-kernel launches with more LDS per workgroup run eight waves per workgroup
   int attn_mfma_min_rows = 1;  // passes with at least this many rows run attention on the MFMA units (where the shape allows)
+  bool has_tiled = false;      // the context owns the MFMA-ordered copy of the projection weights
+  bool use_tiled = true;       // "mfma_tiled" = 0 keeps the MFMA projections on the kernel that stages weights through LDS
   bool fuse_norm = true;       // the residual projections' finishing launches prepare the next norm's input (no separate launch)
   bool static_scratch = false; // the scratch area is the library's static device array (spark_init_static)
   int device = 0;
@@ -193,6 +204,29 @@ void derive(const spark_config &c, Derived &d) {
   d.kv_pool_bytes = d.page_elems * d.esz * d.n_pages_total;
 }
 
+// the MFMA kernels load 16-byte vectors of 8 weights; other widths stay on the vector kernel
+bool shape_allows_mfma(const spark_config &c) {
+  return c.dtype == SPARK_DTYPE_BF16 && c.d_model % 8 == 0 && (c.n_q_heads * c.head_dim) % 8 == 0 && c.d_ffn % 8 == 0;
+}
+
+void tiled_map(const spark_config &c, const Derived &d, TiledMap &tm) {
+  tm = TiledMap();
+  if (!shape_allows_mfma(c)) return;
+  const int dm = c.d_model, qw = c.n_q_heads * c.head_dim, F = c.d_ffn;
+  size_t o = 0;
+  auto take = [&](int n_tasks, int n_in) { size_t at = o; o += tg_tiled_elems(n_tasks, n_in); return at; };
+  for (int l = 0; l < c.n_layers; ++l) {
+    tm.qkv.push_back(take((c.n_q_heads + 2 * c.n_kv_heads) * (c.head_dim / 2), dm));
+    tm.o.push_back(take(dm / 2, qw));
+    tm.gateup.push_back(take(F, dm));
+    tm.down.push_back(take(dm / 2, F));
+  }
+  tm.lens_a = take(dm / 2, dm);
+  tm.lens_head = take((d.V + 1) / 2, dm);
+  tm.lm_head = take((d.V + 1) / 2, dm);
+  tm.total = o;
+}
+
 void layout(const spark_config &c, const Derived &d, Layout &l) {
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
@@ -237,6 +271,12 @@ void layout(const spark_config &c, const Derived &d, Layout &l) {
   l.rope = take(sizeof(float2) * (size_t)c.max_seq_len * (c.head_dim / 2));
   l.inv_freq = take(sizeof(float) * (c.head_dim / 2));
   l.total = o;
+  // behind everything else: the MFMA-ordered copy of the bf16 projection weights, for contexts
+  // whose scratch area has room for it
+  TiledMap tm;
+  tiled_map(c, d, tm);
+  l.tiled = o;
+  l.total_tiled = o + align_up(sizeof(bf16_t) * tm.total, 256);
 }
 
 template <typename T> T *at(spark_ctx *c, size_t off) { return (T *)(c->scratch + off); }
@@ -439,9 +479,28 @@ int mfma_occupancy(spark_ctx *c) {
   return found->second;
 }
 
+template <int MTILES, int TB, typename Epi, bool SPLIT>
+int tiled_occupancy(spark_ctx *c) {
+  auto kern = mfma_tiled_k<MTILES, TB, Epi, SPLIT>;
+  const size_t lds = tg_lds_bytes(MTILES);
+  const auto key = std::make_pair((const void *)kern, lds);
+  auto found = c->occ_cache.find(key);
+  if (found == c->occ_cache.end()) {
+    int o = 0;
+    HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, kern, 64 * TG_WAVES, lds));
+    if (o < 1) return fail(c, SPARK_EHIP, "the tiled MFMA kernel for %d rows does not fit on a CU", 32 * MTILES);
+    found = c->occ_cache.emplace(key, o).first;
+  }
+  return found->second;
+}
+
+// tiled: the projection's weights in MFMA operand order (then the kernel that takes them from
+// there runs; its workgroups cover the same tiles of tasks), or nullptr
 template <int MTILES, typename Epi, int WAVES>
 int launch_mfma_shape(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, int n_in, int n_tasks,
-                      bool may_split, bool second_input) {
+                      bool may_split, bool second_input, const bf16_t *tiled) {
+  constexpr int TB = WAVES / 4;   // blocks of 32 tasks per wave of the four-wave tiled kernel
+  constexpr bool STATELESS = std::is_same<typename Epi::State, NoState>::value;
   constexpr int TASKS_PER_BLOCK = WAVES * MG_TASKS_PER_WAVE;
   const int mrows = 32 * MTILES;
   const int z = (m + mrows - 1) / mrows;
@@ -451,13 +510,15 @@ int launch_mfma_shape(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, 
   // quarter of what 32 padded rows would)
   const int m_pad = (int)align_up(m, 8);
   // resident workgroups on the chip: the k range is split until one round of them has work
-  int occ = mfma_occupancy<MTILES, Epi, true, WAVES>(c);
+  int occ = tiled ? tiled_occupancy<MTILES, TB, Epi, true>(c) : mfma_occupancy<MTILES, Epi, true, WAVES>(c);
   if (occ < 0) return occ;
   // k splits: the count that keeps most of the chip busy over whole rounds of resident
   // workgroups, with at least eight chunks each (the pipeline needs a few to fill)
   int split = 1;
   if (may_split) {
-    const int slots = occ * c->n_cu, tiles = bx * z;
+    // (the tiled kernel: one workgroup already keeps a CU's share of the memory system busy, and
+    // two on a CU share that CU's throughput, so rounds are counted in CUs)
+    const int slots = (tiled ? 1 : occ) * c->n_cu, tiles = bx * z;
     const size_t per_split = sizeof(float) * (size_t)n_tasks * 2 * m_pad;
     // (few tiles: shorter k ranges are worth the pipeline fill they cost)
     const int min_chunks = tiles < 32 ? 4 : 8;
@@ -479,9 +540,16 @@ int launch_mfma_shape(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, 
   const int tiles_padded = xcd_groups ? (bx * split + 7) / 8 * 8 : bx * split;
   dim3 grid(tiles_padded * z);
   const size_t lds = mg_lds_bytes(MTILES, WAVES);
-  if (split > 1 || EpiHasRowSum<Epi>::value) {   // (an epilogue that sums over a row runs in the finishing launch only)
-    mfma_rows_k<MTILES, Epi, true, WAVES><<<grid, 64 * WAVES, lds, c->stream>>>(
-        epi, rows, m, xs, xst, n_in, n_tasks, cps, part, m_pad, bx, split, z, xcd_groups);
+  // (an epilogue that sums over a row runs in the finishing launch only; so does, on tiled
+  // weights, one with a running state: the tiled kernel hands every lane 64 tasks of one row,
+  // the finishing launch reduces the states of a row before they reach memory)
+  if (split > 1 || EpiHasRowSum<Epi>::value || (tiled && !STATELESS)) {
+    if (tiled)
+      mfma_tiled_k<MTILES, TB, Epi, true><<<grid, 64 * TG_WAVES, tg_lds_bytes(MTILES), c->stream>>>(
+          epi, tiled, rows, m, xs, xst, n_in, n_tasks, cps, part, m_pad, bx, split, z, xcd_groups);
+    else
+      mfma_rows_k<MTILES, Epi, true, WAVES><<<grid, 64 * WAVES, lds, c->stream>>>(
+          epi, rows, m, xs, xst, n_in, n_tasks, cps, part, m_pad, bx, split, z, xcd_groups);
     if constexpr (std::is_same<typename Epi::State, NoState>::value || EpiHasRowSum<Epi>::value) {
       // epilogues without a running state: stores coalesced over tasks
       const dim3 fgrid((n_tasks + 31) / 32, (m_pad + 31) / 32);
@@ -493,10 +561,20 @@ int launch_mfma_shape(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, 
       mfma_finish_k<Epi><<<(total + 255) / 256, 256, 0, c->stream>>>(epi, rows, m, n_tasks, split, part, m_pad, tpt);
     }
   } else if constexpr (!EpiHasRowSum<Epi>::value) {
-    occ = mfma_occupancy<MTILES, Epi, false, WAVES>(c);
-    if (occ < 0) return occ;
-    mfma_rows_k<MTILES, Epi, false, WAVES><<<grid, 64 * WAVES, lds, c->stream>>>(
-        epi, rows, m, xs, xst, n_in, n_tasks, cps, part, m_pad, bx, split, z, xcd_groups);
+    bool done = false;
+    if constexpr (STATELESS) {
+      if (tiled) {
+        mfma_tiled_k<MTILES, TB, Epi, false><<<grid, 64 * TG_WAVES, tg_lds_bytes(MTILES), c->stream>>>(
+            epi, tiled, rows, m, xs, xst, n_in, n_tasks, cps, part, m_pad, bx, split, z, xcd_groups);
+        done = true;
+      }
+    }
+    if (!done) {
+      occ = mfma_occupancy<MTILES, Epi, false, WAVES>(c);
+      if (occ < 0) return occ;
+      mfma_rows_k<MTILES, Epi, false, WAVES><<<grid, 64 * WAVES, lds, c->stream>>>(
+          epi, rows, m, xs, xst, n_in, n_tasks, cps, part, m_pad, bx, split, z, xcd_groups);
+    }
   }
   HIP_TRY(c, hipGetLastError());
   return SPARK_OK;
@@ -504,7 +582,7 @@ int launch_mfma_shape(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, 
 
 template <int MTILES, typename Epi>
 int launch_mfma_tiles(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, int n_in, int n_tasks,
-                      bool may_split, bool second_input = false) {
+                      bool may_split, const bf16_t *tiled, bool second_input = false) {
   if (n_in % 8) return fail(c, SPARK_EINVAL, "MFMA path needs an input width that is a multiple of 8, not %d", n_in);
   // matrices of few rows and a short k (q/k/v, o, the lens translator): four waves per workgroup,
   // so that the launch has enough workgroups without cutting k into ranges too short to stream
@@ -512,23 +590,72 @@ int launch_mfma_tiles(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, 
   // gate/up, with its many tiles, are better off with eight)
   const int tiles8 = ((n_tasks + MG_TASKS_PER_BLOCK - 1) / MG_TASKS_PER_BLOCK) * ((m + 32 * MTILES - 1) / (32 * MTILES));
   if (tiles8 < c->mfma_small_tiles && n_in <= 8192)
-    return launch_mfma_shape<MTILES, Epi, 4>(c, epi, rows, m, n_in, n_tasks, may_split, second_input);
-  return launch_mfma_shape<MTILES, Epi, 8>(c, epi, rows, m, n_in, n_tasks, may_split, second_input);
+    return launch_mfma_shape<MTILES, Epi, 4>(c, epi, rows, m, n_in, n_tasks, may_split, second_input, tiled);
+  return launch_mfma_shape<MTILES, Epi, 8>(c, epi, rows, m, n_in, n_tasks, may_split, second_input, tiled);
 }
 
 // y = W x for m rows whose hi/lo split sits in the xhi/xlo buffers
 template <typename Epi>
 int launch_mfma(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, int n_in, int n_tasks,
-                bool may_split, int kclass, bool second_input = false) {
+                bool may_split, int kclass, const bf16_t *tiled, bool second_input = false) {
   int rc = prof_begin(c, kclass);
   if (rc) return rc;
-  if (m <= 32) rc = launch_mfma_tiles<1>(c, epi, rows, m, n_in, n_tasks, may_split, second_input);
-  else rc = launch_mfma_tiles<2>(c, epi, rows, m, n_in, n_tasks, may_split, second_input);   // tiles of 64 rows
+  if (m <= 32) rc = launch_mfma_tiles<1>(c, epi, rows, m, n_in, n_tasks, may_split, tiled, second_input);
+  else rc = launch_mfma_tiles<2>(c, epi, rows, m, n_in, n_tasks, may_split, tiled, second_input);   // tiles of 64 rows
   if (rc) return rc;
   return prof_end(c, kclass);
 }
 
 template <typename WT> int launch_attention(spark_ctx *c, const RowDesc *rows, int m, int layer, bool split_out);
+
+// The copy of one projection's weights in MFMA operand order, or nullptr when the context has none
+// (or is told not to use it).
+const bf16_t *tiled_at(spark_ctx *c, size_t elem_off) {
+  return c->has_tiled && c->use_tiled ? at<bf16_t>(c, c->lo.tiled) + elem_off : nullptr;
+}
+
+template <typename Epi>
+int tile_one(spark_ctx *c, const Epi &epi, int n_tasks, int n_in, size_t elem_off) {
+  const int n_chunks = (n_in + MG_KC - 1) / MG_KC, n_tb = (n_tasks + 31) / 32;
+  tile_weights_k<<<dim3(n_chunks, n_tb * 2), 256, 0, c->stream>>>(epi, n_tasks, n_in, n_chunks,
+                                                               at<bf16_t>(c, c->lo.tiled) + elem_off);
+  HIP_TRY(c, hipGetLastError());
+  return SPARK_OK;
+}
+
+// Writes the MFMA-ordered copies once, with the epilogues' own task -> weight rows mapping (only
+// the weight pointers and widths of an epilogue matter here).
+int build_tiled(spark_ctx *c) {
+  typedef bf16_t WT;
+  const spark_config &g = c->cfg;
+  const int d = g.d_model, hd = g.head_dim, nq = g.n_q_heads, nkv = g.n_kv_heads, F = g.d_ffn, V = c->dv.V;
+  const size_t qw = (size_t)nq * hd, kvw = (size_t)nkv * hd;
+  int rc;
+  for (int l = 0; l < g.n_layers; ++l) {
+    EpiQKV<WT> eq;
+    eq.wq = (const WT *)c->w.wq + (size_t)l * qw * d;
+    eq.wk = (const WT *)c->w.wk + (size_t)l * kvw * d;
+    eq.wv = (const WT *)c->w.wv + (size_t)l * kvw * d;
+    eq.d = d; eq.nq = nq; eq.nkv = nkv; eq.hd = hd; eq.layer = l;
+    eq.qbuf = nullptr; eq.rope = nullptr; eq.kv = kv_view(c);
+    if ((rc = tile_one(c, eq, (nq + 2 * nkv) * (hd / 2), d, c->tm.qkv[l]))) return rc;
+    EpiResidual<WT> eo{(const WT *)c->w.wo + (size_t)l * d * qw, (int)qw, d, nullptr, d};
+    if ((rc = tile_one(c, eo, d / 2, (int)qw, c->tm.o[l]))) return rc;
+    EpiSwiGLUSplit<WT> eg{(const WT *)c->w.wg + (size_t)l * F * d, (const WT *)c->w.wu + (size_t)l * F * d, d, F,
+                          SplitOut{nullptr, 0, 0, 0}};
+    if ((rc = tile_one(c, eg, F, d, c->tm.gateup[l]))) return rc;
+    EpiResidual<WT> ed{(const WT *)c->w.wd + (size_t)l * d * F, F, d, nullptr, d};
+    if ((rc = tile_one(c, ed, d / 2, F, c->tm.down[l]))) return rc;
+  }
+  EpiLensAffine<WT> ea{(const WT *)c->w.lens_a, nullptr, nullptr, nullptr, d};
+  if ((rc = tile_one(c, ea, d / 2, d, c->tm.lens_a))) return rc;
+  EpiVocab<WT> el{(const WT *)c->w.lens_head, d, V, nullptr, nullptr};
+  if ((rc = tile_one(c, el, (V + 1) / 2, d, c->tm.lens_head))) return rc;
+  EpiVocab<WT> ev{(const WT *)c->w.lm_head, d, V, nullptr, nullptr};
+  if ((rc = tile_one(c, ev, (V + 1) / 2, d, c->tm.lm_head))) return rc;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return SPARK_OK;
+}
 
 // layers [l0, l1) on m >= 16 rows, bf16 weights
 int run_layers_mfma(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
@@ -556,7 +683,7 @@ int run_layers_mfma(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
     eq.rope = at<float2>(c, c->lo.rope);
     eq.kv = kv_view(c);
     if (qkv_scaled) eq.scale = RowScale{ssq_attn, 1.0f / (float)d, g.rms_eps};
-    if ((rc = launch_mfma(c, eq, rows, m, d, (nq + 2 * nkv) * (hd / 2), true, SPARK_KC_QKV))) return rc;
+    if ((rc = launch_mfma(c, eq, rows, m, d, (nq + 2 * nkv) * (hd / 2), true, SPARK_KC_QKV, tiled_at(c, c->tm.qkv[l])))) return rc;
 
     // attention leaves its output split for the MFMA kernel; so does the SwiGLU epilogue below
     if ((rc = launch_attention<WT>(c, rows, m, l, true))) return rc;
@@ -566,22 +693,22 @@ int run_layers_mfma(spark_ctx *c, int l0, int l1, const RowDesc *rows, int m) {
     if (fuse) {
       EpiResidualNorm<WT> eo{(const WT *)c->w.wo + (size_t)l * d * qw, (int)qw, d, hidden, d,
                              c->w.mlp_norm + (size_t)l * d, split_target(c, d), ssq_mlp};
-      if ((rc = launch_mfma(c, eo, rows, m, (int)qw, d / 2, true, SPARK_KC_OPROJ))) return rc;
+      if ((rc = launch_mfma(c, eo, rows, m, (int)qw, d / 2, true, SPARK_KC_OPROJ, tiled_at(c, c->tm.o[l])))) return rc;
       eg.scale = RowScale{ssq_mlp, 1.0f / (float)d, g.rms_eps};
     } else {
       EpiResidual<WT> eo{(const WT *)c->w.wo + (size_t)l * d * qw, (int)qw, d, hidden, d};
-      if ((rc = launch_mfma(c, eo, rows, m, (int)qw, d / 2, true, SPARK_KC_OPROJ))) return rc;
+      if ((rc = launch_mfma(c, eo, rows, m, (int)qw, d / 2, true, SPARK_KC_OPROJ, tiled_at(c, c->tm.o[l])))) return rc;
       if ((rc = launch_prep(c, rows, m, hidden, d, 1, c->w.mlp_norm + (size_t)l * d, d))) return rc;
     }
-    if ((rc = launch_mfma(c, eg, rows, m, d, F, true, SPARK_KC_GATEUP))) return rc;
+    if ((rc = launch_mfma(c, eg, rows, m, d, F, true, SPARK_KC_GATEUP, tiled_at(c, c->tm.gateup[l])))) return rc;
 
     if (fuse && l + 1 < l1) {
       EpiResidualNorm<WT> ed{(const WT *)c->w.wd + (size_t)l * d * F, F, d, hidden, d,
                              c->w.attn_norm + (size_t)(l + 1) * d, split_target(c, d), ssq_attn};
-      if ((rc = launch_mfma(c, ed, rows, m, F, d / 2, true, SPARK_KC_DOWN, true))) return rc;
+      if ((rc = launch_mfma(c, ed, rows, m, F, d / 2, true, SPARK_KC_DOWN, tiled_at(c, c->tm.down[l]), true))) return rc;
     } else {
       EpiResidual<WT> ed{(const WT *)c->w.wd + (size_t)l * d * F, F, d, hidden, d};
-      if ((rc = launch_mfma(c, ed, rows, m, F, d / 2, true, SPARK_KC_DOWN, true))) return rc;
+      if ((rc = launch_mfma(c, ed, rows, m, F, d / 2, true, SPARK_KC_DOWN, tiled_at(c, c->tm.down[l]), true))) return rc;
     }
   }
   return SPARK_OK;
@@ -637,13 +764,13 @@ template <typename WT> int run_lens_head(spark_ctx *c, const RowDesc *rows, int 
   if (std::is_same<WT, bf16_t>::value && m >= c->mfma_min_rows && c->use_mfma) {
     if ((rc = launch_prep(c, rows, m, hidden, d, 1, nullptr, d))) return rc;
     EpiLensAffine<bf16_t> ea{(const bf16_t *)c->w.lens_a, c->w.lens_b, hidden, u, d};
-    if ((rc = launch_mfma(c, ea, rows, m, d, d / 2, true, SPARK_KC_LENS))) return rc;
+    if ((rc = launch_mfma(c, ea, rows, m, d, d / 2, true, SPARK_KC_LENS, tiled_at(c, c->tm.lens_a)))) return rc;
     if ((rc = launch_prep(c, rows, m, u, d, 0, c->w.lens_norm, d))) return rc;
     EpiVocab<bf16_t> ev{(const bf16_t *)c->w.lens_head, d, V, at<float>(c, c->lo.logits),
                         at<unsigned long long>(c, c->lo.best)};
     rc = prof_begin(c, SPARK_KC_LENS);
     if (rc) return rc;
-    if ((rc = launch_mfma_tiles<1>(c, ev, rows, m, d, (V + 1) / 2, true))) return rc;
+    if ((rc = launch_mfma_tiles<1>(c, ev, rows, m, d, (V + 1) / 2, true, tiled_at(c, c->tm.lens_head)))) return rc;
     return prof_end(c, SPARK_KC_LENS);
   }
   ProPlain ph{hidden, d, 1};
@@ -666,7 +793,7 @@ template <typename WT> int run_final_head(spark_ctx *c, const RowDesc *rows, int
                         at<unsigned long long>(c, c->lo.best)};
     rc = prof_begin(c, SPARK_KC_HEAD);
     if (rc) return rc;
-    if ((rc = launch_mfma_tiles<1>(c, ev, rows, m, d, (V + 1) / 2, true))) return rc;
+    if ((rc = launch_mfma_tiles<1>(c, ev, rows, m, d, (V + 1) / 2, true, tiled_at(c, c->tm.lm_head)))) return rc;
     return prof_end(c, SPARK_KC_HEAD);
   }
   ProNorm pn{at<float>(c, c->lo.hidden), c->w.final_norm, g.rms_eps, d, 1};
@@ -915,7 +1042,7 @@ int spark_workspace_bytes(const spark_config *cfg, size_t *kv_pool_bytes, size_t
   derive(*cfg, d);
   layout(*cfg, d, l);
   if (kv_pool_bytes) *kv_pool_bytes = d.kv_pool_bytes;
-  if (scratch_bytes) *scratch_bytes = l.total;
+  if (scratch_bytes) *scratch_bytes = l.total_tiled;
   return SPARK_OK;
 }
 
@@ -972,6 +1099,10 @@ int init_context(const spark_config *cfg, const spark_weights *weights, void *kv
   // the MFMA kernels load 16-byte vectors of 8 weights; other widths stay on the vector kernel
   c->mfma_ok = cfg->d_model % 8 == 0 && (cfg->n_q_heads * cfg->head_dim) % 8 == 0 && cfg->d_ffn % 8 == 0;
   c->use_mfma = c->mfma_ok;
+  // a scratch area of the full size holds the MFMA-ordered copy of the projection weights (the
+  // static area never does)
+  tiled_map(*cfg, c->dv, c->tm);
+  c->has_tiled = !static_scratch && c->tm.total > 0 && scratch_bytes >= c->lo.total_tiled;
   // Prompt rows per pass: on the MFMA path the widest projection (gate/up) is cut into tiles of 256
   // weight-row pairs x 64 prompt rows; the row count is chosen so that one round of tiles about
   // fills the chip, which needs no k split and no second kernel for that projection.
@@ -1007,6 +1138,7 @@ int init_context(const spark_config *cfg, const spark_weights *weights, void *kv
                                                           cfg->max_seq_len, at<float2>(c, c->lo.rope));
   if (hipGetLastError() != hipSuccess || hipStreamSynchronize(c->stream) != hipSuccess)
     return bail(SPARK_EHIP);
+  if (c->has_tiled && build_tiled(c) != SPARK_OK) return bail(SPARK_EHIP);
   *out = c;
   return SPARK_OK;
 }
@@ -1083,6 +1215,7 @@ int spark_tune(spark_ctx *c, const char *name, int32_t value) {
   else if (k == "attn_pieces") c->attn_pieces = std::max(0, std::min(8, (int)value));
   else if (k == "attn_mfma_min_rows") c->attn_mfma_min_rows = std::max(1, (int)value);
   else if (k == "gemv_big_kb") c->gemv_big_kb = std::max(1, (int)value);
+  else if (k == "mfma_tiled") c->use_tiled = value != 0;
   else if (k == "fuse_norm") c->fuse_norm = value != 0;
   else return fail(c, SPARK_EINVAL, "unknown tuning name '%s'", name);
   return SPARK_OK;

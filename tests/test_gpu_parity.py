@@ -249,10 +249,14 @@ def test_text_schedule_with_long_flushes_on_a_bf16_model(sb):
     sp.close()
 
 
-def test_batched_decode_on_the_mfma_path(sb):
+@pytest.mark.parametrize("tiled", [1, 0])
+def test_batched_decode_on_the_mfma_path(sb, tiled):
     """24 bf16 sequences with mixed schedules in every step: 24 rows through layers 1..e, the
     early-exit rows through the layer-specific head, the full-depth rows with their pending rows
-    (up to 4 each) through layers e+1..L and the final head -- all as MFMA contractions"""
+    (up to 4 each) through layers e+1..L and the final head -- all as MFMA contractions, once with
+    the weights taken from the copy in MFMA operand order (the default of a context with a
+    full-size scratch area) and once with the kernel that stages the caller's rows through LDS
+    (what a context on the static scratch area runs)"""
     shape = wl.TINY.shape.replace(name="bf16-batch", dtype=wl.DTYPE_BF16, n_layers=4, d_model=512,
                                   n_q_heads=8, n_kv_heads=4, head_dim=64, d_ffn=1536 + 72,
                                   vocab_text=1500, vocab_speech=701)
@@ -264,8 +268,9 @@ def test_batched_decode_on_the_mfma_path(sb):
     prompts = [wl.make_prompt(shape, int(n), seed=40 + i) for i, n in enumerate(lens)]
     offsets = [i % 6 for i in range(B)]
     sp = sb.Spark(shape, sched, weights, max_batch=B, max_seq_len=160, kv_page_tokens=16)
+    sp.tune("mfma_tiled", tiled)
     a = compare_run(sp, shape, sched, weights, prompts, offsets, 14, check_kv_every=7,
-                    label="batch24 bf16")
+                    label=f"batch24 bf16 tiled={tiled}")
     assert len(np.unique(a["depths"], axis=1)) > 1
     sp.close()
 

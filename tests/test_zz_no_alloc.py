@@ -2,7 +2,12 @@
 array inside the library), against spark_init with a caller's scratch buffer: the same prompt and
 teacher-forced stream through both contexts give bit-identical tokens, depths and logits, on two
 calls in a row, the second with a smaller configuration (a smaller model and batch, so the second
-context finds the first one's leftovers in the shared array); then the refusals."""
+context finds the first one's leftovers in the shared array); then the refusals.
+
+A context on a caller's buffer of the full size also holds a copy of the projection weights in MFMA
+operand order, which the static area has no room for; the comparison switches that copy off
+("mfma_tiled" = 0), so that both contexts run the same kernels with the same k ranges and the
+results can be compared bit by bit."""
 import numpy as np
 import pytest
 
@@ -20,6 +25,7 @@ def run_both(sb, shape, sched, weights, n_seq, n_prompt, n_steps, seed):
     for static in (True, False):
         sp = sb.Spark(shape, sched, weights, max_batch=n_seq, max_seq_len=n_prompt + 3 * n_seq + n_steps + 8,
                       kv_page_tokens=16, static_scratch=static)
+        sp.tune("mfma_tiled", 0)
         sids = [sp.seq_open(o) for o in offsets]
         for s_, p_ in zip(sids, prompts):
             sp.prefill(s_, p_)
