@@ -120,8 +120,12 @@ typedef struct spark_ctx spark_ctx;
  * pool (every sequence at max_seq_len) and the scratch area (activations, schedule state, logits).
  * What has to be kept follows from Sec. IV-B.3: the KV cache of all L layers for every position,
  * and the hidden states h^(e) of the early-exited positions until the next full-depth step; on
- * memory management itself the paper is silent.  cfg [host]; the two sizes are written to
- * kv_pool_bytes / scratch_bytes [host] (either may be NULL).
+ * memory management itself the paper is silent.  For bf16 models whose widths are multiples of 8
+ * the scratch size also has room for a second copy of the projection and head matrices, laid out
+ * in the order the matrix units consume them, which the context writes when it is created and
+ * which the projections of five and more rows read instead of the caller's tensors (as many bytes
+ * again as those matrices).  cfg [host]; the two sizes are written to kv_pool_bytes /
+ * scratch_bytes [host] (either may be NULL).
  * Returns SPARK_EINVAL for a configuration the library refuses. */
 int spark_workspace_bytes(const spark_config *cfg, size_t *kv_pool_bytes, size_t *scratch_bytes);
 
@@ -138,7 +142,8 @@ int spark_schedule_preview(const spark_config *cfg, int32_t cycle_offset, int32_
  * kv_pool and scratch [device] must be at least the sizes reported above and 256-byte aligned and
  * stay the caller's (they must outlive the context; their contents need not be cleared);
  * hip_stream is a hipStream_t (NULL = the default stream) on which every kernel of this context is
- * launched.  The weights struct is copied; the tensors are not.  *out [host] receives the context,
+ * launched.  The weights struct is copied; the tensors are not, and they must keep their contents
+ * while the context lives (the copy mentioned above is taken from them here, once).  *out [host] receives the context,
  * to be released with spark_destroy.  SPARK_EINVAL: refused configuration or a NULL tensor;
  * SPARK_ENOMEM: a buffer is NULL, too small or misaligned; SPARK_EHIP: a runtime call failed. */
 int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_pool,
@@ -149,8 +154,9 @@ int spark_init(const spark_config *cfg, const spark_weights *weights, void *kv_p
  * serving loops, harnesses that forbid hipMalloc): the scratch area is a static device array of
  * SPARK_STATIC_SCRATCH_BYTES inside the library instead of a caller's buffer, and the staging
  * buffers are ordinary host arrays; the call makes no hipMalloc / hipHostMalloc / hipFree.  The
- * caller still passes the weights and the KV pool.  Configurations whose
- * spark_workspace_bytes scratch size exceeds SPARK_STATIC_SCRATCH_BYTES are refused
+ * caller still passes the weights and the KV pool.  Such a context keeps no second copy of the
+ * weights (its projections of five and more rows read the caller's tensors); configurations whose
+ * scratch need without that copy exceeds SPARK_STATIC_SCRATCH_BYTES are refused
  * (SPARK_ENOMEM, with a message on stderr).  Each GPU has one such array: at most one context per
  * device may live on it at a time (a second spark_init_static on the same device returns
  * SPARK_ESTATE until the first is destroyed), the array keeps the previous context's contents

@@ -92,6 +92,7 @@ struct spark_ctx {
   int attn_pieces = 0;         // 64-token pieces per attention workgroup (0: by the launch's size)
   int gemv_big_kb = 40;        // vector-kernel launches with more LDS per workgroup run eight waves per workgroup
   int attn_mfma_min_rows = 1;  // passes with at least this many rows run attention on the MFMA units (where the shape allows)
+  int mfma_small_max_k = 32768;  // ... and an input width of at most this
   bool has_tiled = false;      // the context owns the MFMA-ordered copy of the projection weights
   bool use_tiled = true;       // "mfma_tiled" = 0 keeps the MFMA projections on the kernel that stages weights through LDS
   bool fuse_norm = true;       // the residual projections' finishing launches prepare the next norm's input (no separate launch)
@@ -589,7 +590,7 @@ int launch_mfma_tiles(spark_ctx *c, const Epi &epi, const RowDesc *rows, int m, 
   // (measured at 32 rows: q/k/v 23.5 -> 20.8 us, o 20.2 -> 16.0 us; down, with its long k, and
   // gate/up, with its many tiles, are better off with eight)
   const int tiles8 = ((n_tasks + MG_TASKS_PER_BLOCK - 1) / MG_TASKS_PER_BLOCK) * ((m + 32 * MTILES - 1) / (32 * MTILES));
-  if (tiles8 < c->mfma_small_tiles && n_in <= 8192)
+  if (tiles8 < c->mfma_small_tiles && n_in <= c->mfma_small_max_k)
     return launch_mfma_shape<MTILES, Epi, 4>(c, epi, rows, m, n_in, n_tasks, may_split, second_input, tiled);
   return launch_mfma_shape<MTILES, Epi, 8>(c, epi, rows, m, n_in, n_tasks, may_split, second_input, tiled);
 }
@@ -1215,6 +1216,8 @@ int spark_tune(spark_ctx *c, const char *name, int32_t value) {
   else if (k == "attn_pieces") c->attn_pieces = std::max(0, std::min(8, (int)value));
   else if (k == "attn_mfma_min_rows") c->attn_mfma_min_rows = std::max(1, (int)value);
   else if (k == "gemv_big_kb") c->gemv_big_kb = std::max(1, (int)value);
+  else if (k == "prefill_rows") c->prefill_chunk = std::max(32, std::min(PREFILL_CHUNK, (int)value / 32 * 32));
+  else if (k == "mfma_small_max_k") c->mfma_small_max_k = std::max(8, (int)value);
   else if (k == "mfma_tiled") c->use_tiled = value != 0;
   else if (k == "fuse_norm") c->fuse_norm = value != 0;
   else return fail(c, SPARK_EINVAL, "unknown tuning name '%s'", name);
