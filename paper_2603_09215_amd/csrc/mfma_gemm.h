@@ -12,6 +12,10 @@
 // supplies 8 consecutive k of row (l % 32), k-block (l / 32); of the 16 results in a lane,
 // register r belongs to weight row (r/4)*8 + (l/32)*4 + r%4 and activation row l % 32.
 //
+// Two kernels run the contraction: mfma_tiled_k (further down) takes its weights from a copy in
+// MFMA operand order that the context wrote when it was created, and is the one a context with
+// such a copy runs; mfma_rows_k, described next, takes them from the caller's row-major tensors.
+//
 // A workgroup of eight waves owns 256 "tasks" (the same pairs of weight rows the vector kernel
 // uses, so the epilogues are shared: rotary pairs, gate/up pairs, adjacent rows), 32 per wave, and
 // all rows of one tile of 32 or 64 activation rows; more rows are further tiles (grid.z), whose

@@ -275,6 +275,26 @@ def test_batched_decode_on_the_mfma_path(sb, tiled):
     sp.close()
 
 
+@pytest.mark.parametrize("rows,small_max_k", [(32, 32768), (96, 32768), (96, 8), (160, 8)])
+def test_prompt_pass_row_counts_and_tile_shapes(sb, rows, small_max_k):
+    """a 150-token prompt in passes of 32, 96 or 160 rows (one 32-row tile; a 64-row and a 32-row
+    tile; ragged last tiles), with the 128-task tiles that matrices of few tiles get by default and
+    with 256-task tiles forced for every projection (64 tasks, four A tiles, per wave); the decoding
+    steps behind the prompt and cache entries across it are compared with the oracle"""
+    shape = wl.TINY.shape.replace(name="bf16-prompt", dtype=wl.DTYPE_BF16, n_layers=4, d_model=512,
+                                  n_q_heads=4, n_kv_heads=2, head_dim=128, d_ffn=1024 + 40,
+                                  vocab_text=900, vocab_speech=301)
+    sched = wl.TINY.schedule
+    say(f"case prompt passes of {rows} rows, small tiles up to k = {small_max_k}")
+    weights = wl.make_weights(shape, seed=8, gain_std=0.1)
+    sp = sb.Spark(shape, sched, weights, max_batch=1, max_seq_len=256, kv_page_tokens=64)
+    sp.tune("prefill_rows", rows)
+    sp.tune("mfma_small_max_k", small_max_k)
+    compare_run(sp, shape, sched, weights, [wl.make_prompt(shape, 150, seed=61)], [2], 8, check_kv_every=1,
+                label=f"prompt150 rows={rows} small_k={small_max_k}", kv_all_positions=True)
+    sp.close()
+
+
 @pytest.mark.parametrize("B", [3, 4, 5, 7, 8])
 def test_row_counts_around_the_mfma_threshold(sb, B):
     """bf16 sequences with the same cycle offset: every pass of the lower layers has exactly B rows
