@@ -286,7 +286,7 @@ int spark_profile_read(spark_ctx *ctx, int64_t *n_launches, double *total_ms, do
 
 /* Measurement support: what the memory system delivers to the simplest possible reader, to be
  * quoted next to the published peak.  Reads buf [device, 16-byte aligned, bytes a multiple of 16]
- * `reps` times with a plain grid-stride kernel of 16-byte loads (nontemporal != 0: with the
+ * `reps` times with a plain kernel of 16-byte loads (every wave eight consecutive KiB per trip) (nontemporal != 0: with the
  * non-temporal hint the weight-streaming kernels use) on the context's stream, bracketed by HIP
  * events after one untimed pass, and writes the rate in GB/s (10^9 bytes) to *gbps [host] and the
  * XOR of all 32-bit words of buf to *checksum [host, may be NULL].  buf should be larger than the
@@ -299,7 +299,11 @@ int spark_measure_read(spark_ctx *ctx, const void *buf, size_t bytes, int32_t re
  *   "mfma" (0: every row count stays on the vector kernels), "mfma_min_rows" (rows from which the
  *   projections run on the MFMA units), "mfma_small_tiles", "mfma_xcd_max_split",
  *   "attn_pieces" (64-token pieces per attention workgroup, 0 = by the size of the launch, at most
- *   8), "attn_mfma_min_rows", "gemv_big_kb".  SPARK_EINVAL for an unknown name. */
+ *   8), "attn_mfma_min_rows", "gemv_big_kb", "mfma_tiled" (0: the MFMA projections stage the
+ *   caller's weight rows through LDS instead of reading the context's copy in operand order),
+ *   "mfma_small_max_k", "fuse_norm" (0: every RMSNorm of the batched path is its own launch),
+ *   "prefill_rows" (prompt rows per pass, a multiple of 32, at most 256).
+ * SPARK_EINVAL for an unknown name. */
 int spark_tune(spark_ctx *ctx, const char *name, int32_t value);
 
 #ifdef __cplusplus
