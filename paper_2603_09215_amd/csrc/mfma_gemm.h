@@ -536,7 +536,12 @@ mfma_tiled_k(Epi epi, const bf16_t *__restrict__ tiled, const RowDesc *__restric
     x_dst[i] = m * MG_ROWPAD + kv;
   }
   u32x4_t xr[XV][MG_PARTS];
-  u32x4_t wr[2][QT][STEPS];   // ring of two chunks of weights: slot = chunk parity
+  // chunks of weights in registers, slot = chunk % RING: three for 64-row tiles, whose one wave per
+  // SIMD has nothing else to cover a late load with (prompt pass 29.6 -> 28.6 ms, passes of 33..64
+  // rows in a batch of 32: 5.23 -> 5.17 ms per step); 32-row tiles keep two workgroups on a CU with
+  // a ring of two, and lose with three (4.44 -> 4.61 ms per step)
+  constexpr int RING = MTILES == 2 ? 3 : 2;
+  u32x4_t wr[RING][QT][STEPS];
   const u32x4_t zero4 = {0u, 0u, 0u, 0u};
 
   // all loads are unconditional (chunks past the range are clamped to its last one) so that the
@@ -570,7 +575,7 @@ mfma_tiled_k(Epi epi, const bf16_t *__restrict__ tiled, const RowDesc *__restric
   for (int n = 0; n < NX; ++n) load_x1(n, c_begin + 1);
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
+  for (int j = 0; j < RING; ++j)
 #pragma unroll
     for (int s = 0; s < STEPS; ++s)
 #pragma unroll
@@ -581,21 +586,22 @@ mfma_tiled_k(Epi epi, const bf16_t *__restrict__ tiled, const RowDesc *__restric
   for (int i = 0; i < NB; ++i) bcur[i] = zero4;
 
   // Region k (one barrier each) works on chunk i = c_begin + k, whose weights sit in ring slot
-  // k % 2 and whose activations in LDS buffer k % 2:
+  // k % RING and whose activations in LDS buffer k % 2:
   //   step 3 of chunk i - 1 (its B operands were fetched before the last barrier; zeros in region 0),
   //   steps 0..2 of chunk i, while the B operands of the step after each are fetched,
   //   the staging of chunk i + 1 into the other buffer, the loads of the activations of chunk i + 2,
   //   and the reloads of the weight registers whose step has just been finished with (chunks
-  //   i + 1 and i + 2).
+  //   i + RING - 1 and i + RING).
   // Every read of a buffer lies in the region of its chunk, every write to it in the regions next
   // to that one, so the one barrier per region separates them; the MFMAs run on across it.
-  // An odd number of chunks gets one more region on zeros.
-  const int n_regions = (c_end - c_begin + 1) & ~1;
-  for (int k0 = 0; k0 < n_regions; k0 += 2) {
+  // A number of chunks that is not a multiple of RING is filled up with regions on zeros.
+  const int n_regions = (c_end - c_begin + RING - 1) / RING * RING;
+  int buf = 0;   // LDS buffer of the region's chunk
+  for (int k0 = 0; k0 < n_regions; k0 += RING) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < RING; ++j) {
       const int chunk = c_begin + k0 + j;
-      const int jp = j ^ 1;
+      const int jp = (j + RING - 1) % RING;
 #pragma unroll
       for (int t = 0; t < STEPS; ++t) {
         // t = 0: step 3 of the previous chunk; t = 1..3: steps 0..2 of this one
@@ -607,17 +613,17 @@ mfma_tiled_k(Epi epi, const bf16_t *__restrict__ tiled, const RowDesc *__restric
           for (int q = 0; q < QT; ++q)
             acc[q][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wr[slot][q][s]),
                                                                 __builtin_bit_cast(bf16x8_t, bcur[i]), acc[q][c], 0, 0, 0);
-          bnext[i] = load_b1(i, j, t);   // operands of step t of this chunk (t = 0 follows the last barrier)
+          bnext[i] = load_b1(i, buf, t);   // operands of step t of this chunk (t = 0 follows the last barrier)
 #pragma unroll
           for (int e = 0; e < PER; ++e) {
             const int q = i * PER + e;
             if (q < QT) {
-              if (t == 0) load_a1(jp, q, STEPS - 2, chunk + 1);        // step 2 of chunk i - 1 -> chunk i + 1
-              else if (t == 1) load_a1(jp, q, STEPS - 1, chunk + 1);   // step 3 of chunk i - 1 -> chunk i + 1
-              else load_a1(j, q, t - 2, chunk + 2);                    // steps 0, 1 of chunk i -> chunk i + 2
+              if (t == 0) load_a1(jp, q, STEPS - 2, chunk + RING - 1);        // step 2 of chunk i - 1 -> chunk i - 1 + RING
+              else if (t == 1) load_a1(jp, q, STEPS - 1, chunk + RING - 1);   // step 3 of chunk i - 1 likewise
+              else load_a1(j, q, t - 2, chunk + RING);                 // steps 0, 1 of chunk i -> chunk i + RING
             }
           }
-          if (t == 1) store_x1(i, jp, chunk + 1 < c_end);
+          if (t == 1) store_x1(i, buf ^ 1, chunk + 1 < c_end);
           if (t == 2) load_x1(i, chunk + 2);
           __builtin_amdgcn_sched_barrier(0);
         }
@@ -625,6 +631,7 @@ mfma_tiled_k(Epi epi, const bf16_t *__restrict__ tiled, const RowDesc *__restric
         for (int i = 0; i < NB; ++i) bcur[i] = bnext[i];
       }
       __syncthreads();
+      buf ^= 1;
     }
   }
   // step 3 of the last chunk
@@ -632,7 +639,7 @@ mfma_tiled_k(Epi epi, const bf16_t *__restrict__ tiled, const RowDesc *__restric
   for (int i = 0; i < NB; ++i)
 #pragma unroll
     for (int q = 0; q < QT; ++q)
-      acc[q][i % MTILES] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wr[1][q][STEPS - 1]),
+      acc[q][i % MTILES] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wr[RING - 1][q][STEPS - 1]),
                                                                    __builtin_bit_cast(bf16x8_t, bcur[i]), acc[q][i % MTILES], 0, 0, 0);
 
   // register r of acc[2 jb + which][c] <-> weight row `which` of task (tb0 + jb) * 32 + (r/4)*8 + (lane/32)*4 + r%4,
